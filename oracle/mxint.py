@@ -1,0 +1,124 @@
+"""MXINT block format: oracle quantizer, dequantizer and canonical byte layouts.
+
+TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
+
+Sec. 2.2 describes MXINT as a block of fixed-point mantissas sharing one
+exponent; Sec. 4.1 fixes the block at 16 elements ([1,16] for activations,
+[16,1] for W_q, A_k, B_k, i.e. always along the contraction axis) and the
+mantissa widths (4 for W_q, 8 for X, A_k, B_k).  The paper gives no formula,
+so the reading taken here is:
+
+  amax  = max |v_i| over the block
+  e     = floor(log2 amax), clamped to [-127, 127];  e = -127 when amax == 0
+  ebyte = e + 127                                    (one byte per block)
+  scale = 2^(e - (b - 2))          1 sign bit, 1 integer bit, b-2 fraction bits
+  c_i   = clamp(round_half_even(v_i / scale), -(2^(b-1) - 1), +(2^(b-1) - 1))
+  dq    : v^_i = c_i * scale
+
+Rounding that reaches 2^(b-1) saturates; the exponent is never bumped.
+All arithmetic is fp64; every step above is exact in fp64 for fp32 inputs.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+BLOCK = 16
+EXP_BIAS = 127
+E_MIN = -127
+E_MAX = 127
+
+
+def code_limit(bits: int) -> int:
+    """Largest code magnitude of a b-bit symmetric mantissa."""
+    return (1 << (bits - 1)) - 1
+
+
+def _to_blocks(v: np.ndarray, axis: int) -> np.ndarray:
+    """Move `axis` last and split it into blocks of 16: shape (..., n/16, 16)."""
+    v = np.moveaxis(v, axis, -1)
+    n = v.shape[-1]
+    if n % BLOCK != 0:
+        raise ValueError(f"length {n} along the block axis is not a multiple of {BLOCK}")
+    return v.reshape(v.shape[:-1] + (n // BLOCK, BLOCK))
+
+
+def block_exponent(amax: np.ndarray) -> np.ndarray:
+    """Unbiased shared exponent e = floor(log2 amax) clamped to [-127,127]; -127 for 0."""
+    amax = np.asarray(amax, dtype=np.float64)
+    _, ex = np.frexp(amax)               # amax = m * 2^ex with m in [0.5, 1)
+    e = np.where(amax > 0.0, ex - 1, E_MIN)
+    return np.clip(e, E_MIN, E_MAX).astype(np.int64)
+
+
+def mx_quantize(v, bits: int, axis: int = -1):
+    """Quantize `v` to MXINT with `bits`-bit mantissas in blocks of 16 along `axis`.
+
+    Returns (codes, exps): codes is int8 with the shape of `v`; exps is uint8
+    (biased by 127) with `axis` shrunk by 16.
+    """
+    v = np.asarray(v, dtype=np.float64)
+    if not np.all(np.isfinite(v)):
+        raise ValueError("MXINT quantizer requires finite inputs")
+    blk = _to_blocks(v, axis)
+    amax = np.max(np.abs(blk), axis=-1)
+    e = block_exponent(amax)
+    shift = e - (bits - 2)                                   # log2(scale)
+    q = np.rint(np.ldexp(blk, (-shift)[..., None]))          # v / scale, exact, then RNE
+    lim = code_limit(bits)
+    codes = np.clip(q, -lim, lim).astype(np.int8)
+    codes = codes.reshape(codes.shape[:-2] + (codes.shape[-2] * BLOCK,))
+    codes = np.moveaxis(codes, -1, axis)
+    exps = np.moveaxis((e + EXP_BIAS).astype(np.uint8), -1, axis)
+    return np.ascontiguousarray(codes), np.ascontiguousarray(exps)
+
+
+def mx_dequantize(codes, exps, bits: int, axis: int = -1) -> np.ndarray:
+    """v^ = code * 2^(e - (bits-2)) in fp64 (exact)."""
+    c = _to_blocks(np.asarray(codes).astype(np.float64), axis)
+    e = np.moveaxis(np.asarray(exps).astype(np.int64), axis, -1) - EXP_BIAS
+    out = np.ldexp(c, (e - (bits - 2))[..., None])
+    out = out.reshape(out.shape[:-2] + (out.shape[-2] * BLOCK,))
+    return np.ascontiguousarray(np.moveaxis(out, -1, axis))
+
+
+# --------------------------------------------------------------------------
+# canonical byte layouts (contraction axis contiguous for every tensor)
+# --------------------------------------------------------------------------
+
+def pack_int4(codes: np.ndarray) -> np.ndarray:
+    """[..., n] int8 codes in [-7,7] -> [..., n/2] uint8.
+
+    Element 2i sits in the low nibble, element 2i+1 in the high nibble, both as
+    two's-complement nibbles.
+    """
+    c = np.asarray(codes).astype(np.int16)
+    if c.shape[-1] % 2:
+        raise ValueError("need an even number of 4-bit codes")
+    lo = c[..., 0::2] & 0xF
+    hi = c[..., 1::2] & 0xF
+    return (lo | (hi << 4)).astype(np.uint8)
+
+
+def unpack_int4(packed: np.ndarray) -> np.ndarray:
+    """Inverse of pack_int4: [..., n/2] uint8 -> [..., n] int8."""
+    p = np.asarray(packed).astype(np.int16)
+    lo = p & 0xF
+    hi = (p >> 4) & 0xF
+    out = np.empty(p.shape[:-1] + (p.shape[-1] * 2,), dtype=np.int16)
+    out[..., 0::2] = lo
+    out[..., 1::2] = hi
+    out = np.where(out >= 8, out - 16, out)
+    return out.astype(np.int8)
+
+
+def average_bits(mant_bits: int, exp_bits: int, block: int = BLOCK) -> float:
+    """Average bits per element of one MXINT tensor (App. D): one shared
+    exponent spread over `block` mantissas."""
+    return mant_bits + exp_bits / block
+
+
+def lqer_average_weight_bits(m: int, n: int, k: int, w_bits: int, lr_bits: int,
+                             w_exp_bits: int, lr_exp_bits: int) -> float:
+    """Average stored bits per element of W for W_q plus A_k, B_k (App. D)."""
+    total = m * n * average_bits(w_bits, w_exp_bits) + (m + n) * k * average_bits(lr_bits, lr_exp_bits)
+    return total / (m * n)
