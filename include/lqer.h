@@ -1,0 +1,159 @@
+/*
+ * lqer.h - C ABI of the MI355X (gfx950) LQER W4A8 linear layer.
+ *
+ * The layer computes (arXiv 2402.02446, Eq. 3 and Eq. 6)
+ *
+ *        Y = X_q W_q + (X_q A_k) B_k
+ *
+ * with X_q = MXINT8 activations quantized on the fly, W_q = MXINT4 weights and
+ * A_k, B_k = MXINT8 rank-k factors of the (activation-scaled) quantization
+ * error S (W - W_q) (Eq. 1-2, Eq. 4-5, App. A).  Every MXINT tensor uses blocks
+ * of 16 along the contraction axis and one biased-127 exponent byte per block
+ * (Sec. 2.2, Sec. 4.1).
+ *
+ * Conventions
+ *   M = tokens (the paper's t), K = in-features (m), N = out-features (n),
+ *   k = rank, kp = k rounded up to a multiple of 16.  W is K x N (Y = X W).
+ *   "_dev" pointers are device memory, "_host" pointers are host memory.
+ *   Every call returns an lqer_status; none throws or aborts.  Argument errors
+ *   are reported before anything is launched.  Launches are asynchronous on
+ *   the given HIP stream (a hipStream_t passed as void*; NULL = default stream).
+ *
+ * MXINT element format (b-bit mantissa, block of 16, exponent byte eb):
+ *   e = eb - 127 = floor(log2 max|v|) clamped to [-127,127] (-127 for an all-zero block),
+ *   value = code * 2^(e - (b-2)),  code = round-half-even(v / 2^(e-(b-2))) saturated
+ *   to +-(2^(b-1) - 1).  Inputs must be finite.
+ *
+ * Canonical packed layouts (contraction axis contiguous everywhere):
+ *   Wc[N][K/2]   two 4-bit two's-complement codes per byte, element 2i in the low nibble
+ *   We[N][K/16]  exponent bytes
+ *   Ac[kp][K] int8, Ae[kp][K/16];   Bc[N][kp] int8, Be[N][kp/16]
+ *   Xc[M][K]  int8, Xe[M][K/16]
+ */
+#ifndef LQER_H
+#define LQER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LQER_OK = 0,
+    LQER_ERR_NULL = 1,            /* a required pointer is NULL */
+    LQER_ERR_SHAPE = 2,           /* K % 16 != 0, k > min(K,N), ld < cols, negative size ... */
+    LQER_ERR_UNSUPPORTED = 3,     /* mantissa width not in {4,8}, exponent width != 8, block != 16 */
+    LQER_ERR_SINGULAR_SCALE = 4,  /* a calibrated channel magnitude is <= 0 or not finite (Sec. 3.2 needs S^-1) */
+    LQER_ERR_WORKSPACE = 5,       /* workspace NULL, misaligned or too small */
+    LQER_ERR_HIP = 6,             /* a HIP runtime call or launch failed */
+    LQER_ERR_NO_CONVERGENCE = 7,  /* the truncated SVD did not reach its tolerance */
+    LQER_ERR_VALUE = 8            /* packed bytes hold a value the format excludes (nibble -8, exponent byte out of range) */
+} lqer_status;
+
+/* Number-format description for lqer_build_factors.  Only {4, 8, 8, 16} is supported. */
+typedef struct {
+    int w_bits;     /* mantissa bits of W_q               (4) */
+    int h_bits;     /* mantissa bits of X, A_k, B_k       (8) */
+    int exp_bits;   /* shared exponent bits               (8) */
+    int block;      /* block size                         (16) */
+} lqer_config;
+
+/* Opaque layer: owns the device copies of W_q, A_k, B_k (in an internal tiled layout). */
+typedef struct lqer_layer lqer_layer;
+
+/* Short English name of a status code; never NULL. */
+const char* lqer_status_string(int status);
+
+/*
+ * MX block quantizer (Sec. 2.2; block shape [1,16] of Sec. 4.1): blocks of 16 along
+ * the contiguous axis of a row-major fp32 matrix.
+ *   x_dev      [rows][ld] fp32, device; only the first `cols` of each row are read
+ *   cols       multiple of 16;  ld >= cols
+ *   elem_bits  8 (codes_dev = int8 [rows][cols]) or 4 (codes_dev = uint8 [rows][cols/2], canonical nibbles)
+ *   exp_bits   8
+ *   exps_dev   uint8 [rows][cols/16]
+ * rows == 0 is a no-op.  Caller owns all buffers.
+ */
+int lqer_quantize_mx(const float* x_dev, int64_t rows, int64_t cols, int64_t ld,
+                     int elem_bits, int exp_bits,
+                     void* codes_dev, uint8_t* exps_dev, void* hip_stream);
+
+/*
+ * Offline construction (Sec. 3.1 Eq. 1-2; Sec. 3.2 Eq. 4-5; App. A Eq. 7-8).
+ *   W_host      [K][N] fp32 row-major, host
+ *   calib_host  [n_samples][rows_per_sample][K] fp32, host (ignored when mode == 0; may be NULL then)
+ *   k           rank, 0 <= k <= min(K, N)
+ *   mode        0 = LQER (S = I), 1 = L2QER (S from calib_host)
+ *   cfg         NULL = {4, 8, 8, 16}
+ *   out         receives an owning handle; release with lqer_layer_free
+ * Computes W_q = q(W), E_q = W - W_q, S, the k leading singular triplets of S E_q,
+ * A_k = S^-1 U_k, B_k = Sigma_k V_k^T, quantizes A_k and B_k to MXINT8 and uploads
+ * everything to the current device.  Synchronous.
+ */
+int lqer_build_factors(const float* W_host, int64_t K, int64_t N,
+                       const float* calib_host, int64_t n_samples, int64_t rows_per_sample,
+                       int k, int mode, const lqer_config* cfg, lqer_layer** out);
+
+/*
+ * Layer from / to canonical packed bytes (host pointers, layouts above).
+ * Import copies; the caller keeps its buffers.  Ac/Ae/Bc/Be may be NULL when k == 0.
+ * Wc nibbles must not be -8; We bytes must be <= 247; Ae, Be bytes must be <= 254
+ * (LQER_ERR_VALUE otherwise).  Export writes exactly the bytes that were imported
+ * (or that lqer_build_factors produced); any output pointer may be NULL to skip it.
+ */
+int lqer_layer_import(int64_t K, int64_t N, int k,
+                      const uint8_t* Wc, const uint8_t* We,
+                      const int8_t* Ac, const uint8_t* Ae,
+                      const int8_t* Bc, const uint8_t* Be, lqer_layer** out);
+int lqer_layer_export(const lqer_layer* layer, uint8_t* Wc, uint8_t* We,
+                      int8_t* Ac, uint8_t* Ae, int8_t* Bc, uint8_t* Be);
+int lqer_layer_dims(const lqer_layer* layer, int64_t* K, int64_t* N, int* k, int* kp);
+int lqer_layer_free(lqer_layer* layer);
+
+/*
+ * Forward pass (Eq. 3 / Eq. 6).
+ *   X_dev  [M][ldx] fp32 device (ldx >= K);  Y_dev [M][ldy] fp32 device (ldy >= N)
+ *   workspace_dev  device scratch of at least lqer_linear_workspace_bytes(layer, M)
+ *                  bytes, 256-byte aligned, caller-owned; its contents are scratch.
+ * Steps, all in this library's kernels: quantize X to MXINT8 (Sec. 4.1), T = X_q A_k,
+ * Y = X_q W_q + T B_k accumulated in fp32 in one pass over Y.  M == 0 is a no-op.
+ * Calls on different streams need distinct workspaces.  The library allocates nothing here.
+ * lqer_linear_forward_q takes activations that are already quantized
+ * (Xc int8 [M][K], Xe uint8 [M][K/16], canonical, device).
+ */
+size_t lqer_linear_workspace_bytes(const lqer_layer* layer, int64_t M);
+int lqer_linear_forward(const lqer_layer* layer, const float* X_dev, int64_t M, int64_t ldx,
+                        float* Y_dev, int64_t ldy,
+                        void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+int lqer_linear_forward_q(const lqer_layer* layer, const int8_t* Xc_dev, const uint8_t* Xe_dev,
+                          int64_t M, float* Y_dev, int64_t ldy,
+                          void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Launch control for measurement and tuning (Sec. 2.1 distinguishes the memory-bound
+ * and the compute-bound regime; the dispatcher picks by M, this overrides it).
+ *   path    0 = automatic, 1 = streaming kernel (small M), 2 = tiled MFMA kernel (large M)
+ *   variant 0 = automatic, otherwise a tile-shape index of the chosen path
+ *   stages  bit 0 = quantize + T, bit 1 = main product; 0 = both
+ * Same contract as lqer_linear_forward otherwise.  Running stage bit 1 alone reuses
+ * what an earlier call with bit 0 left in the same workspace.
+ */
+typedef struct {
+    int path;
+    int variant;
+    int stages;
+} lqer_launch_opts;
+int lqer_linear_forward_ex(const lqer_layer* layer, const float* X_dev, int64_t M, int64_t ldx,
+                           float* Y_dev, int64_t ldy,
+                           void* workspace_dev, size_t workspace_bytes, void* hip_stream,
+                           const lqer_launch_opts* opts);
+
+/* Which path the dispatcher picks for this layer at M tokens: 1 = streaming, 2 = tiled MFMA. */
+int lqer_linear_path(const lqer_layer* layer, int64_t M);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LQER_H */

@@ -1,0 +1,226 @@
+// Stage 1 of the forward pass: quantize activations to MXINT8 (Sec. 4.1, block [1,16]) and
+// compute the low-rank projection T = X_q A_k (Eq. 3 / Eq. 6, first small matmul).
+//
+// One workgroup owns 16 token rows and a K slice; its four wavefronts take the slice's 256-wide
+// K tiles in turn.  Lane (t = lane % 16, q = lane / 16) owns the blocks q + 4p (p = 0..3) of a
+// tile for token t: it finds the block maximum, quantizes, and keeps the dequantized values
+// code * 2^(e-6) - exact in bf16 - both for the store to the bf16 activation matrix the main
+// kernels read and as its MFMA operand.  A_k's int8 codes are scaled to bf16 the same way, so
+// every product entering the fp32 MFMA accumulator is exact.
+//
+// S == 1: T is final; it is split into two bf16 terms T_hi + T_lo and stored behind the
+//         activations of the same row, where the main kernel treats it as 2*kp more K columns.
+// S  > 1: each K slice stores an fp32 partial T; the main kernel adds the slices in a fixed order.
+#include "lqer_internal.h"
+#include "mx_device.h"
+
+namespace lqer {
+
+struct PrepArgs {
+    const float* X; int64_t ldx;
+    const int8_t* Xc; const uint8_t* Xe;
+    int64_t M, K;
+    int64_t KT;            // K tiles
+    int tiles_per_slice;
+    int kp, kp16;
+    int groups_per_wg;     // rank groups one workgroup computes (kp16, or 1 when split over grid.z)
+    const uint8_t* At;
+    uint16_t* Xh; int64_t ldxh;
+    int64_t tail_cols;     // columns behind K_pad in Xh (T_hi | T_lo | zero padding)
+    float* Tpart;
+};
+
+__device__ __forceinline__ void split_bf16(float t, uint16_t& hi, uint16_t& lo) {
+    const uint32_t hb = f32_bits(t) & 0xFFFF0000u;
+    hi = (uint16_t)(hb >> 16);
+    const float rem = t - f32_from_bits(hb);              // exact
+    lo = (uint16_t)(f32_bits(rem) >> 16);
+}
+
+template <bool FROM_CODES, bool FINAL, int MAXG>
+__global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
+    __shared__ float red[4][MAXG][64][4];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int t = lane & 15, q = lane >> 4;
+    const int64_t row = (int64_t)blockIdx.x * 16 + t;
+    const bool row_ok = row < a.M;
+    const int slice = blockIdx.y;
+    const int g0 = blockIdx.z * a.groups_per_wg;
+    const bool store_x = (blockIdx.z == 0);
+    const int64_t nblk = a.K / 16;
+
+    f32x4 acc[MAXG];
+#pragma unroll
+    for (int g = 0; g < MAXG; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int64_t tile_begin = (int64_t)slice * a.tiles_per_slice;
+    int64_t tile_end = tile_begin + a.tiles_per_slice;
+    if (tile_end > a.KT) tile_end = a.KT;
+
+    for (int64_t tile = tile_begin + wave; tile < tile_end; tile += 4) {
+        Frag xf[4][2];                                       // [p][half]
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int64_t kb = tile * 16 + q + 4 * p;        // block index along K
+            const bool ok = row_ok && kb < nblk;
+            float scale = 0.f;
+            float r[16];
+            if (FROM_CODES) {
+                u32x4 cw = u32x4{0, 0, 0, 0};
+                uint32_t eb = 0;
+                if (ok) {
+                    cw = *reinterpret_cast<const u32x4*>(a.Xc + row * a.K + kb * 16);
+                    eb = a.Xe[row * nblk + kb];
+                }
+                scale = h_scale(eb);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = cw[i];
+                    r[4 * i + 0] = (float)(int)(int8_t)(w & 0xFF);
+                    r[4 * i + 1] = (float)(int)(int8_t)((w >> 8) & 0xFF);
+                    r[4 * i + 2] = (float)(int)(int8_t)((w >> 16) & 0xFF);
+                    r[4 * i + 3] = (float)(int)(int8_t)(w >> 24);
+                }
+            } else {
+                float4 v[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    v[i] = ok ? *reinterpret_cast<const float4*>(a.X + row * a.ldx + kb * 16 + 4 * i)
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
+                float m = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(v[i].x), __builtin_fabsf(v[i].y)),
+                                                           __builtin_fmaxf(__builtin_fabsf(v[i].z), __builtin_fabsf(v[i].w))));
+                }
+                const uint32_t eb = (f32_bits(m) >> 23) & 0xFFu;
+                const int sh = 6 - ((int)eb - 127);
+                scale = h_scale(eb);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float in[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        float c = __builtin_rintf(__builtin_amdgcn_ldexpf(in[j], sh));
+                        r[4 * i + j] = __builtin_fminf(__builtin_fmaxf(c, -127.0f), 127.0f);
+                    }
+                }
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    xf[p][h].u[i] = pack_bf16_exact(r[8 * h + 2 * i] * scale, r[8 * h + 2 * i + 1] * scale);
+            if (store_x && row_ok) {
+                uint16_t* dst = a.Xh + row * a.ldxh + (tile * 16 + q + 4 * p) * 16;
+                *reinterpret_cast<u32x4*>(dst) = xf[p][0].u;
+                *reinterpret_cast<u32x4*>(dst + 8) = xf[p][1].u;
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < MAXG; ++g) {
+            if (g < a.groups_per_wg) {
+                const uint8_t* rec = a.At + ((int64_t)(g0 + g) * a.KT + tile) * kARecordBytes;
+                const uint32_t ew = *reinterpret_cast<const uint32_t*>(rec + 4096 + lane * 4);
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const u32x4 cw = *reinterpret_cast<const u32x4*>(rec + p * 1024 + lane * 16);
+                    const float sc = h_scale((ew >> (8 * p)) & 0xFFu);
+                    Frag af[2];
+                    int8x16_to_frags(cw, sc, af[0], af[1]);
+                    acc[g] = mfma16(af[0].v, xf[p][0].v, acc[g]);
+                    acc[g] = mfma16(af[1].v, xf[p][1].v, acc[g]);
+                }
+            }
+        }
+    }
+
+    if (a.kp == 0) {
+        // no low-rank branch: only the zero padding behind K_pad (none) remains
+        return;
+    }
+
+    // add the four wavefronts' partial T in a fixed order
+#pragma unroll
+    for (int g = 0; g < MAXG; ++g)
+        *reinterpret_cast<f32x4*>(&red[wave][g][lane][0]) = acc[g];
+    __syncthreads();
+    for (int item = threadIdx.x; item < a.groups_per_wg * 64; item += 256) {
+        const int g = item >> 6, l = item & 63;
+        f32x4 s = *reinterpret_cast<const f32x4*>(&red[0][g][l][0]);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const f32x4 o = *reinterpret_cast<const f32x4*>(&red[w][g][l][0]);
+            s[0] += o[0]; s[1] += o[1]; s[2] += o[2]; s[3] += o[3];
+        }
+        const int64_t orow = (int64_t)blockIdx.x * 16 + (l & 15);
+        const int r0 = (g0 + g) * 16 + 4 * (l >> 4);          // first of this lane's 4 ranks
+        if (orow < a.M) {
+            if (FINAL) {
+                uint16_t hi[4], lo[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) split_bf16(s[j], hi[j], lo[j]);
+                uint16_t* base = a.Xh + orow * a.ldxh + a.KT * kTileK;
+                *reinterpret_cast<u32x2*>(base + r0) =
+                    u32x2{(uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)};
+                *reinterpret_cast<u32x2*>(base + a.kp + r0) =
+                    u32x2{(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
+            } else {
+                *reinterpret_cast<f32x4*>(a.Tpart + ((int64_t)slice * a.M + orow) * a.kp + r0) = s;
+            }
+        }
+    }
+    // zero the padding behind T_hi | T_lo so the main kernel can read whole 64-column chunks
+    if (FINAL && blockIdx.z == 0) {
+        const int pad = (int)(a.tail_cols - 2 * a.kp);
+        for (int item = threadIdx.x; item < 16 * pad; item += 256) {
+            const int64_t orow = (int64_t)blockIdx.x * 16 + item / pad;
+            if (orow < a.M) a.Xh[orow * a.ldxh + a.KT * kTileK + 2 * a.kp + item % pad] = 0;
+        }
+    }
+}
+
+int prep_slices(const Layer& L, int64_t M, int path) {
+    if (path != 1) return 1;
+    // streaming path: M <= 64 rows means at most 4 row groups; spread K over workgroups so the
+    // projection does not serialise on a handful of compute units.
+    int64_t s = L.KT / 4;
+    if (s < 1) s = 1;
+    if (s > 8) s = 8;
+    return (int)s;
+}
+
+hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t* Xc, const uint8_t* Xe,
+                       int64_t M, const Workspace& ws, hipStream_t s) {
+    if (M == 0) return hipSuccess;
+    PrepArgs a;
+    a.X = X; a.ldx = ldx; a.Xc = Xc; a.Xe = Xe;
+    a.M = M; a.K = L.K; a.KT = L.KT;
+    a.tiles_per_slice = (int)((L.KT + ws.S - 1) / ws.S);
+    a.kp = L.kp; a.kp16 = L.kp16;
+    const bool split_groups = ws.S > 1 && L.kp16 > 1;
+    a.groups_per_wg = split_groups ? 1 : L.kp16;
+    a.At = L.At; a.Xh = ws.Xh; a.ldxh = ws.ldxh;
+    a.tail_cols = ws.ldxh - L.KT * kTileK;
+    a.Tpart = ws.Tpart;
+    dim3 grid((unsigned)((M + 15) / 16), (unsigned)ws.S, (unsigned)(split_groups ? L.kp16 : 1));
+    dim3 block(256);
+    const bool from_codes = (Xc != nullptr);
+    const bool fin = (ws.S == 1);
+#define LQER_PREP(FC, FN, MG) hipLaunchKernelGGL((prep_kernel<FC, FN, MG>), grid, block, 0, s, a)
+    if (a.groups_per_wg <= 1) {
+        if (from_codes) { if (fin) LQER_PREP(true, true, 1); else LQER_PREP(true, false, 1); }
+        else            { if (fin) LQER_PREP(false, true, 1); else LQER_PREP(false, false, 1); }
+    } else if (a.groups_per_wg <= 4) {
+        if (from_codes) { if (fin) LQER_PREP(true, true, 4); else LQER_PREP(true, false, 4); }
+        else            { if (fin) LQER_PREP(false, true, 4); else LQER_PREP(false, false, 4); }
+    } else {
+        return hipErrorInvalidValue;      // kp > 64 is rejected at import
+    }
+#undef LQER_PREP
+    return hipGetLastError();
+}
+
+}  // namespace lqer

@@ -1,0 +1,429 @@
+// Host side of liblqer: the C ABI, layer import/export (canonical bytes <-> tiled device layout),
+// workspace planning and the dispatch between the streaming and the tiled main kernel.
+#include <atomic>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "lqer_internal.h"
+#include "host_parallel.h"
+
+struct lqer_layer {
+    lqer::Layer L;
+};
+
+namespace lqer {
+
+static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+// ---- W code words -------------------------------------------------------------------------------
+// 8 signed codes (-7..7) -> one 32-bit word, layout documented in lqer_internal.h.
+static uint32_t encode_word(const int8_t* c) {
+    uint32_t w = 0;
+    for (int i = 0; i < 4; ++i) {
+        const int lo = c[i], hi = c[4 + i];
+        const uint32_t mag_lo = (uint32_t)(lo < 0 ? -lo : lo), s_lo = lo < 0;
+        const uint32_t mag_hi = (uint32_t)(hi < 0 ? -hi : hi), s_hi = hi < 0;
+        w |= (mag_lo | (s_lo << 7) | (mag_hi << 4)) << (8 * i);
+        w |= (s_hi << 3) << (8 * ((i + 1) & 3));
+    }
+    return w;
+}
+
+static void decode_word(uint32_t w, int8_t* c) {
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t b = (w >> (8 * i)) & 0xFF;
+        const uint32_t bn = (w >> (8 * ((i + 1) & 3))) & 0xFF;
+        const int mag_lo = b & 7, s_lo = (b >> 7) & 1;
+        const int mag_hi = (b >> 4) & 7, s_hi = (bn >> 3) & 1;
+        c[i] = (int8_t)(s_lo ? -mag_lo : mag_lo);
+        c[4 + i] = (int8_t)(s_hi ? -mag_hi : mag_hi);
+    }
+}
+
+static inline int nibble_to_code(uint32_t v) { return v < 8 ? (int)v : (int)v - 16; }
+
+// canonical Wc/We -> tiled records.  Returns LQER_ERR_VALUE on a -8 nibble or an exponent byte > 247.
+static int tile_weights(const Layer& L, const uint8_t* Wc, const uint8_t* We, std::vector<uint8_t>& out) {
+    const int64_t nblk = L.K / 16;
+    out.assign((size_t)(L.N16 * L.KT) * kWRecordBytes, 0);
+    for (int64_t n = 0; n < L.N; ++n)
+        for (int64_t kb = 0; kb < nblk; ++kb)
+            if (We[n * nblk + kb] > kMaxWExpByte) return LQER_ERR_VALUE;
+    std::atomic<int> bad{0};
+    parallel_for(L.N16, [&](int64_t g) {
+        for (int64_t tile = 0; tile < L.KT; ++tile) {
+            uint8_t* rec = out.data() + (size_t)(g * L.KT + tile) * kWRecordBytes;
+            for (int lane = 0; lane < 64; ++lane) {
+                const int c = lane & 15, q = lane >> 4;
+                const int64_t n = g * 16 + c;
+                uint32_t ew = 0;
+                for (int p = 0; p < 4; ++p) {
+                    const int64_t kb = tile * 16 + q + 4 * p;
+                    int8_t codes[16] = {0};
+                    uint32_t eb = 0;
+                    if (n < L.N && kb < nblk) {
+                        const uint8_t* src = Wc + n * (L.K / 2) + kb * 8;
+                        for (int i = 0; i < 8; ++i) {
+                            const uint32_t lo = src[i] & 0xF, hi = src[i] >> 4;
+                            if (lo == 8 || hi == 8) bad.store(1, std::memory_order_relaxed);
+                            codes[2 * i] = (int8_t)nibble_to_code(lo);
+                            codes[2 * i + 1] = (int8_t)nibble_to_code(hi);
+                        }
+                        eb = We[n * nblk + kb];
+                    }
+                    const uint32_t w0 = encode_word(codes), w1 = encode_word(codes + 8);
+                    uint8_t* dst = rec + (p >> 1) * 1024 + lane * 16 + (p & 1) * 8;
+                    memcpy(dst, &w0, 4);
+                    memcpy(dst + 4, &w1, 4);
+                    ew |= eb << (8 * p);
+                }
+                memcpy(rec + 2048 + lane * 4, &ew, 4);
+            }
+        }
+    });
+    return bad.load() ? LQER_ERR_VALUE : LQER_OK;
+}
+
+static void untile_weights(const Layer& L, const std::vector<uint8_t>& in, uint8_t* Wc, uint8_t* We) {
+    const int64_t nblk = L.K / 16;
+    parallel_for(L.N16, [&](int64_t g) {
+        for (int64_t tile = 0; tile < L.KT; ++tile) {
+            const uint8_t* rec = in.data() + (size_t)(g * L.KT + tile) * kWRecordBytes;
+            for (int lane = 0; lane < 64; ++lane) {
+                const int c = lane & 15, q = lane >> 4;
+                const int64_t n = g * 16 + c;
+                if (n >= L.N) continue;
+                uint32_t ew;
+                memcpy(&ew, rec + 2048 + lane * 4, 4);
+                for (int p = 0; p < 4; ++p) {
+                    const int64_t kb = tile * 16 + q + 4 * p;
+                    if (kb >= nblk) continue;
+                    uint32_t w0, w1;
+                    const uint8_t* src = rec + (p >> 1) * 1024 + lane * 16 + (p & 1) * 8;
+                    memcpy(&w0, src, 4);
+                    memcpy(&w1, src + 4, 4);
+                    int8_t codes[16];
+                    decode_word(w0, codes);
+                    decode_word(w1, codes + 8);
+                    if (Wc) {
+                        uint8_t* dst = Wc + n * (L.K / 2) + kb * 8;
+                        for (int i = 0; i < 8; ++i)
+                            dst[i] = (uint8_t)((codes[2 * i] & 0xF) | ((codes[2 * i + 1] & 0xF) << 4));
+                    }
+                    if (We) We[n * nblk + kb] = (uint8_t)((ew >> (8 * p)) & 0xFF);
+                }
+            }
+        }
+    });
+}
+
+static int tile_a(const Layer& L, const int8_t* Ac, const uint8_t* Ae, std::vector<uint8_t>& out) {
+    const int64_t nblk = L.K / 16;
+    out.assign((size_t)(L.kp16 * L.KT) * kARecordBytes, 0);
+    for (int64_t i = 0; i < (int64_t)L.kp * nblk; ++i)
+        if (Ae[i] == 255) return LQER_ERR_VALUE;
+    for (int g = 0; g < L.kp16; ++g)
+        for (int64_t tile = 0; tile < L.KT; ++tile) {
+            uint8_t* rec = out.data() + (size_t)(g * L.KT + tile) * kARecordBytes;
+            for (int lane = 0; lane < 64; ++lane) {
+                const int c = lane & 15, q = lane >> 4;
+                const int64_t r = g * 16 + c;
+                uint32_t ew = 0;
+                for (int p = 0; p < 4; ++p) {
+                    const int64_t kb = tile * 16 + q + 4 * p;
+                    if (kb >= nblk) continue;
+                    memcpy(rec + p * 1024 + lane * 16, Ac + r * L.K + kb * 16, 16);
+                    ew |= (uint32_t)Ae[r * nblk + kb] << (8 * p);
+                }
+                memcpy(rec + 4096 + lane * 4, &ew, 4);
+            }
+        }
+    return LQER_OK;
+}
+
+static void untile_a(const Layer& L, const std::vector<uint8_t>& in, int8_t* Ac, uint8_t* Ae) {
+    const int64_t nblk = L.K / 16;
+    for (int g = 0; g < L.kp16; ++g)
+        for (int64_t tile = 0; tile < L.KT; ++tile) {
+            const uint8_t* rec = in.data() + (size_t)(g * L.KT + tile) * kARecordBytes;
+            for (int lane = 0; lane < 64; ++lane) {
+                const int c = lane & 15, q = lane >> 4;
+                const int64_t r = g * 16 + c;
+                uint32_t ew;
+                memcpy(&ew, rec + 4096 + lane * 4, 4);
+                for (int p = 0; p < 4; ++p) {
+                    const int64_t kb = tile * 16 + q + 4 * p;
+                    if (kb >= nblk) continue;
+                    if (Ac) memcpy(Ac + r * L.K + kb * 16, rec + p * 1024 + lane * 16, 16);
+                    if (Ae) Ae[r * nblk + kb] = (uint8_t)((ew >> (8 * p)) & 0xFF);
+                }
+            }
+        }
+}
+
+static int tile_b(const Layer& L, const int8_t* Bc, const uint8_t* Be, std::vector<uint8_t>& out) {
+    out.assign((size_t)(L.N16 * L.kp16) * kBRecordBytes, 0);
+    for (int64_t i = 0; i < L.N * L.kp16; ++i)
+        if (Be[i] == 255) return LQER_ERR_VALUE;
+    for (int64_t g = 0; g < L.N16; ++g)
+        for (int rb = 0; rb < L.kp16; ++rb) {
+            uint8_t* rec = out.data() + (size_t)(g * L.kp16 + rb) * kBRecordBytes;
+            for (int c = 0; c < 16; ++c) {
+                const int64_t n = g * 16 + c;
+                if (n >= L.N) continue;
+                memcpy(rec + c * 16, Bc + n * L.kp + rb * 16, 16);
+                rec[256 + c] = Be[n * L.kp16 + rb];
+            }
+        }
+    return LQER_OK;
+}
+
+static void untile_b(const Layer& L, const std::vector<uint8_t>& in, int8_t* Bc, uint8_t* Be) {
+    for (int64_t g = 0; g < L.N16; ++g)
+        for (int rb = 0; rb < L.kp16; ++rb) {
+            const uint8_t* rec = in.data() + (size_t)(g * L.kp16 + rb) * kBRecordBytes;
+            for (int c = 0; c < 16; ++c) {
+                const int64_t n = g * 16 + c;
+                if (n >= L.N) continue;
+                if (Bc) memcpy(Bc + n * L.kp + rb * 16, rec + c * 16, 16);
+                if (Be) Be[n * L.kp16 + rb] = rec[256 + c];
+            }
+        }
+}
+
+static void free_device(Layer& L) {
+    if (L.Wt) (void)hipFree(L.Wt);
+    if (L.At) (void)hipFree(L.At);
+    if (L.Bt) (void)hipFree(L.Bt);
+    L.Wt = L.At = L.Bt = nullptr;
+}
+
+static int upload(const std::vector<uint8_t>& host, uint8_t** dev) {
+    *dev = nullptr;
+    if (host.empty()) return LQER_OK;
+    if (hipMalloc((void**)dev, host.size()) != hipSuccess) return LQER_ERR_HIP;
+    if (hipMemcpy(*dev, host.data(), host.size(), hipMemcpyHostToDevice) != hipSuccess) return LQER_ERR_HIP;
+    return LQER_OK;
+}
+
+static int download(const uint8_t* dev, size_t bytes, std::vector<uint8_t>& host) {
+    host.resize(bytes);
+    if (bytes == 0) return LQER_OK;
+    if (hipMemcpy(host.data(), dev, bytes, hipMemcpyDeviceToHost) != hipSuccess) return LQER_ERR_HIP;
+    return LQER_OK;
+}
+
+static Workspace plan_workspace(const Layer& L, int64_t M, int path, void* base) {
+    Workspace ws;
+    ws.ldxh = L.KT * kTileK + round_up(2 * (int64_t)L.kp, 64);
+    ws.S = prep_slices(L, M, path);
+    const size_t xh_bytes = (size_t)round_up(M * ws.ldxh * 2, 256);
+    const size_t tp_bytes = (ws.S > 1) ? (size_t)round_up((int64_t)ws.S * M * L.kp * 4, 256) : 0;
+    ws.Xh = (uint16_t*)base;
+    ws.Tpart = (ws.S > 1) ? (float*)((uint8_t*)base + xh_bytes) : nullptr;
+    ws.bytes = xh_bytes + tp_bytes;
+    return ws;
+}
+
+static int pick_path(const Layer& L, int64_t M) {
+    (void)L;
+    return (M <= skinny_max_rows()) ? 1 : 2;
+}
+
+static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, const int8_t* Xc,
+                        const uint8_t* Xe, int64_t M, float* Y, int64_t ldy, void* wsp, size_t ws_bytes,
+                        void* stream, const lqer_launch_opts* opts) {
+    if (!layer) return LQER_ERR_NULL;
+    const Layer& L = layer->L;
+    if (M < 0) return LQER_ERR_SHAPE;
+    if (M == 0) return LQER_OK;
+    if (!Y) return LQER_ERR_NULL;
+    if (Xc) {
+        if (!Xe) return LQER_ERR_NULL;
+        if (((uintptr_t)Xc & 15) != 0) return LQER_ERR_SHAPE;
+    } else {
+        if (!X) return LQER_ERR_NULL;
+        if (ldx < L.K || (ldx & 3) != 0 || ((uintptr_t)X & 15) != 0) return LQER_ERR_SHAPE;
+    }
+    if (ldy < L.N || (ldy & 3) != 0 || ((uintptr_t)Y & 15) != 0) return LQER_ERR_SHAPE;
+    int path = opts ? opts->path : 0;
+    const int variant = opts ? opts->variant : 0;
+    int stages = opts ? opts->stages : 0;
+    if (path < 0 || path > 2 || (stages & ~3) != 0) return LQER_ERR_SHAPE;
+    if (path == 0) path = pick_path(L, M);
+    if (path == 1 && M > skinny_max_rows()) return LQER_ERR_SHAPE;
+    if (stages == 0) stages = 3;
+    if (!wsp || ((uintptr_t)wsp & 255) != 0) return LQER_ERR_WORKSPACE;
+    const Workspace ws = plan_workspace(L, M, path, wsp);
+    if (ws.bytes > ws_bytes) return LQER_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    if (stages & 1) {
+        if (launch_prep(L, X, ldx, Xc, Xe, M, ws, s) != hipSuccess) return LQER_ERR_HIP;
+    }
+    if (stages & 2) {
+        const hipError_t e = (path == 1) ? launch_skinny(L, M, ws, Y, ldy, variant, s)
+                                         : launch_tiled(L, M, ws, Y, ldy, variant, s);
+        if (e == hipErrorInvalidValue) return LQER_ERR_SHAPE;
+        if (e != hipSuccess) return LQER_ERR_HIP;
+    }
+    return LQER_OK;
+}
+
+}  // namespace lqer
+
+using namespace lqer;
+
+extern "C" {
+
+const char* lqer_status_string(int status) {
+    switch (status) {
+        case LQER_OK: return "ok";
+        case LQER_ERR_NULL: return "null pointer";
+        case LQER_ERR_SHAPE: return "bad shape, stride or alignment";
+        case LQER_ERR_UNSUPPORTED: return "unsupported format";
+        case LQER_ERR_SINGULAR_SCALE: return "singular activation scale";
+        case LQER_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case LQER_ERR_HIP: return "HIP runtime error";
+        case LQER_ERR_NO_CONVERGENCE: return "truncated SVD did not converge";
+        case LQER_ERR_VALUE: return "packed bytes hold an excluded value";
+        default: return "unknown status";
+    }
+}
+
+int lqer_quantize_mx(const float* x_dev, int64_t rows, int64_t cols, int64_t ld, int elem_bits,
+                     int exp_bits, void* codes_dev, uint8_t* exps_dev, void* hip_stream) {
+    if (elem_bits != 4 && elem_bits != 8) return LQER_ERR_UNSUPPORTED;
+    if (exp_bits != 8) return LQER_ERR_UNSUPPORTED;
+    if (rows < 0 || cols < 0 || (cols & 15) != 0 || ld < cols) return LQER_ERR_SHAPE;
+    if (rows == 0 || cols == 0) return LQER_OK;
+    if (!x_dev || !codes_dev || !exps_dev) return LQER_ERR_NULL;
+    if ((ld & 3) != 0 || ((uintptr_t)x_dev & 15) != 0 || ((uintptr_t)codes_dev & 3) != 0) return LQER_ERR_SHAPE;
+    if (launch_quantize_mx(x_dev, rows, cols, ld, elem_bits, codes_dev, exps_dev, (hipStream_t)hip_stream) !=
+        hipSuccess)
+        return LQER_ERR_HIP;
+    return LQER_OK;
+}
+
+int lqer_layer_import(int64_t K, int64_t N, int k, const uint8_t* Wc, const uint8_t* We, const int8_t* Ac,
+                      const uint8_t* Ae, const int8_t* Bc, const uint8_t* Be, lqer_layer** out) {
+    if (!out) return LQER_ERR_NULL;
+    *out = nullptr;
+    if (K <= 0 || N <= 0 || (K & 15) != 0 || k < 0 || k > K || k > N) return LQER_ERR_SHAPE;
+    if (!Wc || !We) return LQER_ERR_NULL;
+    if (k > 0 && (!Ac || !Ae || !Bc || !Be)) return LQER_ERR_NULL;
+    const int kp = (k + 15) / 16 * 16;
+    if (kp > 64) return LQER_ERR_UNSUPPORTED;
+    lqer_layer* h = new (std::nothrow) lqer_layer;
+    if (!h) return LQER_ERR_HIP;
+    Layer& L = h->L;
+    L.K = K; L.N = N; L.k = k; L.kp = kp;
+    L.KT = (K + kTileK - 1) / kTileK;
+    L.N16 = (N + 15) / 16;
+    L.kp16 = kp / 16;
+    L.Wt = L.At = L.Bt = nullptr;
+    if (hipGetDevice(&L.device) != hipSuccess) { delete h; return LQER_ERR_HIP; }
+    int st;
+    {
+        std::vector<uint8_t> buf;
+        st = tile_weights(L, Wc, We, buf);
+        if (st == LQER_OK) st = upload(buf, &L.Wt);
+    }
+    if (st == LQER_OK && kp > 0) {
+        std::vector<uint8_t> buf;
+        st = tile_a(L, Ac, Ae, buf);
+        if (st == LQER_OK) st = upload(buf, &L.At);
+    }
+    if (st == LQER_OK && kp > 0) {
+        std::vector<uint8_t> buf;
+        st = tile_b(L, Bc, Be, buf);
+        if (st == LQER_OK) st = upload(buf, &L.Bt);
+    }
+    if (st != LQER_OK) {
+        free_device(L);
+        delete h;
+        return st;
+    }
+    *out = h;
+    return LQER_OK;
+}
+
+int lqer_layer_export(const lqer_layer* layer, uint8_t* Wc, uint8_t* We, int8_t* Ac, uint8_t* Ae, int8_t* Bc,
+                      uint8_t* Be) {
+    if (!layer) return LQER_ERR_NULL;
+    const Layer& L = layer->L;
+    std::vector<uint8_t> buf;
+    int st;
+    if (Wc || We) {
+        st = download(L.Wt, (size_t)(L.N16 * L.KT) * kWRecordBytes, buf);
+        if (st != LQER_OK) return st;
+        untile_weights(L, buf, Wc, We);
+    }
+    if (L.kp > 0 && (Ac || Ae)) {
+        st = download(L.At, (size_t)(L.kp16 * L.KT) * kARecordBytes, buf);
+        if (st != LQER_OK) return st;
+        untile_a(L, buf, Ac, Ae);
+    }
+    if (L.kp > 0 && (Bc || Be)) {
+        st = download(L.Bt, (size_t)(L.N16 * L.kp16) * kBRecordBytes, buf);
+        if (st != LQER_OK) return st;
+        untile_b(L, buf, Bc, Be);
+    }
+    return LQER_OK;
+}
+
+int lqer_layer_dims(const lqer_layer* layer, int64_t* K, int64_t* N, int* k, int* kp) {
+    if (!layer) return LQER_ERR_NULL;
+    if (K) *K = layer->L.K;
+    if (N) *N = layer->L.N;
+    if (k) *k = layer->L.k;
+    if (kp) *kp = layer->L.kp;
+    return LQER_OK;
+}
+
+int lqer_layer_free(lqer_layer* layer) {
+    if (!layer) return LQER_OK;
+    free_device(layer->L);
+    delete layer;
+    return LQER_OK;
+}
+
+size_t lqer_linear_workspace_bytes(const lqer_layer* layer, int64_t M) {
+    if (!layer || M <= 0) return 0;
+    const Layer& L = layer->L;
+    size_t best = plan_workspace(L, M, 2, nullptr).bytes;
+    if (M <= skinny_max_rows()) {
+        const size_t b1 = plan_workspace(L, M, 1, nullptr).bytes;
+        if (b1 > best) best = b1;
+    }
+    return best;
+}
+
+int lqer_linear_path(const lqer_layer* layer, int64_t M) {
+    if (!layer) return 0;
+    return pick_path(layer->L, M);
+}
+
+int lqer_linear_forward(const lqer_layer* layer, const float* X_dev, int64_t M, int64_t ldx, float* Y_dev,
+                        int64_t ldy, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+    return forward_impl(layer, X_dev, ldx, nullptr, nullptr, M, Y_dev, ldy, workspace_dev, workspace_bytes,
+                        hip_stream, nullptr);
+}
+
+int lqer_linear_forward_q(const lqer_layer* layer, const int8_t* Xc_dev, const uint8_t* Xe_dev, int64_t M,
+                          float* Y_dev, int64_t ldy, void* workspace_dev, size_t workspace_bytes,
+                          void* hip_stream) {
+    if (!Xc_dev) return LQER_ERR_NULL;
+    return forward_impl(layer, nullptr, 0, Xc_dev, Xe_dev, M, Y_dev, ldy, workspace_dev, workspace_bytes,
+                        hip_stream, nullptr);
+}
+
+int lqer_linear_forward_ex(const lqer_layer* layer, const float* X_dev, int64_t M, int64_t ldx, float* Y_dev,
+                           int64_t ldy, void* workspace_dev, size_t workspace_bytes, void* hip_stream,
+                           const lqer_launch_opts* opts) {
+    return forward_impl(layer, X_dev, ldx, nullptr, nullptr, M, Y_dev, ldy, workspace_dev, workspace_bytes,
+                        hip_stream, opts);
+}
+
+}  // extern "C"

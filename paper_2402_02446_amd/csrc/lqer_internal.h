@@ -1,0 +1,81 @@
+// Internal declarations shared by the host side and the kernel launchers of liblqer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "lqer.h"
+
+namespace lqer {
+
+// ---- internal device layout of one layer ------------------------------------------------
+//
+// W_q is stored as records of [16 columns] x [256 K] so that one wavefront reads a record
+// with fully coalesced 16-byte loads and every lane ends up owning whole MXINT blocks:
+//
+//   record (2304 B) = codes[2][64 lanes][16 B]  +  exps[64 lanes][4 B]
+//   lane = c + 16 q  (c = column within the group, q = 0..3)
+//   lane owns the four 16-blocks b = q + 4p (p = 0..3) of the record's 256-K range;
+//   codes[p/2][lane] holds blocks p and p+1 of that half (8 B each = two 32-bit words),
+//   exps[lane] byte p is block p's exponent byte.
+//   records are ordered [column group][K tile].
+//
+// A 32-bit code word holds 8 consecutive K elements e0..e7 as sign-magnitude nibbles placed so
+// that two mask operations yield fp8 (E4M3) subnormal bytes  s0000mmm = +-m * 2^-9:
+//   byte i:  bit 7 = sign(e_i), bits 6..4 = |e_{4+i}|, bit 3 = sign(e_{4+(i+3)%4}), bits 2..0 = |e_i|
+//   r0 = w & 0x87878787            -> bytes e0 e1 e2 e3
+//   r1 = rotr(w, 4) & 0x87878787   -> bytes e4 e5 e6 e7
+// The MX scale-and-convert instruction then turns two such bytes into two bf16 values
+// code * 2^(e-2) exactly.
+//
+// A_k: records of [16 ranks] x [256 K]: codes[4][64 lanes][16 B] (lane owns blocks q+4p, p-th
+//      16 bytes are block p's int8 codes) + exps[64 lanes][4 B]; ordered [rank group][K tile].
+// B_k: records of [16 columns] x [16 ranks] (one MXINT block per column): codes[16 columns][16 B]
+//      + exps[16 columns][1 B]; ordered [column group][rank block].
+
+constexpr int kTileK = 256;          // K covered by one W / A record
+constexpr int kWRecordBytes = 2304;
+constexpr int kARecordBytes = 4352;
+constexpr int kBRecordBytes = 272;
+constexpr int kMaxWExpByte = 247;    // (byte + 7) must stay a finite fp32 exponent field
+
+struct Layer {
+    int64_t K, N;
+    int k, kp;
+    int64_t KT;        // K tiles of 256
+    int64_t N16;       // column groups of 16
+    int kp16;          // rank groups (= MXINT blocks along k) of 16
+    int device;
+    uint8_t* Wt;       // device, N16*KT records
+    uint8_t* At;       // device, kp16*KT records
+    uint8_t* Bt;       // device, N16*kp16 records
+};
+
+// Workspace layout for one forward call.
+struct Workspace {
+    int64_t ldxh;        // row stride of Xh in bf16 elements = KT*256 + roundup(2*kp, 64)
+    int S;               // K slices of the T partial sums (1 = T final, written into Xh)
+    uint16_t* Xh;        // [M][ldxh] bf16 : dequantized X_q | T_hi | T_lo
+    float* Tpart;        // [S][M][kp] fp32 (only when S > 1)
+    size_t bytes;
+};
+
+// ---- kernel launchers (each returns the hipError_t of its launch) ------------------------
+hipError_t launch_quantize_mx(const float* x, int64_t rows, int64_t cols, int64_t ld, int bits,
+                              void* codes, uint8_t* exps, hipStream_t s);
+
+// Quantize X (or take codes) -> Xh bf16, and T = X_q A_k.  S == 1 writes T_hi/T_lo into Xh,
+// S > 1 writes fp32 partial sums per K slice.
+hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t* Xc, const uint8_t* Xe,
+                       int64_t M, const Workspace& ws, hipStream_t s);
+
+// Streaming (small M) main kernel.  variant 0 = automatic.
+hipError_t launch_skinny(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
+                         int variant, hipStream_t s);
+// Tiled MFMA (large M) main kernel.
+hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
+                        int variant, hipStream_t s);
+
+int skinny_max_rows();      // largest M the streaming kernel accepts
+int prep_slices(const Layer& L, int64_t M, int path);
+
+}  // namespace lqer

@@ -1,0 +1,183 @@
+"""GPU parity of lqer_linear_forward against the fp64 oracle (Eq. 3, Eq. 6): relative Frobenius
+error of Y within the stated 1e-3 bar (and within what fp32 accumulation of exact products
+should give), bitwise equality where the arithmetic is exact in any order, both kernels, every
+tile shape, ragged sizes, and the full LLaMA-shaped workloads on sampled rows."""
+import numpy as np
+import pytest
+
+from oracle import factors, forward, mxint
+from paper_2402_02446_amd import synth
+from helpers import (Y_TOL, Y_TOL_DERIVED, oracle_forward_cols, oracle_layer_big, oracle_layer_small,
+                     oracle_rows, upload)
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu_forward(h, X, **kw):
+    import torch
+    from paper_2402_02446_amd import binding
+    Xd = torch.from_numpy(np.ascontiguousarray(X)).cuda()
+    Y = binding.lqer_linear_forward_ex(h, Xd, **kw) if kw else binding.lqer_linear_forward(h, Xd)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy()
+
+
+def _assert_close(Y, Yref):
+    err = forward.rel_frobenius(Y, Yref)
+    assert np.all(np.isfinite(Y))
+    assert err <= Y_TOL, err
+    assert err <= Y_TOL_DERIVED, err
+
+
+def test_cfg1_exact_factors():
+    wl = synth.WORKLOADS["cfg1"]
+    d = synth.draw(wl)
+    layer = factors.build_factors(d.W, d.calib, wl.k, 1)
+    h = upload(layer)
+    X = d.X[16]
+    _assert_close(_gpu_forward(h, X), forward.forward(X, layer))
+    h.free()
+
+
+@pytest.mark.parametrize("M", [1, 2, 15, 16, 17, 33, 48, 64])
+def test_streaming_kernel_row_counts(M):
+    layer, ch = oracle_layer_small(512, 256, 24, seed=M)
+    h = upload(layer)
+    X = synth.gen_activations(np.random.default_rng(M), M, 512, ch, 30.0)
+    _assert_close(_gpu_forward(h, X, path=1), forward.forward(X, layer))
+    h.free()
+
+
+@pytest.mark.parametrize("K,N,k", [(48, 40, 0), (272, 100, 8), (1024, 272, 64), (2304, 528, 33), (4096, 64, 16)])
+@pytest.mark.parametrize("ng", [1, 2, 4])
+def test_streaming_kernel_shapes(K, N, k, ng):
+    layer, ch = oracle_layer_small(K, N, k, seed=K + k)
+    h = upload(layer)
+    X = synth.gen_activations(np.random.default_rng(1), 5, K, ch, 30.0)
+    _assert_close(_gpu_forward(h, X, path=1, variant=ng), forward.forward(X, layer))
+    h.free()
+
+
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("M,K,N,k", [(16, 512, 512, 8), (300, 272, 200, 0), (513, 1024, 528, 64), (100, 2304, 40, 33)])
+def test_tiled_kernel_shapes(variant, M, K, N, k):
+    layer, ch = oracle_layer_small(K, N, k, seed=M + variant)
+    h = upload(layer)
+    X = synth.gen_activations(np.random.default_rng(2), M, K, ch, 30.0)
+    _assert_close(_gpu_forward(h, X, path=2, variant=variant), forward.forward(X, layer))
+    h.free()
+
+
+@pytest.mark.parametrize("path", [1, 2])
+def test_uniform_exponent_case_is_bitwise_exact(path):
+    # Every partial sum is an integer multiple of one power of two below 2^24: any fp32 order is exact.
+    rng = np.random.default_rng(6)
+    K, N, M = 512, 96, 16
+    Wc = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    layer = factors.PackedLayer(K=K, N=N, k=0, kp=0, Wc=mxint.pack_int4(Wc),
+                                We=np.full((N, K // 16), 125, np.uint8),
+                                Ac=np.zeros((0, K), np.int8), Ae=np.zeros((0, K // 16), np.uint8),
+                                Bc=np.zeros((N, 0), np.int8), Be=np.zeros((N, 0), np.uint8))
+    codes = rng.integers(-100, 101, size=(M, K)).astype(np.float64)
+    codes[:, ::16] = 127.0                                   # pins every block's exponent to 0
+    X = (codes / 64.0).astype(np.float32)
+    Yref = forward.forward(X, layer)
+    assert np.abs(Yref * 2 ** 10).max() < 2 ** 24
+    Y = _gpu_forward(upload(layer), X, path=path)
+    assert np.array_equal(Y.astype(np.float64), Yref)
+
+
+def test_wide_exponent_spread():
+    # block exponents spread over 2^+-40 on both operands; still exact products, fp32 accumulation
+    rng = np.random.default_rng(8)
+    K, N, M = 512, 64, 16
+    W = (rng.standard_normal((K, N)) * np.exp2(rng.integers(-40, 40, (K // 16, 1, N)).repeat(16, 0).reshape(K, N))).astype(np.float32)
+    X = (rng.standard_normal((M, K)) * np.exp2(rng.integers(-40, 40, (M, K // 16)).repeat(16, 1))).astype(np.float32)
+    calib = np.abs(rng.standard_normal((1, 16, K))).astype(np.float32) + 0.1
+    layer = factors.build_factors(W, calib, 16, 1)
+    h = upload(layer)
+    Yref = forward.forward(X, layer)
+    for path in (1, 2):
+        _assert_close(_gpu_forward(h, X, path=path), Yref)
+    h.free()
+
+
+def test_prequantized_entry_point_and_stage_split():
+    import torch
+    from paper_2402_02446_amd import binding
+    layer, ch = oracle_layer_small(1024, 272, 32, seed=9)
+    h = upload(layer)
+    for M in (7, 200):
+        X = synth.gen_activations(np.random.default_rng(M), M, 1024, ch, 30.0)
+        Xd = torch.from_numpy(X).cuda()
+        Y = binding.lqer_linear_forward(h, Xd)
+        Xc, Xe = binding.lqer_quantize_mx(Xd, 8)
+        Yq = binding.lqer_linear_forward_q(h, Xc, Xe)
+        Y1 = torch.zeros_like(Y)
+        binding.lqer_linear_forward_ex(h, Xd, Y=Y1, stages=1)
+        binding.lqer_linear_forward_ex(h, Xd, Y=Y1, stages=2)
+        torch.cuda.synchronize()
+        assert torch.equal(Y, Yq) and torch.equal(Y, Y1)
+        _assert_close(Y.cpu().numpy(), forward.forward(X, layer))
+    h.free()
+
+
+def test_strided_x_and_y():
+    import torch
+    from paper_2402_02446_amd import binding
+    layer, ch = oracle_layer_small(512, 100, 8, seed=4)
+    h = upload(layer)
+    X = synth.gen_activations(np.random.default_rng(3), 9, 512, ch, 30.0)
+    xb = torch.full((9, 600), 7.0e30, dtype=torch.float32, device="cuda")
+    xb[:, :512] = torch.from_numpy(X).cuda()
+    yb = torch.full((9, 128), -5.0, dtype=torch.float32, device="cuda")
+    binding.lqer_linear_forward(h, xb[:, :512], Y=yb[:, :100])
+    torch.cuda.synchronize()
+    out = yb.cpu().numpy()
+    assert np.all(out[:, 100:] == -5.0)                    # nothing written outside Y
+    _assert_close(out[:, :100], forward.forward(X, layer))
+    h.free()
+
+
+def test_argument_errors_on_device():
+    import torch
+    from paper_2402_02446_amd import binding
+    layer, _ = oracle_layer_small(64, 32, 8)
+    h = upload(layer)
+    X = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.LqerError) as e:
+        binding.lqer_linear_forward(h, X, workspace=small)
+    assert e.value.status == 5
+    with pytest.raises(binding.LqerError) as e:
+        binding.lqer_linear_forward_ex(h, torch.zeros((100, 64), device="cuda"), path=1)   # too many rows
+    assert e.value.status == 2
+    Y = binding.lqer_linear_forward(h, X[:0])
+    assert Y.shape == (0, 32)
+    h.free()
+
+
+# ---- the LLaMA-shaped workloads at full size, in the launch configuration the benchmark times ----
+
+def test_cfg2_decode_full():
+    wl = synth.WORKLOADS["cfg2"]
+    layer, ch = oracle_layer_big(wl.K, wl.N, wl.k, seed=0, n_outlier=wl.n_outlier, gain=wl.gain)
+    h = upload(layer)
+    for M in wl.Ms:
+        X = synth.gen_activations(np.random.default_rng(M), M, wl.K, ch, wl.gain)
+        _assert_close(_gpu_forward(h, X), forward.forward(X, layer))
+    h.free()
+
+
+@pytest.mark.parametrize("name", ["cfg3_up", "cfg3_down"])
+def test_cfg3_prefill_sampled_rows(name):
+    wl = synth.WORKLOADS[name]
+    layer, ch = oracle_layer_big(wl.K, wl.N, wl.k, seed=1, n_outlier=wl.n_outlier, gain=wl.gain)
+    h = upload(layer)
+    M = wl.Ms[0]
+    X = synth.gen_activations(np.random.default_rng(11), M, wl.K, ch, wl.gain)
+    Y = _gpu_forward(h, X)
+    rows = np.r_[0, 1, 255, 256, 1023, M - 1, np.random.default_rng(0).integers(0, M, 26)]
+    _assert_close(Y[rows], oracle_rows(X[rows], layer))
+    assert np.all(np.isfinite(Y))
+    h.free()

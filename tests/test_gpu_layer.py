@@ -1,0 +1,82 @@
+"""Layer handles on the GPU: canonical bytes survive the internal tiled layout, bad bytes are
+rejected, lqer_build_factors reproduces the oracle's W_q bit for bit and reaches the optimal
+rank-k residual (Eq. 1-2, 4-5; App. A)."""
+import numpy as np
+import pytest
+
+from oracle import factors, mxint
+from paper_2402_02446_amd import synth
+from helpers import oracle_layer_small, upload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("K,N,k", [(512, 512, 8), (272, 40, 0), (48, 100, 33), (1024, 272, 64)])
+def test_import_export_roundtrip(K, N, k):
+    from paper_2402_02446_amd import binding
+    layer, _ = oracle_layer_small(K, N, k, seed=K + N + k)
+    h = upload(layer)
+    out = binding.lqer_layer_export(h)
+    assert (h.K, h.N, h.k, h.kp) == (K, N, k, layer.kp)
+    assert np.array_equal(out["Wc"], layer.Wc) and np.array_equal(out["We"], layer.We)
+    if k:
+        assert np.array_equal(out["Ac"], layer.Ac) and np.array_equal(out["Ae"], layer.Ae)
+        assert np.array_equal(out["Bc"], layer.Bc) and np.array_equal(out["Be"], layer.Be)
+    h.free()
+
+
+def test_import_rejects_excluded_values():
+    from paper_2402_02446_amd import binding
+    layer, _ = oracle_layer_small(64, 32, 0)
+    bad = layer.Wc.copy()
+    bad[3, 5] = 0x08 | (bad[3, 5] & 0xF0)             # nibble -8 is not a code
+    with pytest.raises(binding.LqerError) as e:
+        binding.lqer_layer_import(64, 32, 0, bad, layer.We)
+    assert e.value.status == 8
+    bade = layer.We.copy()
+    bade[0, 0] = 250
+    with pytest.raises(binding.LqerError) as e:
+        binding.lqer_layer_import(64, 32, 0, layer.Wc, bade)
+    assert e.value.status == 8
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_build_factors_against_oracle(mode):
+    from paper_2402_02446_amd import binding
+    wl = synth.WORKLOADS["cfg1"]
+    d = synth.draw(wl)
+    ref = factors.build_factors(d.W, d.calib, wl.k, mode)
+    h = binding.lqer_build_factors(d.W, d.calib, wl.k, mode)
+    out = binding.lqer_layer_export(h)
+    # W_q: bit-exact codes and exponents
+    assert np.array_equal(out["Wc"], ref.Wc) and np.array_equal(out["We"], ref.We)
+    # factors: SVD sign / rotation freedom -> compare what is unique: the weighted residual of the
+    # unquantized optimum, and the product A B
+    W_hat, A_ref, B_ref = factors.dequantize_layer(ref)
+    got = factors.PackedLayer(K=wl.K, N=wl.N, k=wl.k, kp=h.kp, **out)
+    _, A_got, B_got = factors.dequantize_layer(got)
+    s = factors.calibrate_scale(d.calib) if mode == 1 else np.ones(wl.K)
+    E = d.W.astype(np.float64) - W_hat
+    r_ref = np.linalg.norm(s[:, None] * (E - A_ref @ B_ref))
+    r_got = np.linalg.norm(s[:, None] * (E - A_got @ B_got))
+    sig = np.linalg.svd(s[:, None] * E, compute_uv=False)
+    opt = np.sqrt((sig[wl.k:] ** 2).sum())
+    assert r_got <= opt * 1.01 and abs(r_got - r_ref) <= 0.01 * r_ref
+    h.free()
+
+
+def test_build_factors_full_rank_and_zero_rank():
+    from paper_2402_02446_amd import binding
+    rng = np.random.default_rng(3)
+    W = synth.gen_weight(rng, 64, 48)
+    h = binding.lqer_build_factors(W, None, 48, mode=0)
+    out = binding.lqer_layer_export(h)
+    got = factors.PackedLayer(K=64, N=48, k=48, kp=48, **out)
+    W_hat, A, B = factors.dequantize_layer(got)
+    # k = min(K, N): W_q + A B recovers W up to the 8-bit quantization of the factors
+    base = np.linalg.norm(W - W_hat)
+    assert np.linalg.norm(W - W_hat - A @ B) < 0.05 * base
+    h.free()
+    h0 = binding.lqer_build_factors(W, None, 0, mode=0)
+    assert h0.kp == 0
+    h0.free()
