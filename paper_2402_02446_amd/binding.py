@@ -47,6 +47,9 @@ def lib() -> C.CDLL:
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch ships its own HIP runtime: import it first so that liblqer.so binds to the same
+    # runtime instance (and the same streams and allocations) instead of loading a second one.
+    import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2402_02446_amd.build` "
                            "(there is no CPU fallback)")

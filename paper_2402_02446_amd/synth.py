@@ -139,3 +139,24 @@ def adversarial_blocks(rng: np.random.Generator, n_blocks: int) -> np.ndarray:
         else:              # ordinary Gaussian at a random binade
             out[i] = np.float32(rng.standard_normal(16)) * base
     return out
+
+
+def random_packed_layer(rng: np.random.Generator, K: int, N: int, k: int):
+    """Random canonical bytes with the statistics of a quantized Gaussian layer, for timing runs
+    at sizes where quantizing real draws on the host would dominate the run: 4-bit codes drawn
+    uniformly from [-7, 7] with exponent bytes near 2^-6, int8 factor codes with exponents near
+    2^-8 (A_k) and 2^-10 (B_k).  Returns a dict of the six canonical arrays plus kp."""
+    kp = ((k + 15) // 16) * 16
+    nib = rng.integers(1, 16, size=(N, K), dtype=np.uint8)            # two's-complement nibbles, never -8
+    nib[nib >= 8] += 1                                                # 8..14 -> 9..15  (codes -7..-1)
+    Wc = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+    We = rng.integers(119, 123, size=(N, K // 16), dtype=np.uint8)
+    Ac = rng.integers(-127, 128, size=(kp, K)).astype(np.int8)
+    Ae = rng.integers(117, 121, size=(kp, K // 16), dtype=np.uint8)
+    Bc = rng.integers(-127, 128, size=(N, kp)).astype(np.int8)
+    Be = rng.integers(115, 119, size=(N, max(kp // 16, 0)), dtype=np.uint8)
+    if kp > k:
+        Ac[k:] = 0
+        Ae[k:] = 0
+        Bc[:, k:] = 0
+    return dict(K=K, N=N, k=k, kp=kp, Wc=Wc, We=We, Ac=Ac, Ae=Ae, Bc=Bc, Be=Be)
