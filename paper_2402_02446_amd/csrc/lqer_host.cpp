@@ -47,39 +47,38 @@ static inline int nibble_to_code(uint32_t v) { return v < 8 ? (int)v : (int)v - 
 // canonical Wc/We -> tiled records.  Returns LQER_ERR_VALUE on a -8 nibble or an exponent byte > 247.
 static int tile_weights(const Layer& L, const uint8_t* Wc, const uint8_t* We, std::vector<uint8_t>& out) {
     const int64_t nblk = L.K / 16;
-    out.assign((size_t)(L.N16 * L.KT) * kWRecordBytes, 0);
+    out.assign((size_t)(L.N32 * L.KT) * kWRecordBytes, 0);
     for (int64_t n = 0; n < L.N; ++n)
         for (int64_t kb = 0; kb < nblk; ++kb)
             if (We[n * nblk + kb] > kMaxWExpByte) return LQER_ERR_VALUE;
     std::atomic<int> bad{0};
-    parallel_for(L.N16, [&](int64_t g) {
+    parallel_for(L.N32, [&](int64_t g) {
         for (int64_t tile = 0; tile < L.KT; ++tile) {
             uint8_t* rec = out.data() + (size_t)(g * L.KT + tile) * kWRecordBytes;
             for (int lane = 0; lane < 64; ++lane) {
-                const int c = lane & 15, q = lane >> 4;
-                const int64_t n = g * 16 + c;
-                uint32_t ew = 0;
-                for (int p = 0; p < 4; ++p) {
-                    const int64_t kb = tile * 16 + q + 4 * p;
-                    int8_t codes[16] = {0};
-                    uint32_t eb = 0;
-                    if (n < L.N && kb < nblk) {
-                        const uint8_t* src = Wc + n * (L.K / 2) + kb * 8;
-                        for (int i = 0; i < 8; ++i) {
-                            const uint32_t lo = src[i] & 0xF, hi = src[i] >> 4;
-                            if (lo == 8 || hi == 8) bad.store(1, std::memory_order_relaxed);
-                            codes[2 * i] = (int8_t)nibble_to_code(lo);
-                            codes[2 * i + 1] = (int8_t)nibble_to_code(hi);
+                const int i = lane & 31, hh = lane >> 5;
+                const int64_t n = g * 32 + i;
+                for (int c = 0; c < 4; ++c)
+                    for (int j = 0; j < 2; ++j) {
+                        const int64_t kb = tile * 16 + 4 * c + 2 * hh + j;
+                        int8_t codes[16] = {0};
+                        uint8_t eb = 0;
+                        if (n < L.N && kb < nblk) {
+                            const uint8_t* src = Wc + n * (L.K / 2) + kb * 8;
+                            for (int e = 0; e < 8; ++e) {
+                                const uint32_t lo = src[e] & 0xF, hi = src[e] >> 4;
+                                if (lo == 8 || hi == 8) bad.store(1, std::memory_order_relaxed);
+                                codes[2 * e] = (int8_t)nibble_to_code(lo);
+                                codes[2 * e + 1] = (int8_t)nibble_to_code(hi);
+                            }
+                            eb = We[n * nblk + kb];
                         }
-                        eb = We[n * nblk + kb];
+                        const uint32_t w0 = encode_word(codes), w1 = encode_word(codes + 8);
+                        uint8_t* dst = rec + c * 1024 + lane * 16 + j * 8;
+                        memcpy(dst, &w0, 4);
+                        memcpy(dst + 4, &w1, 4);
+                        rec[kWExpOffset + lane * 8 + 2 * c + j] = eb;
                     }
-                    const uint32_t w0 = encode_word(codes), w1 = encode_word(codes + 8);
-                    uint8_t* dst = rec + (p >> 1) * 1024 + lane * 16 + (p & 1) * 8;
-                    memcpy(dst, &w0, 4);
-                    memcpy(dst + 4, &w1, 4);
-                    ew |= eb << (8 * p);
-                }
-                memcpy(rec + 2048 + lane * 4, &ew, 4);
             }
         }
     });
@@ -88,32 +87,31 @@ static int tile_weights(const Layer& L, const uint8_t* Wc, const uint8_t* We, st
 
 static void untile_weights(const Layer& L, const std::vector<uint8_t>& in, uint8_t* Wc, uint8_t* We) {
     const int64_t nblk = L.K / 16;
-    parallel_for(L.N16, [&](int64_t g) {
+    parallel_for(L.N32, [&](int64_t g) {
         for (int64_t tile = 0; tile < L.KT; ++tile) {
             const uint8_t* rec = in.data() + (size_t)(g * L.KT + tile) * kWRecordBytes;
             for (int lane = 0; lane < 64; ++lane) {
-                const int c = lane & 15, q = lane >> 4;
-                const int64_t n = g * 16 + c;
+                const int i = lane & 31, hh = lane >> 5;
+                const int64_t n = g * 32 + i;
                 if (n >= L.N) continue;
-                uint32_t ew;
-                memcpy(&ew, rec + 2048 + lane * 4, 4);
-                for (int p = 0; p < 4; ++p) {
-                    const int64_t kb = tile * 16 + q + 4 * p;
-                    if (kb >= nblk) continue;
-                    uint32_t w0, w1;
-                    const uint8_t* src = rec + (p >> 1) * 1024 + lane * 16 + (p & 1) * 8;
-                    memcpy(&w0, src, 4);
-                    memcpy(&w1, src + 4, 4);
-                    int8_t codes[16];
-                    decode_word(w0, codes);
-                    decode_word(w1, codes + 8);
-                    if (Wc) {
-                        uint8_t* dst = Wc + n * (L.K / 2) + kb * 8;
-                        for (int i = 0; i < 8; ++i)
-                            dst[i] = (uint8_t)((codes[2 * i] & 0xF) | ((codes[2 * i + 1] & 0xF) << 4));
+                for (int c = 0; c < 4; ++c)
+                    for (int j = 0; j < 2; ++j) {
+                        const int64_t kb = tile * 16 + 4 * c + 2 * hh + j;
+                        if (kb >= nblk) continue;
+                        uint32_t w0, w1;
+                        const uint8_t* src = rec + c * 1024 + lane * 16 + j * 8;
+                        memcpy(&w0, src, 4);
+                        memcpy(&w1, src + 4, 4);
+                        int8_t codes[16];
+                        decode_word(w0, codes);
+                        decode_word(w1, codes + 8);
+                        if (Wc) {
+                            uint8_t* dst = Wc + n * (L.K / 2) + kb * 8;
+                            for (int e = 0; e < 8; ++e)
+                                dst[e] = (uint8_t)((codes[2 * e] & 0xF) | ((codes[2 * e + 1] & 0xF) << 4));
+                        }
+                        if (We) We[n * nblk + kb] = rec[kWExpOffset + lane * 8 + 2 * c + j];
                     }
-                    if (We) We[n * nblk + kb] = (uint8_t)((ew >> (8 * p)) & 0xFF);
-                }
             }
         }
     });
@@ -164,31 +162,31 @@ static void untile_a(const Layer& L, const std::vector<uint8_t>& in, int8_t* Ac,
 }
 
 static int tile_b(const Layer& L, const int8_t* Bc, const uint8_t* Be, std::vector<uint8_t>& out) {
-    out.assign((size_t)(L.N16 * L.kp16) * kBRecordBytes, 0);
+    out.assign((size_t)(L.N32 * L.kp16) * kBRecordBytes, 0);
     for (int64_t i = 0; i < L.N * L.kp16; ++i)
         if (Be[i] == 255) return LQER_ERR_VALUE;
-    for (int64_t g = 0; g < L.N16; ++g)
+    for (int64_t g = 0; g < L.N32; ++g)
         for (int rb = 0; rb < L.kp16; ++rb) {
             uint8_t* rec = out.data() + (size_t)(g * L.kp16 + rb) * kBRecordBytes;
-            for (int c = 0; c < 16; ++c) {
-                const int64_t n = g * 16 + c;
+            for (int c = 0; c < 32; ++c) {
+                const int64_t n = g * 32 + c;
                 if (n >= L.N) continue;
                 memcpy(rec + c * 16, Bc + n * L.kp + rb * 16, 16);
-                rec[256 + c] = Be[n * L.kp16 + rb];
+                rec[512 + c] = Be[n * L.kp16 + rb];
             }
         }
     return LQER_OK;
 }
 
 static void untile_b(const Layer& L, const std::vector<uint8_t>& in, int8_t* Bc, uint8_t* Be) {
-    for (int64_t g = 0; g < L.N16; ++g)
+    for (int64_t g = 0; g < L.N32; ++g)
         for (int rb = 0; rb < L.kp16; ++rb) {
             const uint8_t* rec = in.data() + (size_t)(g * L.kp16 + rb) * kBRecordBytes;
-            for (int c = 0; c < 16; ++c) {
-                const int64_t n = g * 16 + c;
+            for (int c = 0; c < 32; ++c) {
+                const int64_t n = g * 32 + c;
                 if (n >= L.N) continue;
                 if (Bc) memcpy(Bc + n * L.kp + rb * 16, rec + c * 16, 16);
-                if (Be) Be[n * L.kp16 + rb] = rec[256 + c];
+                if (Be) Be[n * L.kp16 + rb] = rec[512 + c];
             }
         }
 }
@@ -320,7 +318,7 @@ int lqer_layer_import(int64_t K, int64_t N, int k, const uint8_t* Wc, const uint
     Layer& L = h->L;
     L.K = K; L.N = N; L.k = k; L.kp = kp;
     L.KT = (K + kTileK - 1) / kTileK;
-    L.N16 = (N + 15) / 16;
+    L.N32 = (N + 31) / 32;
     L.kp16 = kp / 16;
     L.Wt = L.At = L.Bt = nullptr;
     if (hipGetDevice(&L.device) != hipSuccess) { delete h; return LQER_ERR_HIP; }
@@ -356,7 +354,7 @@ int lqer_layer_export(const lqer_layer* layer, uint8_t* Wc, uint8_t* We, int8_t*
     std::vector<uint8_t> buf;
     int st;
     if (Wc || We) {
-        st = download(L.Wt, (size_t)(L.N16 * L.KT) * kWRecordBytes, buf);
+        st = download(L.Wt, (size_t)(L.N32 * L.KT) * kWRecordBytes, buf);
         if (st != LQER_OK) return st;
         untile_weights(L, buf, Wc, We);
     }
@@ -366,7 +364,7 @@ int lqer_layer_export(const lqer_layer* layer, uint8_t* Wc, uint8_t* We, int8_t*
         untile_a(L, buf, Ac, Ae);
     }
     if (L.kp > 0 && (Bc || Be)) {
-        st = download(L.Bt, (size_t)(L.N16 * L.kp16) * kBRecordBytes, buf);
+        st = download(L.Bt, (size_t)(L.N32 * L.kp16) * kBRecordBytes, buf);
         if (st != LQER_OK) return st;
         untile_b(L, buf, Bc, Be);
     }

@@ -9,14 +9,18 @@ namespace lqer {
 
 // ---- internal device layout of one layer ------------------------------------------------
 //
-// W_q is stored as records of [16 columns] x [256 K] so that one wavefront reads a record
-// with fully coalesced 16-byte loads and every lane ends up owning whole MXINT blocks:
+// The main kernels use the 32x32x16 bf16 MFMA with the weights as its first operand: lane
+// (i = lane % 32, hh = lane / 32) supplies 8 consecutive K elements of output column i, and the
+// 16-wide K step splits between the two lane halves.  The K axis is permuted inside every
+// 64-wide chunk so that a lane owns whole MXINT blocks: in MFMA step s (0..3) of a chunk, lane
+// half hh covers k = 32 hh + 8 s .. + 7, i.e. hh owns blocks 2hh and 2hh+1 of the chunk and no
+// block scale ever crosses lanes.  Activations follow the same permutation simply by reading
+// 16 bytes at that offset.
 //
-//   record (2304 B) = codes[2][64 lanes][16 B]  +  exps[64 lanes][4 B]
-//   lane = c + 16 q  (c = column within the group, q = 0..3)
-//   lane owns the four 16-blocks b = q + 4p (p = 0..3) of the record's 256-K range;
-//   codes[p/2][lane] holds blocks p and p+1 of that half (8 B each = two 32-bit words),
-//   exps[lane] byte p is block p's exponent byte.
+// W_q record = [32 columns] x [256 K], 4608 B, read by one wavefront with coalesced 16-byte loads:
+//   codes[4 chunks][64 lanes][16 B]  lane's 16 B = blocks (4c + 2hh), (4c + 2hh + 1) of the tile,
+//                                    two 32-bit words (8 elements each) per block
+//   exps[64 lanes][8 B]              byte 2c + j = exponent byte of block 4c + 2hh + j
 //   records are ordered [column group][K tile].
 //
 // A 32-bit code word holds 8 consecutive K elements e0..e7 as sign-magnitude nibbles placed so
@@ -27,27 +31,29 @@ namespace lqer {
 // The MX scale-and-convert instruction then turns two such bytes into two bf16 values
 // code * 2^(e-2) exactly.
 //
-// A_k: records of [16 ranks] x [256 K]: codes[4][64 lanes][16 B] (lane owns blocks q+4p, p-th
-//      16 bytes are block p's int8 codes) + exps[64 lanes][4 B]; ordered [rank group][K tile].
-// B_k: records of [16 columns] x [16 ranks] (one MXINT block per column): codes[16 columns][16 B]
-//      + exps[16 columns][1 B]; ordered [column group][rank block].
+// A_k (used by the projection kernel with the 16x16x32 MFMA, lane = c + 16 q owning blocks
+//      q + 4p): records of [16 ranks] x [256 K]: codes[4][64 lanes][16 B] (p-th 16 bytes are block
+//      q + 4p's int8 codes) + exps[64 lanes][4 B]; ordered [rank group][K tile].
+// B_k: records of [32 columns] x [16 ranks] (one MXINT block per column): codes[32 columns][16 B]
+//      + exps[32 columns][1 B]; ordered [column group][rank block].
 
 constexpr int kTileK = 256;          // K covered by one W / A record
-constexpr int kWRecordBytes = 2304;
+constexpr int kWRecordBytes = 4608;
+constexpr int kWExpOffset = 4096;
 constexpr int kARecordBytes = 4352;
-constexpr int kBRecordBytes = 272;
+constexpr int kBRecordBytes = 544;
 constexpr int kMaxWExpByte = 247;    // (byte + 7) must stay a finite fp32 exponent field
 
 struct Layer {
     int64_t K, N;
     int k, kp;
     int64_t KT;        // K tiles of 256
-    int64_t N16;       // column groups of 16
+    int64_t N32;       // column groups of 32
     int kp16;          // rank groups (= MXINT blocks along k) of 16
     int device;
-    uint8_t* Wt;       // device, N16*KT records
+    uint8_t* Wt;       // device, N32*KT records
     uint8_t* At;       // device, kp16*KT records
-    uint8_t* Bt;       // device, N16*kp16 records
+    uint8_t* Bt;       // device, N32*kp16 records
 };
 
 // Workspace layout for one forward call.

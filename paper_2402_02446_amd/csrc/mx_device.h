@@ -8,10 +8,11 @@ namespace lqer {
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-union Frag {            // one MFMA 16x16x32 bf16 operand: 8 bf16 per lane
+union Frag {            // one bf16 MFMA operand (16x16x32 or 32x32x16): 8 bf16 per lane
     bf16x8 v;
     u32x4 u;
     bf16x2 h[4];
@@ -67,6 +68,12 @@ __device__ __forceinline__ float h_scale(uint32_t eb) {
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// D[i][j] += sum_k A[i][k] B[k][j], 32 x 32 x 16.  Lane (l % 32, l / 32) supplies A[l % 32][8 (l/32) ..+7]
+// and B[8 (l/32) ..+7][l % 32]; accumulator register r of lane l is D[8 (r/4) + 4 (l/32) + r % 4][l % 32].
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
 // MXINT8 quantization of one value given the block's exponent byte: code = sat(rne(v * 2^(6-e))).
