@@ -3,15 +3,23 @@
 // whole job here is to read 0.5625 B per weight once, as contiguous 1 KiB wavefront loads, and to
 // hide everything else under that stream.
 //
-// A workgroup owns NG groups of 32 output columns and all of K; its NW wavefronts take the
-// 256-wide K tiles in turn and their partial sums are added through LDS in a fixed tree order.
-// Per tile and column group a lane reads 64 B of packed codes (eight whole MXINT4 blocks) and
-// their eight exponent bytes, expands 8 codes to bf16 values code * 2^(e-2) with seven VALU
-// instructions (unpack_w8) and feeds them to the 32x32x16 bf16 MFMA against the dequantized
-// activations (tokens beyond M repeat the last one and are never stored); all products are exact
-// and accumulation is fp32.  The rank-kp correction is 2*kp further "K columns": T_hi and T_lo
-// against B_k's codes.  Weight records are fetched one tile ahead and activations one 64-wide
-// chunk ahead, so HBM and L2 latency overlap the arithmetic.
+// A workgroup is a grid of NWC x NWK wavefronts: wavefront (wc, wk) owns one group of 32 output
+// columns and every NWK-th 256-wide K tile, so in each iteration the workgroup works on NWK
+// consecutive K tiles.  Their activations (bf16, exact dequantized X_q) are staged once per
+// workgroup into LDS and shared by the NWC column groups, which keeps activation traffic at
+// 1/NWC-th of what every wavefront fetching its own would cost.  The order of loads matters:
+// vector-memory loads retire in order, so a wavefront that waits for a load also waits for every
+// load issued before it.  Each iteration therefore issues the (small) activation loads of the
+// next iteration first and the weight record of the iteration after next last; when the
+// activations are written to LDS at the end of the iteration the weight record stays in flight,
+// and three weight records rotate through three named register sets (the loop is unrolled by
+// three) so that no register copy ever forces a wait on the newest one.
+// Per tile a lane reads 64 B of packed codes (eight whole MXINT4 blocks) and their eight exponent
+// bytes, expands 8 codes to bf16 values code * 2^(e-2) with seven VALU instructions (unpack_w8)
+// and feeds them to the 32x32x16 bf16 MFMA against the activations (tokens beyond M repeat the
+// last one and are never stored); products are exact, accumulation is fp32.  The rank-kp
+// correction is 2*kp further "K columns": T_hi and T_lo against B_k's codes.  The NWK partial sums
+// of a column group are added through LDS in a fixed tree order.
 #include "lqer_internal.h"
 #include "mx_device.h"
 
@@ -39,223 +47,249 @@ __device__ __forceinline__ WRec load_wrec(const uint8_t* rec, int lane) {
     return r;
 }
 
-struct XChunk {         // one lane's activations for a 64-wide chunk: 4 MFMA steps x 8 bf16
-    u32x4 s[4];
-};
-
-__device__ __forceinline__ XChunk load_xchunk(const uint16_t* p) {
-    XChunk x;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) x.s[s] = *reinterpret_cast<const u32x4*>(p + 8 * s);
-    return x;
-}
-
-template <int TM, int NG, int NW>
-__global__ __launch_bounds__(64 * NW) void skinny_kernel(SkinnyArgs a) {
-    __shared__ float red[NW / 2][TM][NG][64][16];
+// LR = log2 of the token rows staged (4, 16 or 32).  LDS cell order of a stage is
+// [16-byte column of the NWK*256-wide K range][token row], so 16 lanes read 256 contiguous bytes.
+template <int NWC, int NWK, int LR>
+__global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
+    constexpr int NW = NWC * NWK;
+    constexpr int R = 1 << LR;
+    constexpr int XT = NWK * R * 512;                // bytes of one stage: R rows x NWK tiles of bf16
+    constexpr int NL = XT / 1024;                    // direct loads (1 KiB each) per stage
+    constexpr int XL = (NL + NW - 1) / NW;           // ... per wavefront
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    float* red = reinterpret_cast<float*>(lds);      // reused after the main loop: [NWK/2][NWC][64][16]
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
+    const int uwave = __builtin_amdgcn_readfirstlane(wave);
+    const int wc = uwave % NWC, wk = uwave / NWC;
     const int t = lane & 31, hh = lane >> 5;
 
-    int64_t grp[NG];
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-        grp[g] = (int64_t)blockIdx.x * NG + g;
-        if (grp[g] >= a.N32) grp[g] = a.N32 - 1;          // clamp; the store is masked
-    }
-    const uint16_t* xrow[TM];
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-        int64_t row = 32 * tm + t;
-        if (row >= a.M) row = a.M - 1;                    // repeat a valid token; never stored
-        xrow[tm] = a.Xh + row * a.ldxh + 32 * hh;
-    }
+    int64_t grp = (int64_t)blockIdx.x * NWC + wc;
+    const bool grp_ok = grp < a.N32;
+    if (!grp_ok) grp = a.N32 - 1;                         // clamp; the store is masked
+    int64_t trow = t;
+    if (trow >= a.M) trow = a.M - 1;                      // repeat a valid token; never stored
+    const uint16_t* xrow = a.Xh + trow * a.ldxh + 32 * hh;     // for the correction term (global reads)
 
-    f32x16 acc[TM][NG];
+    // staging: this wavefront's loads x = 0..XL-1 are cells j = uwave + NW x of 1 KiB of the stage;
+    // slot = 64 j + lane -> (16-byte column, row)
+    const uint16_t* st_row[XL];
+    int st_col[XL];
+    int st_dst[XL];
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
+    for (int x = 0; x < XL; ++x) {
+        const int j = uwave + NW * x;
+        const int slot = 64 * (j < NL ? j : 0) + lane;
+        int64_t row = slot & (R - 1);
+        if (row >= a.M) row = a.M - 1;
+        st_row[x] = a.Xh + row * a.ldxh;
+        st_col[x] = 8 * (slot >> LR);
+        st_dst[x] = (j < NL) ? slot * 16 : -1;
+    }
+    const int64_t kspan = (int64_t)NWK * kTileK;          // K range of one iteration
+    const int64_t NI = (a.KT + NWK - 1) / NWK;            // iterations, the same for every wavefront
+    const int64_t kcap = a.KT * kTileK - 8;               // last 16-byte column of a row
+    auto fetch_x = [&](int64_t it, u32x4 (&st)[XL]) {
+        const int64_t k0 = (it < NI ? it : NI - 1) * kspan;
 #pragma unroll
-        for (int g = 0; g < NG; ++g)
+        for (int x = 0; x < XL; ++x) {
+            // the last range may run past K_pad: those columns belong to tiles no wavefront
+            // computes; clamp them so the loads stay inside the row
+            int64_t col = k0 + st_col[x];
+            if (col > kcap) col = kcap;
+            if (st_dst[x] >= 0) st[x] = *reinterpret_cast<const u32x4*>(st_row[x] + col);
+        }
+    };
+    auto store_x = [&](const u32x4 (&st)[XL], int buf) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[tm][g][r] = 0.f;
+        for (int x = 0; x < XL; ++x)
+            if (st_dst[x] >= 0) *reinterpret_cast<u32x4*>(lds + buf * XT + st_dst[x]) = st[x];
+    };
+    // operand read: token row min(t, R-1), 16-byte column 32 wk + 8 c + 4 hh + s of the stage
+    const int rd_base = (((32 * wk + 4 * hh) << LR) + (t < R ? t : R - 1)) << 4;
 
-    // ---- main product: stream this wavefront's K tiles ------------------------------------
-    int64_t tile = wave;
-    if (tile < a.KT) {
-        WRec cur[NG];
-        XChunk xc[TM];
+    f32x16 acc;
 #pragma unroll
-        for (int g = 0; g < NG; ++g) cur[g] = load_wrec(a.Wt + (grp[g] * a.KT + tile) * kWRecordBytes, lane);
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+
+    // ---- main product ----------------------------------------------------------------------------
+    // per iteration: wait, barrier, stage activations of iteration+1, fetch weights of iteration+2,
+    // then the arithmetic of this iteration
+    {
+        auto tile_at = [&](int64_t it) {
+            int64_t tl = wk + NWK * it;
+            return tl < a.KT ? tl : a.KT - 1;                                // clamped re-read
+        };
+        const uint8_t* wrec = a.Wt + grp * a.KT * kWRecordBytes;
+        // Three weight records rotate through three register sets by name (the loop is unrolled by
+        // three); copying one set into another would make the wavefront wait for the newest load.
+        WRec wa, wb, wd;
+        {
+            u32x4 st[XL];
+            fetch_x(0, st);
+            wa = load_wrec(wrec + tile_at(0) * kWRecordBytes, lane);
+            wb = load_wrec(wrec + tile_at(1) * kWRecordBytes, lane);
+            store_x(st, 0);
+        }
+        auto step = [&](const WRec& cur, WRec& fill, int64_t it) {
+            const int buf = (int)(it & 1);
+            __syncthreads();                 // stage `it` is complete; buffer buf^1 is free again
+            u32x4 st[XL];
+            fetch_x(it + 1, st);
+            fill = load_wrec(wrec + tile_at(it + 2) * kWRecordBytes, lane);
+            if (wk + NWK * it < a.KT) {
+                const uint8_t* xs = lds + buf * XT + rd_base;
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) xc[tm] = load_xchunk(xrow[tm] + tile * kTileK);
-        for (; tile < a.KT; tile += NW) {
-            const bool more = tile + NW < a.KT;
-            const int64_t ntile = more ? tile + NW : tile;             // re-read on the last round
-            WRec nxt[NG];
-#pragma unroll
-            for (int g = 0; g < NG; ++g)
-                nxt[g] = load_wrec(a.Wt + (grp[g] * a.KT + ntile) * kWRecordBytes, lane);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                XChunk xn[TM];
-                const int64_t noff = (c < 3) ? tile * kTileK + 64 * (c + 1) : ntile * kTileK;
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) xn[tm] = load_xchunk(xrow[tm] + noff);
-#pragma unroll
-                for (int g = 0; g < NG; ++g) {
-                    const uint32_t ew = cur[g].e[c >> 1] >> (16 * (c & 1));
-                    const float sc0 = w_scale(ew & 0xFFu), sc1 = w_scale((ew >> 8) & 0xFFu);
+                for (int c = 0; c < 4; ++c) {
 #pragma unroll
                     for (int s = 0; s < 4; ++s) {
-                        const bf16x8 wv = unpack_w8(cur[g].c[c][s], s < 2 ? sc0 : sc1);
-#pragma unroll
-                        for (int tm = 0; tm < TM; ++tm) {
-                            Frag xf;
-                            xf.u = xc[tm].s[s];
-                            acc[tm][g] = mfma32(wv, xf.v, acc[tm][g]);
-                        }
+                        Frag xf;
+                        xf.u = *reinterpret_cast<const u32x4*>(xs + ((8 * c + s) << (LR + 4)));
+                        const uint32_t ew = cur.e[c >> 1] >> (16 * (c & 1) + 8 * (s >> 1));
+                        const bf16x8 wv = unpack_w8(cur.c[c][s], w_scale(ew & 0xFFu));
+                        acc = mfma32(wv, xf.v, acc);
                     }
                 }
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) xc[tm] = xn[tm];
             }
-#pragma unroll
-            for (int g = 0; g < NG; ++g) cur[g] = nxt[g];
+            store_x(st, buf ^ 1);            // waits for the activation loads only; `fill` stays in flight
+        };
+        for (int64_t it = 0; it < NI; it += 3) {
+            step(wa, wd, it);
+            if (it + 1 < NI) step(wb, wa, it + 1);
+            if (it + 2 < NI) step(wd, wb, it + 2);
         }
     }
 
-    // ---- rank-kp correction: 64-wide chunks of [T_hi | T_lo], spread over the wavefronts ----------
+    // ---- rank-kp correction: 64-wide chunks of [T_hi | T_lo], spread over the K slices ----------
     // Lane half hh owns rank blocks jb = 4 ch + 2 hh + {0, 1} of chunk ch, as in the main loop;
     // jb < kp16 is T_hi for ranks 16 jb.., otherwise T_lo for ranks 16 (jb - kp16)...
     const int nb2 = 2 * a.kp16;
     const int nchunks = (nb2 + 3) / 4;
-    for (int ch = (wave + NW - (int)(a.KT % NW)) % NW; ch < nchunks; ch += NW) {
+    for (int ch = wk; ch < nchunks; ch += NWK) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int jb = 4 * ch + 2 * hh + j;
             const bool live = jb < nb2;
             const bool is_lo = jb >= a.kp16;
             const int rb = live ? (is_lo ? jb - a.kp16 : jb) : 0;
-            Frag ta[TM][2];
+            Frag ta[2];
+            if (!live) {
+                ta[0].u = u32x4{0, 0, 0, 0};
+                ta[1].u = u32x4{0, 0, 0, 0};
+            } else if (a.S == 1) {
+                const uint16_t* src = xrow - 32 * hh + a.KT * kTileK + 16 * jb;
+                ta[0].u = *reinterpret_cast<const u32x4*>(src);
+                ta[1].u = *reinterpret_cast<const u32x4*>(src + 8);
+            } else {
+                float tv[16];
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                if (!live) {
-                    ta[tm][0].u = u32x4{0, 0, 0, 0};
-                    ta[tm][1].u = u32x4{0, 0, 0, 0};
-                } else if (a.S == 1) {
-                    const uint16_t* src = xrow[tm] - 32 * hh + a.KT * kTileK + 16 * jb;
-                    ta[tm][0].u = *reinterpret_cast<const u32x4*>(src);
-                    ta[tm][1].u = *reinterpret_cast<const u32x4*>(src + 8);
-                } else {
-                    int64_t row = 32 * tm + t;
-                    if (row >= a.M) row = a.M - 1;
-                    float tv[16];
+                for (int i = 0; i < 16; ++i) tv[i] = 0.f;
+                for (int sl = 0; sl < a.S; ++sl) {                      // fixed order over the K slices
+                    const float* src = a.Tpart + ((int64_t)sl * a.M + trow) * a.kp + 16 * rb;
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) tv[i] = 0.f;
-                    for (int s = 0; s < a.S; ++s) {                     // fixed order over the K slices
-                        const float* src = a.Tpart + ((int64_t)s * a.M + row) * a.kp + 16 * rb;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const f32x4 v = *reinterpret_cast<const f32x4*>(src + 4 * i);
-                            tv[4 * i] += v[0]; tv[4 * i + 1] += v[1]; tv[4 * i + 2] += v[2]; tv[4 * i + 3] += v[3];
-                        }
+                    for (int i = 0; i < 4; ++i) {
+                        const f32x4 v = *reinterpret_cast<const f32x4*>(src + 4 * i);
+                        tv[4 * i] += v[0]; tv[4 * i + 1] += v[1]; tv[4 * i + 2] += v[2]; tv[4 * i + 3] += v[3];
                     }
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const uint32_t hb = f32_bits(tv[i]) & 0xFFFF0000u;
-                        const float part = is_lo ? (tv[i] - f32_from_bits(hb)) : f32_from_bits(hb);
-                        tv[i] = f32_from_bits(f32_bits(part) & 0xFFFF0000u);
-                    }
-#pragma unroll
-                    for (int h = 0; h < 2; ++h)
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            ta[tm][h].u[i] = pack_bf16_exact(tv[8 * h + 2 * i], tv[8 * h + 2 * i + 1]);
                 }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const uint32_t hb = f32_bits(tv[i]) & 0xFFFF0000u;
+                    const float part = is_lo ? (tv[i] - f32_from_bits(hb)) : f32_from_bits(hb);
+                    tv[i] = f32_from_bits(f32_bits(part) & 0xFFFF0000u);
+                }
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        ta[h].u[i] = pack_bf16_exact(tv[8 * h + 2 * i], tv[8 * h + 2 * i + 1]);
             }
-#pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                u32x4 cw = u32x4{0, 0, 0, 0};
-                uint32_t eb = 0;
-                if (live) {
-                    const uint8_t* rec = a.Bt + (grp[g] * a.kp16 + rb) * kBRecordBytes;
-                    cw = *reinterpret_cast<const u32x4*>(rec + t * 16);
-                    eb = rec[512 + t];
-                }
-                Frag bf[2];
-                int8x16_to_frags(cw, h_scale(eb), bf[0], bf[1]);
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) {
-                    acc[tm][g] = mfma32(bf[0].v, ta[tm][0].v, acc[tm][g]);
-                    acc[tm][g] = mfma32(bf[1].v, ta[tm][1].v, acc[tm][g]);
-                }
+            u32x4 cw = u32x4{0, 0, 0, 0};
+            uint32_t eb = 0;
+            if (live) {
+                const uint8_t* rec = a.Bt + (grp * a.kp16 + rb) * kBRecordBytes;
+                cw = *reinterpret_cast<const u32x4*>(rec + t * 16);
+                eb = rec[512 + t];
             }
+            Frag bf[2];
+            int8x16_to_frags(cw, h_scale(eb), bf[0], bf[1]);
+            acc = mfma32(bf[0].v, ta[0].v, acc);
+            acc = mfma32(bf[1].v, ta[1].v, acc);
         }
     }
 
-    // ---- add the wavefronts in a fixed tree order; wavefront 0 stores ------------------------------
+    // ---- add the K slices of each column group in a fixed tree order; slice 0 stores ---------------
+    __syncthreads();                             // every wavefront is done with the staging buffers
+    auto red_at = [&](int k, int r4) {
+        return reinterpret_cast<f32x4*>(red + (((size_t)k * NWC + wc) * 64 + lane) * 16 + 4 * r4);
+    };
 #pragma unroll
-    for (int off = NW / 2; off >= 1; off >>= 1) {
-        if (wave >= off && wave < 2 * off) {
+    for (int off = NWK / 2; off >= 1; off >>= 1) {
+        if (wk >= off && wk < 2 * off) {
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int g = 0; g < NG; ++g)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4)
-                        *reinterpret_cast<f32x4*>(&red[wave - off][tm][g][lane][4 * r4]) =
-                            f32x4{acc[tm][g][4 * r4], acc[tm][g][4 * r4 + 1], acc[tm][g][4 * r4 + 2], acc[tm][g][4 * r4 + 3]};
+            for (int r4 = 0; r4 < 4; ++r4)
+                *red_at(wk - off, r4) = f32x4{acc[4 * r4], acc[4 * r4 + 1], acc[4 * r4 + 2], acc[4 * r4 + 3]};
         }
         __syncthreads();
-        if (wave < off) {
+        if (wk < off) {
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int g = 0; g < NG; ++g)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        const f32x4 o = *reinterpret_cast<const f32x4*>(&red[wave][tm][g][lane][4 * r4]);
-                        acc[tm][g][4 * r4] += o[0]; acc[tm][g][4 * r4 + 1] += o[1];
-                        acc[tm][g][4 * r4 + 2] += o[2]; acc[tm][g][4 * r4 + 3] += o[3];
-                    }
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const f32x4 o = *red_at(wk, r4);
+                acc[4 * r4] += o[0]; acc[4 * r4 + 1] += o[1]; acc[4 * r4 + 2] += o[2]; acc[4 * r4 + 3] += o[3];
+            }
         }
         __syncthreads();
     }
-    if (wave == 0) {
+    if (wk == 0 && grp_ok && t < a.M) {
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
-            const int64_t row = 32 * tm + t;
-            if (row >= a.M) continue;
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const int64_t n = grp * 32 + 8 * r4 + 4 * hh;              // this lane's 4 consecutive columns
+            float* dst = a.Y + (int64_t)t * a.ldy + n;
+            const f32x4 v = f32x4{acc[4 * r4], acc[4 * r4 + 1], acc[4 * r4 + 2], acc[4 * r4 + 3]};
+            if (n + 3 < a.N) {
+                *reinterpret_cast<f32x4*>(dst) = v;
+            } else {
 #pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                const int64_t cg = (int64_t)blockIdx.x * NG + g;
-                if (cg >= a.N32) continue;
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int64_t n = cg * 32 + 8 * r4 + 4 * hh;       // this lane's 4 consecutive columns
-                    float* dst = a.Y + row * a.ldy + n;
-                    const f32x4 v = f32x4{acc[tm][g][4 * r4], acc[tm][g][4 * r4 + 1], acc[tm][g][4 * r4 + 2], acc[tm][g][4 * r4 + 3]};
-                    if (n + 3 < a.N) {
-                        *reinterpret_cast<f32x4*>(dst) = v;
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            if (n + j < a.N) dst[j] = v[j];
-                    }
-                }
+                for (int j = 0; j < 4; ++j)
+                    if (n + j < a.N) dst[j] = v[j];
             }
         }
     }
 }
 
-int skinny_max_rows() { return 64; }
+int skinny_max_rows() { return 32; }
 
-template <int TM, int NG, int NW>
+template <int NWC, int NWK, int LR>
 static hipError_t launch_skinny_t(const SkinnyArgs& a, hipStream_t s) {
-    dim3 grid((unsigned)((a.N32 + NG - 1) / NG)), block(64 * NW);
-    hipLaunchKernelGGL((skinny_kernel<TM, NG, NW>), grid, block, 0, s, a);
+    constexpr int XT = NWK * (1 << LR) * 512;
+    constexpr int STAGING = 2 * XT;
+    constexpr int REDUCE = (NWK / 2) * NWC * 4096;
+    constexpr int LDS_BYTES = STAGING > REDUCE ? STAGING : REDUCE;
+    static_assert(LDS_BYTES <= 160 * 1024, "does not fit the 160 KB of LDS");
+    auto kern = skinny_kernel<NWC, NWK, LR>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((unsigned)((a.N32 + NWC - 1) / NWC)), block(64 * NWC * NWK);
+    hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, s, a);
     return hipGetLastError();
+}
+
+template <int NWC, int NWK>
+static hipError_t launch_skinny_rows(const SkinnyArgs& a, hipStream_t s) {
+    if (a.M <= 4) return launch_skinny_t<NWC, NWK, 2>(a, s);
+    if constexpr (NWK <= 8) {
+        if (a.M <= 16) return launch_skinny_t<NWC, NWK, 4>(a, s);
+    }
+    if constexpr (NWK <= 4) {
+        return launch_skinny_t<NWC, NWK, 5>(a, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_skinny(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
@@ -264,33 +298,29 @@ hipError_t launch_skinny(const Layer& L, int64_t M, const Workspace& ws, float* 
     SkinnyArgs a;
     a.Wt = L.Wt; a.Bt = L.Bt; a.Xh = ws.Xh; a.ldxh = ws.ldxh; a.Tpart = ws.Tpart; a.S = ws.S;
     a.Y = Y; a.ldy = ldy; a.M = M; a.N = L.N; a.KT = L.KT; a.N32 = L.N32; a.kp = L.kp; a.kp16 = L.kp16;
-    const int tm = (M > 32) ? 2 : 1;
-    // variant = 10 * NG + log2(NW) - 1 ... kept simple: 1 -> (NG 1, NW 4), 2 -> (1, 8), 3 -> (1, 16), 4 -> (2, 4).
-    // Automatic: one column group per workgroup; as many wavefronts as there are K tiles (up to 16)
-    // when the layer is too narrow to fill the chip with 4-wavefront workgroups.
+    // variant = 100 * NWC + NWK (column-group wavefronts x K slices per workgroup); 0 = automatic:
+    // wide layers share staged activations between many column groups, narrow layers split K
+    // further so that the chip still has enough loads in flight.  The staging buffers bound the
+    // K slices: 16 token rows allow 8, 32 rows allow 4.
     int v = variant;
-    if (v < 1 || v > 4) {
-        if (L.N32 >= 512) v = 1;
-        else if (L.N32 >= 256) v = (L.KT >= 8) ? 2 : 1;
-        else v = (L.KT >= 16) ? 3 : (L.KT >= 8 ? 2 : 1);
+    if (v == 0) {
+        if (L.N32 >= 512) v = 404;
+        else if (L.N32 >= 256) v = 204;
+        else v = (M <= 4) ? 116 : (M <= 16 ? 108 : 204);
     }
-#define LQER_SK(TM_, NG_, NW_) return launch_skinny_t<TM_, NG_, NW_>(a, s)
-    if (tm == 1) {
-        switch (v) {
-            case 1: LQER_SK(1, 1, 4);
-            case 2: LQER_SK(1, 1, 8);
-            case 3: LQER_SK(1, 1, 16);
-            default: LQER_SK(1, 2, 4);
-        }
-    } else {
-        switch (v) {
-            case 1: LQER_SK(2, 1, 4);
-            case 2: LQER_SK(2, 1, 8);
-            case 3: LQER_SK(2, 1, 16);
-            default: LQER_SK(2, 2, 4);
-        }
+    const int max_k = (M <= 4) ? 16 : (M <= 16 ? 8 : 4);
+    if (v % 100 > max_k) return hipErrorInvalidValue;
+    switch (v) {
+        case 802: return launch_skinny_rows<8, 2>(a, s);
+        case 404: return launch_skinny_rows<4, 4>(a, s);
+        case 402: return launch_skinny_rows<4, 2>(a, s);
+        case 208: return launch_skinny_rows<2, 8>(a, s);
+        case 204: return launch_skinny_rows<2, 4>(a, s);
+        case 116: return launch_skinny_rows<1, 16>(a, s);
+        case 108: return launch_skinny_rows<1, 8>(a, s);
+        case 104: return launch_skinny_rows<1, 4>(a, s);
+        default: return hipErrorInvalidValue;
     }
-#undef LQER_SK
 }
 
 }  // namespace lqer
