@@ -137,6 +137,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
             __syncthreads();                 // stage `it` is complete; buffer buf^1 is free again
             u32x4 st[XL];
             fetch_x(it + 1, st);
+            __builtin_amdgcn_sched_barrier(0);      // loads retire in order: activations stay ahead of weights
             fill = load_wrec(wrec + tile_at(it + 2) * kWRecordBytes, lane);
             if (wk + NWK * it < a.KT) {
                 const uint8_t* xs = lds + buf * XT + rd_base;

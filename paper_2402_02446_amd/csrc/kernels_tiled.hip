@@ -7,11 +7,13 @@
 // MFMA (the shape one wavefront per SIMD can keep close to the matrix pipe's peak).  The
 // contraction axis is walked in chunks of 64 = four MFMA steps; lane half hh owns blocks 2hh and
 // 2hh+1 of a chunk for every operand, so block scales never cross lanes.
-//   activations (bf16, exact dequantized X_q, then T_hi | T_lo): global -> LDS with the direct
-//       (no-register) 16-byte loads, into a ring of stages of XOR-swizzled 16-byte cells, then
-//       ds_read_b128 operands shared by the wavefronts of a row;
+//   activations (bf16, exact dequantized X_q, then T_hi | T_lo): global -> registers two chunks
+//       ahead -> a ring of four LDS stages of XOR-swizzled 16-byte cells -> ds_read_b128 operands
+//       shared by the wavefronts of a row;
 //   weights: each wavefront loads the packed MXINT4 records of its own columns straight into
-//       registers (fully coalesced 16-byte loads), one chunk ahead, and expands them there;
+//       registers (fully coalesced 16-byte loads), two chunks ahead, into four register sets used
+//       by name in turn (a copy between sets would force a wait on the newest load), and expands
+//       them there;
 //   the rank-kp correction is ceil(2 kp / 64) more chunks whose weight operand comes from B_k.
 // MFMA operands are swapped (weights first) so a lane ends up with runs of four consecutive
 // output columns of one token and stores each as one 16-byte write.
@@ -30,21 +32,19 @@ struct TiledArgs {
     int group_m;
 };
 
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
-typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
-
 template <int TM, int TN, int WR, int WC, int NS>
 __global__ __launch_bounds__(64 * WR * WC) void tiled_kernel(TiledArgs a) {
     constexpr int BM = 32 * TM * WR;
     constexpr int NW = WR * WC;
     constexpr int STAGE = BM * 128;                // bytes: BM rows x 64 bf16
-    constexpr int LPT = BM / (8 * NW);             // direct loads per lane per chunk (a load fills 8 rows)
-    static_assert(BM % (8 * NW) == 0, "loader must divide evenly");
+    constexpr int NT = 64 * NW;
+    constexpr int LPT = BM * 8 / NT;               // 16-byte cells each thread moves per chunk
+    static_assert((BM * 8) % NT == 0, "loader must divide evenly");
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction
     const int wr = wave / WC, wc = wave % WC;
     const int t = lane & 31, hh = lane >> 5;
 
@@ -64,36 +64,28 @@ __global__ __launch_bounds__(64 * WR * WC) void tiled_kernel(TiledArgs a) {
         tile_n = (lin % width) / gsize;
     }
     const int64_t m0 = (int64_t)tile_m * BM;
-    const int64_t g0 = ((int64_t)tile_n * WC + wc) * TN;       // first column group of this wavefront
-
-    // ---- activation loader ---------------------------------------------------------------------
-    // Load j of this wavefront fills LDS rows (j*NW + wave)*8 .. +7 of a stage: lane i lands in
-    // row i/8, physical cell i%8, so it fetches the logical cell (i%8) ^ ((row>>1)&7) of that row.
-    const uint16_t* ld_src[LPT];
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) {
-        const int row = (j * NW + wave) * 8 + (lane >> 3);
-        const int cell = (lane & 7) ^ ((row >> 1) & 7);
-        int64_t grow = m0 + row;
-        if (grow >= a.M) grow = a.M - 1;                       // repeat a valid token; never stored
-        ld_src[j] = a.Xh + grow * a.ldxh + 8 * cell;
-    }
+    // ---- activation loader: thread -> 16-byte cells of a stage -----------------------------------
+    // Cell j of this thread is row (tid >> 3) + j * (NT / 8), 16-byte column tid & 7.  Rows past M are
+    // read as they are (the workspace rows are padded to the tile height) and never stored.
+    constexpr int ROWS_PER_PASS = NT / 8;
+    const int ld_row0 = tid >> 3;
+    const uint16_t* ld_base = a.Xh + (m0 + ld_row0) * a.ldxh + 8 * (tid & 7);
+    const int64_t ld_stride = (int64_t)ROWS_PER_PASS * a.ldxh;           // elements between passes
+    // (row >> 1) & 7 is the same for every pass because ROWS_PER_PASS is a multiple of 16
+    static_assert(ROWS_PER_PASS % 16 == 0, "swizzle must not depend on the pass");
+    const int ld_dst0 = ld_row0 * 128 + (((tid & 7) ^ ((ld_row0 >> 1) & 7)) << 4);
     // ---- operand reader: in step s this lane reads logical cell 4 hh + s of its TM rows -----------
-    int rd_off[TM][4];
+    // row = (wr TM + tm) 32 + t, so the swizzle term depends on t only
+    int rd_off[4];
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-        const int row = (wr * TM + tm) * 32 + t;
-#pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) rd_off[tm][s4] = row * 128 + (((4 * hh + s4) ^ ((row >> 1) & 7)) << 4);
-    }
-    const uint8_t* wbase[TN];
-    int64_t grp[TN];
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-        grp[tn] = g0 + tn;
-        if (grp[tn] >= a.N32) grp[tn] = a.N32 - 1;             // clamp; the store is masked
-        wbase[tn] = a.Wt + grp[tn] * a.KT * kWRecordBytes + lane * 16;
-    }
+    for (int s4 = 0; s4 < 4; ++s4)
+        rd_off[s4] = (wr * TM * 32 + t) * 128 + (((4 * hh + s4) ^ ((t >> 1) & 7)) << 4);
+    const int64_t g0 = ((int64_t)tile_n * WC + wc) * TN;       // first column group of this wavefront
+    auto group_of = [&](int tn) {
+        const int64_t g = g0 + tn;
+        return g < a.N32 ? g : a.N32 - 1;                      // clamp; the store is masked
+    };
+    const int lane16 = lane * 16;
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -107,83 +99,110 @@ __global__ __launch_bounds__(64 * WR * WC) void tiled_kernel(TiledArgs a) {
     const int nb2 = 2 * a.kp16;
     const int tail_chunks = (nb2 + 3) / 4;
     const int64_t chunks = main_chunks + tail_chunks;
-    const int uwave = __builtin_amdgcn_readfirstlane(wave);
+    static_assert(NS == 4, "stage and register-set indices below assume rings of four");
 
-    // The ring has NS = 4 stages and a K tile has 4 chunks, so chunk ch always uses stage ch % 4.
-    auto issue_stage = [&](int64_t ch, int stage) {
+    struct WSet {                // packed codes of one chunk for this wavefront's TN column groups
+        u32x4 c[TN];
+    };
+    struct ESet {                // exponent bytes of one K tile (four chunks) for the same groups
+        u32x2 e[TN];
+    };
+    auto load_wset = [&](WSet& w, int64_t ch) {
+        const int64_t tile = ch >> 2;
+        const int cc = (int)(ch & 3);
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const uint8_t* rec = a.Wt + (group_of(tn) * a.KT + tile) * kWRecordBytes;   // wave-uniform
+            w.c[tn] = *reinterpret_cast<const u32x4*>(rec + cc * 1024 + lane16);
+        }
+    };
+    auto load_eset = [&](ESet& x, int64_t tile) {
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const uint8_t* rec = a.Wt + (group_of(tn) * a.KT + tile) * kWRecordBytes;
+            x.e[tn] = *reinterpret_cast<const u32x2*>(rec + kWExpOffset + (lane16 >> 1));
+        }
+    };
+    auto fetch_x = [&](u32x4 (&st)[LPT], int64_t ch) {
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) st[j] = *reinterpret_cast<const u32x4*>(ld_base + j * ld_stride + ch * 64);
+    };
+    auto store_x = [&](const u32x4 (&st)[LPT], int stage) {
 #pragma unroll
         for (int j = 0; j < LPT; ++j)
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ld_src[j] + ch * 64),
-                                             (lds_ptr_t)(lds + stage * STAGE + (j * NW + uwave) * 1024), 16, 0, 0);
+            *reinterpret_cast<u32x4*>(lds + stage * STAGE + ld_dst0 + j * ROWS_PER_PASS * 128) = st[j];
     };
-    // Outstanding-load budget when waiting for chunk ch's stage: everything issued after it, i.e.
-    // the weight loads and stage loads of the NS-2 iterations in between (weights are issued
-    // before the stage loads of the same iteration).
-    constexpr int kSteadyVm = (NS - 2) * (LPT + TN);
-    static_assert(NS == 4, "stage indices below assume a ring of four");
-    static_assert(kSteadyVm < 64, "vmcnt field is 6 bits");
-    auto wait_stage = [&](bool steady) {
-        if (steady) __builtin_amdgcn_s_waitcnt(0x0F70 | (kSteadyVm & 15) | ((kSteadyVm >> 4) << 14));
-        else __builtin_amdgcn_s_waitcnt(0x0F70);
-    };
-
-    // prologue: stages for chunks 0 .. NS-2; first chunk of weights
-    u32x4 wcur[TN], wnext[TN];   // packed codes of the current / next chunk
-    u32x2 wexp[TN];              // exponent bytes of the current tile
+    // one 64-wide chunk of the main product: c = chunk index within its K tile = stage = register set
+    auto mma_chunk = [&](const WSet& w, const ESet& x, int c) {
+        const uint8_t* stage = lds + c * STAGE;
+        float sc[TN][2];
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-        wcur[tn] = *reinterpret_cast<const u32x4*>(wbase[tn]);
-        wexp[tn] = *reinterpret_cast<const u32x2*>(wbase[tn] + kWExpOffset - lane * 8);
-        wnext[tn] = wcur[tn];
-    }
+        for (int tn = 0; tn < TN; ++tn) {
+            const uint32_t ew = x.e[tn][c >> 1] >> (16 * (c & 1));
+            sc[tn][0] = w_scale(ew & 0xFFu);
+            sc[tn][1] = w_scale((ew >> 8) & 0xFFu);
+        }
 #pragma unroll
-    for (int p = 0; p < NS - 1; ++p)
-        if (p < chunks) issue_stage(p, p);
-
-    // ---- main product -----------------------------------------------------------------------------
-    for (int64_t tile = 0; tile < a.KT; ++tile) {
+        for (int s4 = 0; s4 < 4; ++s4) {
+            Frag xa[TM];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int64_t ch = tile * 4 + c;
-            // chunk ch's stage has landed (this wavefront's share) ...
-            wait_stage(ch >= NS - 2 && ch + NS - 2 < chunks && ch < main_chunks);
-            __syncthreads();                                   // ... and everybody else's; stage (ch-1)%4 is free
-            if (ch + 1 < main_chunks) {
-                const int64_t nt = (ch + 1) >> 2;
-                constexpr int kNextC[4] = {1, 2, 3, 0};
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    wnext[tn] = *reinterpret_cast<const u32x4*>(wbase[tn] + nt * kWRecordBytes + kNextC[c] * 1024);
-            }
-            if (ch + NS - 1 < chunks) issue_stage(ch + NS - 1, (c + NS - 1) & 3);
-            const uint8_t* stage = lds + c * STAGE;
-            float sc[TN][2];
+            for (int tm = 0; tm < TM; ++tm)
+                xa[tm].u = *reinterpret_cast<const u32x4*>(stage + rd_off[s4] + tm * 4096);
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
-                const uint32_t ew = wexp[tn][c >> 1] >> (16 * (c & 1));
-                sc[tn][0] = w_scale(ew & 0xFFu);
-                sc[tn][1] = w_scale((ew >> 8) & 0xFFu);
+                const bf16x8 wv = unpack_w8(w.c[tn][s4], sc[tn][s4 >> 1]);
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) acc[tm][tn] = mfma32(wv, xa[tm].v, acc[tm][tn]);
             }
-#pragma unroll
-            for (int s4 = 0; s4 < 4; ++s4) {
-                Frag xa[TM];
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
-                    xa[tm].u = *reinterpret_cast<const u32x4*>(stage + rd_off[tm][s4]);
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) {
-                    const bf16x8 wv = unpack_w8(wcur[tn][s4], sc[tn][s4 >> 1]);
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm) acc[tm][tn] = mfma32(wv, xa[tm].v, acc[tm][tn]);
-                }
-            }
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) wcur[tn] = wnext[tn];
-            if (c == 3 && tile + 1 < a.KT) {
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    wexp[tn] = *reinterpret_cast<const u32x2*>(wbase[tn] + (tile + 1) * kWRecordBytes + kWExpOffset - lane * 8);
-            }
+        }
+    };
+
+    // prologue: activations of chunks 0 and 1 into stages 0 and 1, weights of chunks 0 and 1
+    WSet w0, w1, w2, w3;
+    ESet ea, eb;
+    {
+        u32x4 st[LPT];
+        fetch_x(st, 0);
+        load_eset(ea, 0);
+        load_wset(w0, 0);
+        store_x(st, 0);
+        if (chunks > 1) {
+            fetch_x(st, 1);
+            if (main_chunks > 1) load_wset(w1, 1);
+            store_x(st, 1);
+        }
+    }
+
+    // ---- main product -----------------------------------------------------------------------------
+    // chunk ch: barrier; fetch activations and weights of chunk ch+2; arithmetic of chunk ch;
+    // write the fetched activations into stage (ch+2)%4, which was last read two barriers ago.
+    // Exponent bytes of the next tile are fetched during the second chunk of a tile.
+    // Every load below is issued unconditionally, with its index clamped at the end of the range:
+    // a load inside a branch would make the compiler's wait counts assume the worst case and the
+    // LDS write at the end of the chunk would wait for the newest weights as well.
+    const int64_t last_chunk = chunks - 1, last_main = main_chunks - 1, last_tile = a.KT - 1;
+    auto step = [&](const WSet& cur, const ESet& ecur, WSet& fill, ESet& enext, int64_t ch, int c) {
+        __syncthreads();
+        u32x4 st[LPT];
+        fetch_x(st, ch + 2 < last_chunk ? ch + 2 : last_chunk);
+        // loads retire in order: keep the activation loads ahead of the weight loads, so that the
+        // LDS write at the end of this chunk does not have to wait for the weights of chunk ch+2
+        __builtin_amdgcn_sched_barrier(0);
+        load_wset(fill, ch + 2 < last_main ? ch + 2 : last_main);
+        if (c == 1) load_eset(enext, (ch >> 2) + 1 < last_tile ? (ch >> 2) + 1 : last_tile);
+        mma_chunk(cur, ecur, c);
+        store_x(st, (c + 2) & 3);      // stage (ch+2)%4: free since two barriers ago, also for a clamped re-write
+    };
+    for (int64_t tile = 0; tile < a.KT; tile += 2) {
+        step(w0, ea, w2, eb, tile * 4 + 0, 0);
+        step(w1, ea, w3, eb, tile * 4 + 1, 1);
+        step(w2, ea, w0, eb, tile * 4 + 2, 2);
+        step(w3, ea, w1, eb, tile * 4 + 3, 3);
+        if (tile + 1 < a.KT) {
+            step(w0, eb, w2, ea, tile * 4 + 4, 0);
+            step(w1, eb, w3, ea, tile * 4 + 5, 1);
+            step(w2, eb, w0, ea, tile * 4 + 6, 2);
+            step(w3, eb, w1, ea, tile * 4 + 7, 3);
         }
     }
 
@@ -191,9 +210,10 @@ __global__ __launch_bounds__(64 * WR * WC) void tiled_kernel(TiledArgs a) {
     // lane half hh owns rank blocks jb = 4 cc + 2 hh + {0, 1} of tail chunk cc
     for (int cc = 0; cc < tail_chunks; ++cc) {
         const int64_t ch = main_chunks + cc;
-        wait_stage(false);
         __syncthreads();
-        if (ch + NS - 1 < chunks) issue_stage(ch + NS - 1, (cc + NS - 1) & 3);
+        u32x4 st[LPT];
+        const bool more_x = ch + 2 < chunks;
+        if (more_x) fetch_x(st, ch + 2);
         const uint8_t* stage = lds + (cc & 3) * STAGE;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -206,7 +226,7 @@ __global__ __launch_bounds__(64 * WR * WC) void tiled_kernel(TiledArgs a) {
                 u32x4 cw = u32x4{0, 0, 0, 0};
                 uint32_t eb = 0;
                 if (live) {
-                    const uint8_t* rec = a.Bt + (grp[tn] * a.kp16 + rb) * kBRecordBytes;
+                    const uint8_t* rec = a.Bt + (group_of(tn) * a.kp16 + rb) * kBRecordBytes;
                     cw = *reinterpret_cast<const u32x4*>(rec + t * 16);
                     eb = rec[512 + t];
                 }
@@ -217,13 +237,14 @@ __global__ __launch_bounds__(64 * WR * WC) void tiled_kernel(TiledArgs a) {
                 Frag xa[TM];
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
-                    xa[tm].u = *reinterpret_cast<const u32x4*>(stage + rd_off[tm][2 * j + h]);
+                    xa[tm].u = *reinterpret_cast<const u32x4*>(stage + rd_off[2 * j + h] + tm * 4096);
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
                     for (int tm = 0; tm < TM; ++tm) acc[tm][tn] = mfma32(bf[tn][h].v, xa[tm].v, acc[tm][tn]);
             }
         }
+        if (more_x) store_x(st, (cc + 2) & 3);
     }
 
     // ---- store: lane (t, hh) holds columns 8 r4 + 4 hh .. + 3 of token t for every MFMA tile ------
@@ -280,17 +301,31 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
     a.M = M; a.N = L.N; a.KT = L.KT; a.N32 = L.N32; a.kp16 = L.kp16;
     a.grid_m = a.grid_n = 0; a.group_m = 8;
     if (variant == 0) {
-        // 256x256 tiles unless they leave compute units idle or the last round mostly empty
-        const int64_t t256 = ((M + 255) / 256) * ((L.N + 255) / 256);
-        const int64_t rounds = (t256 + 255) / 256;
-        const double eff = (double)t256 / (double)(rounds * 256);
-        variant = (eff >= 0.85) ? 1 : 2;
+        // Pick the tile shape with the lowest estimated time: whole rounds of workgroups over the
+        // 256 compute units, times the tile area, over the rate that shape sustains when the chip
+        // is full (TFLOP/s measured on an 8192 x 28672 layer at M = 4096).
+        struct Shape { int id, bm, bn, per_cu; double rate; };
+        static const Shape shapes[] = {
+            {1, 256, 256, 1, 1140.0}, {3, 128, 256, 1, 1076.0}, {4, 128, 128, 2, 1058.0},
+            {6, 256, 128, 1, 1009.0}, {7, 128, 512, 1, 1296.0},
+        };
+        double best = 0.0;
+        for (const Shape& sh : shapes) {
+            const int64_t tiles = ((M + sh.bm - 1) / sh.bm) * ((L.N + sh.bn - 1) / sh.bn);
+            const int64_t slots = 256 * (int64_t)sh.per_cu;
+            const int64_t rounds = (tiles + slots - 1) / slots;
+            const double t = (double)rounds * sh.per_cu * sh.bm * sh.bn / sh.rate;
+            if (variant == 0 || t < best) { best = t; variant = sh.id; }
+        }
     }
     switch (variant) {
         case 1: return launch_tiled_t<4, 4, 2, 2, 4>(a, M, s);      // 256 x 256
         case 2: return launch_tiled_t<4, 2, 2, 2, 4>(a, M, s);      // 256 x 128
         case 3: return launch_tiled_t<2, 4, 2, 2, 4>(a, M, s);      // 128 x 256
         case 4: return launch_tiled_t<2, 2, 2, 2, 4>(a, M, s);      // 128 x 128
+        case 5: return launch_tiled_t<2, 4, 4, 2, 4>(a, M, s);      // 256 x 256, eight wavefronts
+        case 6: return launch_tiled_t<2, 2, 4, 2, 4>(a, M, s);      // 256 x 128, eight wavefronts
+        case 7: return launch_tiled_t<2, 4, 2, 4, 4>(a, M, s);      // 128 x 512, eight wavefronts
         default: return hipErrorInvalidValue;
     }
 }

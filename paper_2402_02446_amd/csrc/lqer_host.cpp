@@ -217,7 +217,9 @@ static Workspace plan_workspace(const Layer& L, int64_t M, int path, void* base)
     Workspace ws;
     ws.ldxh = L.KT * kTileK + round_up(2 * (int64_t)L.kp, 64);
     ws.S = prep_slices(L, M, path);
-    const size_t xh_bytes = (size_t)round_up(M * ws.ldxh * 2, 256);
+    // the tiled kernel reads whole 256-row tiles of Xh (rows past M hold whatever was there)
+    const int64_t xh_rows = (path == 2) ? round_up(M, 256) : M;
+    const size_t xh_bytes = (size_t)round_up(xh_rows * ws.ldxh * 2, 256);
     const size_t tp_bytes = (ws.S > 1) ? (size_t)round_up((int64_t)ws.S * M * L.kp * 4, 256) : 0;
     ws.Xh = (uint16_t*)base;
     ws.Tpart = (ws.S > 1) ? (float*)((uint8_t*)base + xh_bytes) : nullptr;
