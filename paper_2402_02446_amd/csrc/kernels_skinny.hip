@@ -19,7 +19,7 @@
 // and feeds them to the 32x32x16 bf16 MFMA against the activations (tokens beyond M repeat the
 // last one and are never stored); products are exact, accumulation is fp32.  The rank-kp
 // correction is 2*kp further "K columns": T_hi and T_lo against B_k's codes.  The NWK partial sums
-// of a column group are added through LDS in a fixed tree order.
+// of a column group are added through LDS in slice order.
 #include "lqer_internal.h"
 #include "mx_device.h"
 
@@ -56,8 +56,11 @@ __global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
     constexpr int XT = NWK * R * 512;                // bytes of one stage: R rows x NWK tiles of bf16
     constexpr int NL = XT / 1024;                    // direct loads (1 KiB each) per stage
     constexpr int XL = (NL + NW - 1) / NW;           // ... per wavefront
+    constexpr int kTBytes = 32 * 128 * 2;            // T_hi | T_lo of up to 32 tokens x 64 ranks, bf16
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
-    float* red = reinterpret_cast<float*>(lds);      // reused after the main loop: [NWK/2][NWC][64][16]
+    uint16_t* tlds = reinterpret_cast<uint16_t*>(lds);                 // [32][2 kp] bf16, kept all along
+    uint8_t* xlds = lds + kTBytes;                                     // the two activation stages
+    float* red = reinterpret_cast<float*>(lds + kTBytes);              // reused after the main loop: [NWK-1][NWC][64][16]
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -104,7 +107,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
     auto store_x = [&](const u32x4 (&st)[XL], int buf) {
 #pragma unroll
         for (int x = 0; x < XL; ++x)
-            if (st_dst[x] >= 0) *reinterpret_cast<u32x4*>(lds + buf * XT + st_dst[x]) = st[x];
+            if (st_dst[x] >= 0) *reinterpret_cast<u32x4*>(xlds + buf * XT + st_dst[x]) = st[x];
     };
     // operand read: token row min(t, R-1), 16-byte column 32 wk + 8 c + 4 hh + s of the stage
     const int rd_base = (((32 * wk + 4 * hh) << LR) + (t < R ? t : R - 1)) << 4;
@@ -113,9 +116,82 @@ __global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 
+    // ---- rank-kp correction, part 1: fetch its operands first ---------------------------------------
+    // The correction is 2 kp more "K columns" in 64-wide chunks of [T_hi | T_lo]; chunk ch belongs to
+    // K slice ch.  Lane half hh owns rank blocks jb = 4 ch + 2 hh + {0, 1}: jb < kp16 is T_hi for
+    // ranks 16 jb.., otherwise T_lo for ranks 16 (jb - kp16)...  Its loads are issued before
+    // anything else so that their latency hides behind the first weight records.
+    const int nb2 = 2 * a.kp16;
+    const int nchunks = (nb2 + 3) / 4;
+    const bool has_tail = wk < nchunks;              // NWK >= 2 >= nchunks: at most one chunk each
+    u32x4 tail_cw[2] = {u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
+    uint32_t tail_eb[2] = {0, 0};
+    bool tail_live[2] = {false, false};
+    int tail_jb[2] = {0, 0};
+    if (has_tail) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int jb = 4 * wk + 2 * hh + j;
+            tail_jb[j] = jb;
+            tail_live[j] = jb < nb2;
+            if (tail_live[j]) {
+                const int rb = jb >= a.kp16 ? jb - a.kp16 : jb;
+                const uint8_t* rec = a.Bt + (grp * a.kp16 + rb) * kBRecordBytes;
+                tail_cw[j] = *reinterpret_cast<const u32x4*>(rec + t * 16);
+                tail_eb[j] = rec[512 + t];
+            }
+        }
+    }
+    // T itself: when the projection kernel left S (<= 8) partial sums, the whole workgroup adds them
+    // in slice order and leaves T_hi | T_lo as bf16 in LDS.  One item = 4 consecutive ranks of a
+    // token; a thread owns at most TI items.  The loads are issued here, the sums are formed after
+    // the first weight loads have been issued (so those stay in flight meanwhile).
+    constexpr int TI = (32 * 16 + NW * 64 - 1) / (NW * 64);
+    constexpr int SMAX = 8;
+    f32x4 tpart[TI][SMAX];
+    const int t_rows = a.M < 32 ? (int)a.M : 32;
+    const int kp4 = a.kp >> 2;
+    const int t_items = (a.S > 1) ? t_rows * kp4 : 0;
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+        const int item = threadIdx.x + i * NW * 64;
+        const int it2 = item < t_items ? item : 0;
+        const int row = kp4 ? it2 / kp4 : 0, r4 = it2 - row * kp4;
+#pragma unroll
+        for (int sl = 0; sl < SMAX; ++sl) {
+            tpart[i][sl] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (item < t_items && sl < a.S)
+                tpart[i][sl] = *reinterpret_cast<const f32x4*>(a.Tpart + ((int64_t)sl * a.M + row) * a.kp + 4 * r4);
+        }
+    }
+    auto finish_t = [&]() {
+#pragma unroll
+        for (int i = 0; i < TI; ++i) {
+            const int item = threadIdx.x + i * NW * 64;
+            if (item >= t_items) continue;
+            const int row = item / kp4, r4 = item - row * kp4;
+            f32x4 sum = tpart[i][0];
+#pragma unroll
+            for (int sl = 1; sl < SMAX; ++sl) {
+                sum[0] += tpart[i][sl][0]; sum[1] += tpart[i][sl][1];
+                sum[2] += tpart[i][sl][2]; sum[3] += tpart[i][sl][3];
+            }
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t hb = f32_bits(sum[e]) & 0xFFFF0000u;
+                hi[e] = hb >> 16;
+                lo[e] = f32_bits(sum[e] - f32_from_bits(hb)) >> 16;
+            }
+            uint16_t* dst = tlds + row * 2 * a.kp + 4 * r4;
+            *reinterpret_cast<u32x2*>(dst) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+            *reinterpret_cast<u32x2*>(dst + a.kp) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+        }
+    };
+
     // ---- main product ----------------------------------------------------------------------------
-    // per iteration: wait, barrier, stage activations of iteration+1, fetch weights of iteration+2,
-    // then the arithmetic of this iteration
+    // per iteration: barrier, fetch activations of iteration+1, fetch weights of iteration+2,
+    // the arithmetic of this iteration, then write the fetched activations to LDS
     {
         auto tile_at = [&](int64_t it) {
             int64_t tl = wk + NWK * it;
@@ -130,17 +206,12 @@ __global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
             fetch_x(0, st);
             wa = load_wrec(wrec + tile_at(0) * kWRecordBytes, lane);
             wb = load_wrec(wrec + tile_at(1) * kWRecordBytes, lane);
+            finish_t();
             store_x(st, 0);
         }
-        auto step = [&](const WRec& cur, WRec& fill, int64_t it) {
-            const int buf = (int)(it & 1);
-            __syncthreads();                 // stage `it` is complete; buffer buf^1 is free again
-            u32x4 st[XL];
-            fetch_x(it + 1, st);
-            __builtin_amdgcn_sched_barrier(0);      // loads retire in order: activations stay ahead of weights
-            fill = load_wrec(wrec + tile_at(it + 2) * kWRecordBytes, lane);
+        auto mma_tile = [&](const WRec& cur, int64_t it) {
             if (wk + NWK * it < a.KT) {
-                const uint8_t* xs = lds + buf * XT + rd_base;
+                const uint8_t* xs = xlds + (int)(it & 1) * XT + rd_base;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
 #pragma unroll
@@ -153,94 +224,86 @@ __global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
                     }
                 }
             }
-            store_x(st, buf ^ 1);            // waits for the activation loads only; `fill` stays in flight
         };
-        for (int64_t it = 0; it < NI; it += 3) {
+        // All loads of a full step are unconditional (indices clamped): a load inside a branch would
+        // make the compiler's wait counts assume the worst case.  The last iteration is peeled off
+        // instead and fetches nothing.
+        auto step = [&](const WRec& cur, WRec& fill, int64_t it) {
+            __syncthreads();                 // stage `it` is complete; the other buffer is free again
+            u32x4 st[XL];
+            fetch_x(it + 1, st);
+            __builtin_amdgcn_sched_barrier(0);      // loads retire in order: activations stay ahead of weights
+            fill = load_wrec(wrec + tile_at(it + 2) * kWRecordBytes, lane);
+            mma_tile(cur, it);
+            store_x(st, (int)((it + 1) & 1));    // waits for the activation loads only; `fill` stays in flight
+        };
+        auto last_step = [&](const WRec& cur, int64_t it) {
+            __syncthreads();
+            mma_tile(cur, it);
+        };
+        int64_t it = 0;
+        for (; it + 3 < NI; it += 3) {
             step(wa, wd, it);
-            if (it + 1 < NI) step(wb, wa, it + 1);
-            if (it + 2 < NI) step(wd, wb, it + 2);
+            step(wb, wa, it + 1);
+            step(wd, wb, it + 2);
+        }
+        // one to three iterations remain; the record of iteration it+k sits in set (wa, wb, wd)[k]
+        if (it + 1 == NI) {
+            last_step(wa, it);
+        } else if (it + 2 == NI) {
+            step(wa, wd, it);
+            last_step(wb, it + 1);
+        } else {
+            step(wa, wd, it);
+            step(wb, wa, it + 1);
+            last_step(wd, it + 2);
         }
     }
 
-    // ---- rank-kp correction: 64-wide chunks of [T_hi | T_lo], spread over the K slices ----------
-    // Lane half hh owns rank blocks jb = 4 ch + 2 hh + {0, 1} of chunk ch, as in the main loop;
-    // jb < kp16 is T_hi for ranks 16 jb.., otherwise T_lo for ranks 16 (jb - kp16)...
-    const int nb2 = 2 * a.kp16;
-    const int nchunks = (nb2 + 3) / 4;
-    for (int ch = wk; ch < nchunks; ch += NWK) {
+    // ---- rank-kp correction, part 2: the arithmetic ---------------------------------------------------
+    if (has_tail) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int jb = 4 * ch + 2 * hh + j;
-            const bool live = jb < nb2;
-            const bool is_lo = jb >= a.kp16;
-            const int rb = live ? (is_lo ? jb - a.kp16 : jb) : 0;
             Frag ta[2];
-            if (!live) {
-                ta[0].u = u32x4{0, 0, 0, 0};
-                ta[1].u = u32x4{0, 0, 0, 0};
-            } else if (a.S == 1) {
-                const uint16_t* src = xrow - 32 * hh + a.KT * kTileK + 16 * jb;
-                ta[0].u = *reinterpret_cast<const u32x4*>(src);
-                ta[1].u = *reinterpret_cast<const u32x4*>(src + 8);
-            } else {
-                float tv[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) tv[i] = 0.f;
-                for (int sl = 0; sl < a.S; ++sl) {                      // fixed order over the K slices
-                    const float* src = a.Tpart + ((int64_t)sl * a.M + trow) * a.kp + 16 * rb;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const f32x4 v = *reinterpret_cast<const f32x4*>(src + 4 * i);
-                        tv[4 * i] += v[0]; tv[4 * i + 1] += v[1]; tv[4 * i + 2] += v[2]; tv[4 * i + 3] += v[3];
-                    }
+            ta[0].u = u32x4{0, 0, 0, 0};
+            ta[1].u = u32x4{0, 0, 0, 0};
+            if (tail_live[j]) {
+                if (a.S == 1) {                  // T was final: it sits behind the activations of the row
+                    const uint16_t* src = xrow - 32 * hh + a.KT * kTileK + 16 * tail_jb[j];
+                    ta[0].u = *reinterpret_cast<const u32x4*>(src);
+                    ta[1].u = *reinterpret_cast<const u32x4*>(src + 8);
+                } else {
+                    const uint16_t* src = tlds + (int)trow * 2 * a.kp + 16 * tail_jb[j];
+                    ta[0].u = *reinterpret_cast<const u32x4*>(src);
+                    ta[1].u = *reinterpret_cast<const u32x4*>(src + 8);
                 }
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const uint32_t hb = f32_bits(tv[i]) & 0xFFFF0000u;
-                    const float part = is_lo ? (tv[i] - f32_from_bits(hb)) : f32_from_bits(hb);
-                    tv[i] = f32_from_bits(f32_bits(part) & 0xFFFF0000u);
-                }
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        ta[h].u[i] = pack_bf16_exact(tv[8 * h + 2 * i], tv[8 * h + 2 * i + 1]);
-            }
-            u32x4 cw = u32x4{0, 0, 0, 0};
-            uint32_t eb = 0;
-            if (live) {
-                const uint8_t* rec = a.Bt + (grp * a.kp16 + rb) * kBRecordBytes;
-                cw = *reinterpret_cast<const u32x4*>(rec + t * 16);
-                eb = rec[512 + t];
             }
             Frag bf[2];
-            int8x16_to_frags(cw, h_scale(eb), bf[0], bf[1]);
+            int8x16_to_frags(tail_cw[j], h_scale(tail_eb[j]), bf[0], bf[1]);
             acc = mfma32(bf[0].v, ta[0].v, acc);
             acc = mfma32(bf[1].v, ta[1].v, acc);
         }
     }
 
-    // ---- add the K slices of each column group in a fixed tree order; slice 0 stores ---------------
+    // ---- add the K slices of each column group in slice order; slice 0 stores -----------------------
     __syncthreads();                             // every wavefront is done with the staging buffers
     auto red_at = [&](int k, int r4) {
         return reinterpret_cast<f32x4*>(red + (((size_t)k * NWC + wc) * 64 + lane) * 16 + 4 * r4);
     };
+    if (wk > 0) {
 #pragma unroll
-    for (int off = NWK / 2; off >= 1; off >>= 1) {
-        if (wk >= off && wk < 2 * off) {
+        for (int r4 = 0; r4 < 4; ++r4)
+            *red_at(wk - 1, r4) = f32x4{acc[4 * r4], acc[4 * r4 + 1], acc[4 * r4 + 2], acc[4 * r4 + 3]};
+    }
+    __syncthreads();
+    if (wk == 0) {
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4)
-                *red_at(wk - off, r4) = f32x4{acc[4 * r4], acc[4 * r4 + 1], acc[4 * r4 + 2], acc[4 * r4 + 3]};
-        }
-        __syncthreads();
-        if (wk < off) {
+        for (int k = 0; k < NWK - 1; ++k)
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
-                const f32x4 o = *red_at(wk, r4);
+                const f32x4 o = *red_at(k, r4);
                 acc[4 * r4] += o[0]; acc[4 * r4 + 1] += o[1]; acc[4 * r4 + 2] += o[2]; acc[4 * r4 + 3] += o[3];
             }
-        }
-        __syncthreads();
     }
     if (wk == 0 && grp_ok && t < a.M) {
 #pragma unroll
@@ -265,8 +328,8 @@ template <int NWC, int NWK, int LR>
 static hipError_t launch_skinny_t(const SkinnyArgs& a, hipStream_t s) {
     constexpr int XT = NWK * (1 << LR) * 512;
     constexpr int STAGING = 2 * XT;
-    constexpr int REDUCE = (NWK / 2) * NWC * 4096;
-    constexpr int LDS_BYTES = STAGING > REDUCE ? STAGING : REDUCE;
+    constexpr int REDUCE = (NWK - 1) * NWC * 4096;
+    constexpr int LDS_BYTES = 32 * 128 * 2 + (STAGING > REDUCE ? STAGING : REDUCE);
     static_assert(LDS_BYTES <= 160 * 1024, "does not fit the 160 KB of LDS");
     auto kern = skinny_kernel<NWC, NWK, LR>;
     static bool attr_set = false;
@@ -307,7 +370,7 @@ hipError_t launch_skinny(const Layer& L, int64_t M, const Workspace& ws, float* 
     if (v == 0) {
         if (L.N32 >= 512) v = 404;
         else if (L.N32 >= 256) v = 204;
-        else v = (M <= 4) ? 116 : (M <= 16 ? 108 : 204);
+        else v = (M <= 4) ? 108 : (M <= 16 ? 204 : 104);
     }
     const int max_k = (M <= 4) ? 16 : (M <= 16 ? 8 : 4);
     if (v % 100 > max_k) return hipErrorInvalidValue;
