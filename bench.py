@@ -175,12 +175,53 @@ def cpu_baseline(ctx, M, K, N, kp, budget_s=12.0):
             "gpu_vs_oracle_rel_frobenius": err}
 
 
+PMC_COPY_BYTES = 1 << 30
+
+
+def pmc_probe(rng):
+    """Workload for the two `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE): a plain copy of
+    known size (the calibration of the counter) followed by the headline ring."""
+    import torch
+    from paper_2402_02446_amd import binding, synth
+    src = torch.ones(PMC_COPY_BYTES // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.add(src, 1.0, out=dst)          # one elementwise kernel: reads and writes PMC_COPY_BYTES
+    torch.cuda.synchronize()
+    M, K, N, k = 16, 4096, 4096, 32
+    layers, _ = make_ring(rng, K, N, k, 1.25 * LLC_BYTES)
+    ch = synth.gen_outlier_channels(rng, K, max(1, round(0.01 * K)))
+    X = torch.from_numpy(synth.gen_activations(rng, M, K, ch, 50.0)).cuda()
+    Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    for rep in range(3):
+        for l in layers:
+            binding.lqer_linear_forward(l, X, Y=Y)
+    torch.cuda.synchronize()
+    print("pmc-probe done: copy of %d bytes x3, %d-layer ring x3" % (PMC_COPY_BYTES, len(layers)))
+
+
+def read_pmc_traffic(kernel):
+    """Bytes per launch of `kernel` from profiles/pmc_traffic.txt (lines `key value`), or None."""
+    path = os.path.join(ROOT, "profiles", "pmc_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 2 and parts[0] == kernel + ".traffic_bytes_per_launch":
+                    return float(parts[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--cases", default="all", choices=["headline", "all"])
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="run a plain 1 GiB copy and the headline ring a few times, for rocprofv3 --pmc runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (the layer's sharding "
@@ -193,6 +234,10 @@ def main():
     from paper_2402_02446_amd import binding
     binding.lib()                                     # fail loudly if the HIP library is missing
     rng = np.random.default_rng(0)
+
+    if args.pmc_probe:
+        pmc_probe(rng)
+        return
 
     M, K, N, k = 16, 4096, 4096, 32
     heads, ctx = run_case("cfg2: LLaMA-7B q_proj decode", K, N, k, [16, 1], args.steps, args.warmup, rng,
@@ -220,7 +265,8 @@ def main():
         "config": {"workload": "cfg2: LLaMA-7B-shaped q_proj decode, W 4096x4096 MXINT4, X 16x4096 -> MXINT8, "
                                "k=32 MXINT8 factors, ring of %d distinct layers" % head["ring_layers"],
                    "M": M, "K": K, "N": N, "k": k},
-        "roofline": head["roofline"], "cpu_baseline": cpu,
+        "roofline": dict(head["roofline"], traffic=read_pmc_traffic("skinny_kernel.cfg2_M16")),
+        "cpu_baseline": cpu,
         "headline_detail": head, "cases": cases,
     }
     print(json.dumps(out))
