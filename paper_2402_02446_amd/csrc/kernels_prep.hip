@@ -1,12 +1,12 @@
 // Stage 1 of the forward pass: quantize activations to MXINT8 (Sec. 4.1, block [1,16]) and
 // compute the low-rank projection T = X_q A_k (Eq. 3 / Eq. 6, first small matmul).
 //
-// One workgroup owns 16 token rows and a K slice; its four wavefronts take the slice's 256-wide
+// One workgroup owns 16 token rows and a K slice; its eight wavefronts take the slice's 256-wide
 // K tiles in turn.  Lane (t = lane % 16, q = lane / 16) owns the blocks q + 4p (p = 0..3) of a
 // tile for token t: it finds the block maximum, quantizes, and keeps the dequantized values
 // code * 2^(e-6) - exact in bf16 - both for the store to the bf16 activation matrix the main
-// kernels read and as its MFMA operand.  A_k's int8 codes are scaled to bf16 the same way, so
-// every product entering the fp32 MFMA accumulator is exact.
+// kernels read and as its MFMA operand.  A_k arrives already dequantized to bf16 (exactly, at
+// import), so every product entering the fp32 MFMA accumulator is exact.
 //
 // S == 1: T is final; it is split into two bf16 terms T_hi + T_lo and stored behind the
 //         activations of the same row, where the main kernel treats it as 2*kp more K columns.
@@ -37,9 +37,11 @@ __device__ __forceinline__ void split_bf16(float t, uint16_t& hi, uint16_t& lo) 
     lo = (uint16_t)(f32_bits(rem) >> 16);
 }
 
+constexpr int kPrepWaves = 8;
+
 template <bool FROM_CODES, bool FINAL, int MAXG>
-__global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
-    __shared__ float red[4][MAXG][64][4];
+__global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
+    __shared__ float red[kPrepWaves][MAXG][64][4];
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -59,7 +61,7 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
     int64_t tile_end = tile_begin + a.tiles_per_slice;
     if (tile_end > a.KT) tile_end = a.KT;
 
-    for (int64_t tile = tile_begin + wave; tile < tile_end; tile += 4) {
+    for (int64_t tile = tile_begin + wave; tile < tile_end; tile += kPrepWaves) {
         Frag xf[4][2];                                       // [p][half]
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
@@ -123,13 +125,11 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
         for (int g = 0; g < MAXG; ++g) {
             if (g < a.groups_per_wg) {
                 const uint8_t* rec = a.At + ((int64_t)(g0 + g) * a.KT + tile) * kARecordBytes;
-                const uint32_t ew = *reinterpret_cast<const uint32_t*>(rec + 4096 + lane * 4);
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
-                    const u32x4 cw = *reinterpret_cast<const u32x4*>(rec + p * 1024 + lane * 16);
-                    const float sc = h_scale((ew >> (8 * p)) & 0xFFu);
                     Frag af[2];
-                    int8x16_to_frags(cw, sc, af[0], af[1]);
+                    af[0].u = *reinterpret_cast<const u32x4*>(rec + (2 * p) * 1024 + lane * 16);
+                    af[1].u = *reinterpret_cast<const u32x4*>(rec + (2 * p + 1) * 1024 + lane * 16);
                     acc[g] = mfma16(af[0].v, xf[p][0].v, acc[g]);
                     acc[g] = mfma16(af[1].v, xf[p][1].v, acc[g]);
                 }
@@ -142,16 +142,16 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
         return;
     }
 
-    // add the four wavefronts' partial T in a fixed order
+    // add the wavefronts' partial T in a fixed order
 #pragma unroll
     for (int g = 0; g < MAXG; ++g)
         *reinterpret_cast<f32x4*>(&red[wave][g][lane][0]) = acc[g];
     __syncthreads();
-    for (int item = threadIdx.x; item < a.groups_per_wg * 64; item += 256) {
+    for (int item = threadIdx.x; item < a.groups_per_wg * 64; item += 64 * kPrepWaves) {
         const int g = item >> 6, l = item & 63;
         f32x4 s = *reinterpret_cast<const f32x4*>(&red[0][g][l][0]);
 #pragma unroll
-        for (int w = 1; w < 4; ++w) {
+        for (int w = 1; w < kPrepWaves; ++w) {
             const f32x4 o = *reinterpret_cast<const f32x4*>(&red[w][g][l][0]);
             s[0] += o[0]; s[1] += o[1]; s[2] += o[2]; s[3] += o[3];
         }
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
     // zero the padding behind T_hi | T_lo so the main kernel can read whole 64-column chunks
     if (FINAL && blockIdx.z == 0) {
         const int pad = (int)(a.tail_cols - 2 * a.kp);
-        for (int item = threadIdx.x; item < 16 * pad; item += 256) {
+        for (int item = threadIdx.x; item < 16 * pad; item += 64 * kPrepWaves) {
             const int64_t orow = (int64_t)blockIdx.x * 16 + item / pad;
             if (orow < a.M) a.Xh[orow * a.ldxh + a.KT * kTileK + 2 * a.kp + item % pad] = 0;
         }
@@ -186,7 +186,7 @@ int prep_slices(const Layer& L, int64_t M, int path) {
     if (path != 1) return 1;
     // streaming path: M <= 64 rows means at most 4 row groups; spread K over workgroups so the
     // projection does not serialise on a handful of compute units.
-    int64_t s = L.KT / 4;
+    int64_t s = L.KT / 2;
     if (s < 1) s = 1;
     if (s > 8) s = 8;
     return (int)s;
@@ -206,7 +206,7 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     a.tail_cols = ws.ldxh - L.KT * kTileK;
     a.Tpart = ws.Tpart;
     dim3 grid((unsigned)((M + 15) / 16), (unsigned)ws.S, (unsigned)(split_groups ? L.kp16 : 1));
-    dim3 block(256);
+    dim3 block(64 * kPrepWaves);
     const bool from_codes = (Xc != nullptr);
     const bool fin = (ws.S == 1);
 #define LQER_PREP(FC, FN, MG) hipLaunchKernelGGL((prep_kernel<FC, FN, MG>), grid, block, 0, s, a)

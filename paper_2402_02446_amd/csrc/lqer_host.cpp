@@ -1,6 +1,7 @@
 // Host side of liblqer: the C ABI, layer import/export (canonical bytes <-> tiled device layout),
 // workspace planning and the dispatch between the streaming and the tiled main kernel.
 #include <atomic>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -11,6 +12,7 @@
 
 struct lqer_layer {
     lqer::Layer L;
+    std::vector<uint8_t> Ae_host;     // A_k's exponent bytes [kp][K/16], needed again only by export
 };
 
 namespace lqer {
@@ -117,6 +119,15 @@ static void untile_weights(const Layer& L, const std::vector<uint8_t>& in, uint8
     });
 }
 
+// bf16 bit pattern of code * 2^(eb - 127 - 6): exact (7 significand bits), computed through fp32
+static uint16_t a_value_bf16(int code, int eb) {
+    const float v = std::ldexp((float)code, eb - 127 - 6);
+    uint32_t bits;
+    memcpy(&bits, &v, 4);
+    return (uint16_t)(bits >> 16);
+}
+
+// canonical Ac/Ae -> records of exact bf16 values in the MFMA operand order of the projection kernel
 static int tile_a(const Layer& L, const int8_t* Ac, const uint8_t* Ae, std::vector<uint8_t>& out) {
     const int64_t nblk = L.K / 16;
     out.assign((size_t)(L.kp16 * L.KT) * kARecordBytes, 0);
@@ -128,34 +139,48 @@ static int tile_a(const Layer& L, const int8_t* Ac, const uint8_t* Ae, std::vect
             for (int lane = 0; lane < 64; ++lane) {
                 const int c = lane & 15, q = lane >> 4;
                 const int64_t r = g * 16 + c;
-                uint32_t ew = 0;
                 for (int p = 0; p < 4; ++p) {
                     const int64_t kb = tile * 16 + q + 4 * p;
                     if (kb >= nblk) continue;
-                    memcpy(rec + p * 1024 + lane * 16, Ac + r * L.K + kb * 16, 16);
-                    ew |= (uint32_t)Ae[r * nblk + kb] << (8 * p);
+                    const int eb = Ae[r * nblk + kb];
+                    for (int h = 0; h < 2; ++h) {
+                        uint16_t v[8];
+                        for (int i = 0; i < 8; ++i) v[i] = a_value_bf16(Ac[r * L.K + kb * 16 + 8 * h + i], eb);
+                        memcpy(rec + (2 * p + h) * 1024 + lane * 16, v, 16);
+                    }
                 }
-                memcpy(rec + 4096 + lane * 4, &ew, 4);
             }
         }
     return LQER_OK;
 }
 
-static void untile_a(const Layer& L, const std::vector<uint8_t>& in, int8_t* Ac, uint8_t* Ae) {
+// inverse, given the exponent bytes (kept on the host: a block's exponent is not recoverable from
+// its values when the largest code is below 64)
+static void untile_a(const Layer& L, const std::vector<uint8_t>& in, const std::vector<uint8_t>& Ae_host,
+                     int8_t* Ac, uint8_t* Ae) {
     const int64_t nblk = L.K / 16;
+    if (Ae) memcpy(Ae, Ae_host.data(), Ae_host.size());
+    if (!Ac) return;
     for (int g = 0; g < L.kp16; ++g)
         for (int64_t tile = 0; tile < L.KT; ++tile) {
             const uint8_t* rec = in.data() + (size_t)(g * L.KT + tile) * kARecordBytes;
             for (int lane = 0; lane < 64; ++lane) {
                 const int c = lane & 15, q = lane >> 4;
                 const int64_t r = g * 16 + c;
-                uint32_t ew;
-                memcpy(&ew, rec + 4096 + lane * 4, 4);
                 for (int p = 0; p < 4; ++p) {
                     const int64_t kb = tile * 16 + q + 4 * p;
                     if (kb >= nblk) continue;
-                    if (Ac) memcpy(Ac + r * L.K + kb * 16, rec + p * 1024 + lane * 16, 16);
-                    if (Ae) Ae[r * nblk + kb] = (uint8_t)((ew >> (8 * p)) & 0xFF);
+                    const int eb = Ae_host[r * nblk + kb];
+                    for (int h = 0; h < 2; ++h) {
+                        uint16_t v[8];
+                        memcpy(v, rec + (2 * p + h) * 1024 + lane * 16, 16);
+                        for (int i = 0; i < 8; ++i) {
+                            const uint32_t bits = (uint32_t)v[i] << 16;
+                            float f;
+                            memcpy(&f, &bits, 4);
+                            Ac[r * L.K + kb * 16 + 8 * h + i] = (int8_t)std::lrint(std::ldexp(f, 6 - (eb - 127)));
+                        }
+                    }
                 }
             }
         }
@@ -334,6 +359,7 @@ int lqer_layer_import(int64_t K, int64_t N, int k, const uint8_t* Wc, const uint
         std::vector<uint8_t> buf;
         st = tile_a(L, Ac, Ae, buf);
         if (st == LQER_OK) st = upload(buf, &L.At);
+        if (st == LQER_OK) h->Ae_host.assign(Ae, Ae + (size_t)kp * (K / 16));
     }
     if (st == LQER_OK && kp > 0) {
         std::vector<uint8_t> buf;
@@ -363,7 +389,7 @@ int lqer_layer_export(const lqer_layer* layer, uint8_t* Wc, uint8_t* We, int8_t*
     if (L.kp > 0 && (Ac || Ae)) {
         st = download(L.At, (size_t)(L.kp16 * L.KT) * kARecordBytes, buf);
         if (st != LQER_OK) return st;
-        untile_a(L, buf, Ac, Ae);
+        untile_a(L, buf, layer->Ae_host, Ac, Ae);
     }
     if (L.kp > 0 && (Bc || Be)) {
         st = download(L.Bt, (size_t)(L.N32 * L.kp16) * kBRecordBytes, buf);

@@ -32,15 +32,18 @@ namespace lqer {
 // code * 2^(e-2) exactly.
 //
 // A_k (used by the projection kernel with the 16x16x32 MFMA, lane = c + 16 q owning blocks
-//      q + 4p): records of [16 ranks] x [256 K]: codes[4][64 lanes][16 B] (p-th 16 bytes are block
-//      q + 4p's int8 codes) + exps[64 lanes][4 B]; ordered [rank group][K tile].
+//      q + 4p): records of [16 ranks] x [256 K] holding the dequantized values code * 2^(e-6) as
+//      bf16 (exact): values[8][64 lanes][16 B], entry 2p + h = half h (8 elements) of block q + 4p;
+//      ordered [rank group][K tile].  The exponent bytes stay on the host for export.  A_k is
+//      K*kp elements, well under 1 % of the layer, so the extra byte per element is negligible and
+//      the projection kernel needs no conversion at all.
 // B_k: records of [32 columns] x [16 ranks] (one MXINT block per column): codes[32 columns][16 B]
 //      + exps[32 columns][1 B]; ordered [column group][rank block].
 
 constexpr int kTileK = 256;          // K covered by one W / A record
 constexpr int kWRecordBytes = 4608;
 constexpr int kWExpOffset = 4096;
-constexpr int kARecordBytes = 4352;
+constexpr int kARecordBytes = 8192;
 constexpr int kBRecordBytes = 544;
 constexpr int kMaxWExpByte = 247;    // (byte + 7) must stay a finite fp32 exponent field
 
