@@ -138,6 +138,77 @@ def run_case(name, K, N, k, Ms, steps, warmup, rng, ring_bytes, gain, bound):
     return results, ctx0
 
 
+def run_quantizer_case(rows, cols, steps, rng):
+    """lqer_quantize_mx alone on a cfg5-sized activation matrix: HBM-bound, 5.0625 B per element."""
+    import torch
+    from paper_2402_02446_amd import binding
+    g = torch.Generator(device="cuda").manual_seed(int(rng.integers(1 << 31)))
+    X = torch.randn((rows, cols), generator=g, device="cuda", dtype=torch.float32)
+    f = lambda i: binding.lqer_quantize_mx(X, 8)
+    f(0)
+    torch.cuda.synchronize()
+    ms = _event_ms(f, steps)
+    ach = rows * cols * 5.0625 / (ms * 1e-3) / 1e9
+    return {"workload": "a1 quantizer alone, %d x %d fp32 -> MXINT8" % (rows, cols), "M": rows, "K": cols,
+            "ms_per_call": ms,
+            "roofline": {"bound": "hbm", "kernel": "quantize_mx_kernel", "achieved": ach, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}}
+
+
+def run_cfg5(steps, rng):
+    """cfg5: the seven LQER linears of a LLaMA-7B decoder block at M = 32 x 2048 tokens, k in
+    {16, 32, 64}; activations are drawn on the device (N(0,1), 1 % of channels x 50).  Returns one
+    record per k with the per-shape times and the whole block's TFLOP/s."""
+    import torch
+    from paper_2402_02446_amd import binding, synth
+    M = synth.CFG5_M
+    shapes = {}
+    for name, K, N in synth.CFG5_LINEARS:
+        shapes.setdefault((K, N), []).append(name)
+    out = []
+    g = torch.Generator(device="cuda").manual_seed(int(rng.integers(1 << 31)))
+    for k in (16, 32, 64):
+        total_ms, total_fl, per_shape = 0.0, 0.0, []
+        for (K, N), names in shapes.items():
+            d = synth.random_packed_layer(rng, K, N, k)
+            layer = binding.lqer_layer_import(K, N, k, d["Wc"], d["We"], d["Ac"], d["Ae"], d["Bc"], d["Be"])
+            X = torch.randn((M, K), generator=g, device="cuda", dtype=torch.float32)
+            ch = torch.from_numpy(synth.gen_outlier_channels(rng, K, max(1, round(0.01 * K)))).cuda()
+            X[:, ch] *= 50.0
+            Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+            f = lambda i: binding.lqer_linear_forward(layer, X, Y=Y)
+            f(0)
+            torch.cuda.synchronize()
+            ms = _event_ms(f, steps)
+            fl = flops_forward(M, K, N, layer.kp)
+            per_shape.append({"K": K, "N": N, "linears": names, "ms_per_linear": ms,
+                              "tflops": fl / (ms * 1e-3) / 1e12})
+            total_ms += ms * len(names)
+            total_fl += fl * len(names)
+            layer.free()
+            del X, Y
+        out.append({"workload": "cfg5: LLaMA-7B decoder block, 7 LQER linears, M=%d" % M, "k": k,
+                    "ms_per_block": total_ms, "tflops": total_fl / (total_ms * 1e-3) / 1e12,
+                    "frac_of_mfma_peak": total_fl / (total_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                    "per_shape": per_shape})
+    return out
+
+
+def time_build_factors(rng):
+    """Wall time of the offline step (lqer_build_factors, host fp64 + upload) per layer shape of cfg5."""
+    from paper_2402_02446_amd import binding, synth
+    res = []
+    for (K, N) in ((4096, 4096), (4096, 11008), (11008, 4096)):
+        W = synth.gen_weight(rng, K, N)
+        ch = synth.gen_outlier_channels(rng, K, max(1, round(0.01 * K)))
+        calib = np.stack([synth.gen_activations(rng, 128, K, ch, 50.0)])
+        t0 = time.perf_counter()
+        layer = binding.lqer_build_factors(W, calib, 32, 1)
+        res.append({"K": K, "N": N, "k": 32, "mode": "L2QER", "seconds": time.perf_counter() - t0})
+        layer.free()
+    return res
+
+
 def cpu_baseline(ctx, M, K, N, kp, budget_s=12.0):
     """The oracle as it stands, timed on this machine's host cores on the headline workload, and the
     GPU result checked against it.  Only this function touches oracle/."""
@@ -219,7 +290,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--cases", default="all", choices=["headline", "all"])
+    ap.add_argument("--cases", default="all", choices=["headline", "all", "full"],
+                    help="headline: cfg2 only; all: + cfg3, cfg4 and the quantizer; full: + cfg5 and build_factors timing")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run a plain 1 GiB copy and the headline ring a few times, for rocprofv3 --pmc runs")
     args = ap.parse_args()
@@ -244,7 +316,8 @@ def main():
                           ring_bytes=1.25 * LLC_BYTES, gain=50.0, bound="hbm")
     head = heads[0]
     cases = heads[1:]
-    if args.cases == "all":
+    extra = {}
+    if args.cases in ("all", "full"):
         ksteps = max(10, args.steps // 10)
         plan = [
             ("cfg3: LLaMA-7B MLP up, prefill", 4096, 11008, 32, [2048], ksteps, 0, "mfma"),
@@ -255,6 +328,10 @@ def main():
         for (nm, k_, n_, r_, ms_, st_, ring, bound) in plan:
             res, _ = run_case(nm, k_, n_, r_, ms_, st_, min(args.warmup, st_), rng, ring, 50.0, bound)
             cases.extend(res)
+        cases.append(run_quantizer_case(32 * 2048, 4096, ksteps, rng))
+    if args.cases == "full":
+        extra["cfg5"] = run_cfg5(3, rng)
+        extra["build_factors_seconds_per_layer"] = time_build_factors(rng)
     kp = 32
     cpu = cpu_baseline(ctx, M, K, N, kp)
     out = {
@@ -269,6 +346,7 @@ def main():
         "cpu_baseline": cpu,
         "headline_detail": head, "cases": cases,
     }
+    out.update(extra)
     print(json.dumps(out))
 
 
