@@ -49,7 +49,12 @@ __device__ __forceinline__ WRec load_wrec(const uint8_t* rec, int lane) {
 
 // LR = log2 of the token rows staged (4, 16 or 32).  LDS cell order of a stage is
 // [16-byte column of the NWK*256-wide K range][token row], so 16 lanes read 256 contiguous bytes.
-template <int NWC, int NWK, int LR>
+// NIP = 0: the general, pipelined loop over any number of iterations.  NIP = 2 or 4: short layers
+// whose K range is covered in at most NIP iterations fetch every weight record and every
+// activation stage up front (all HBM requests in flight at once), synchronise once and then do
+// all the arithmetic; with so few iterations a two-deep pipeline would pay the memory latency
+// several times over.
+template <int NWC, int NWK, int LR, int NIP>
 __global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
     constexpr int NW = NWC * NWK;
     constexpr int R = 1 << LR;
@@ -59,7 +64,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
     constexpr int kTBytes = 32 * 128 * 2;            // T_hi | T_lo of up to 32 tokens x 64 ranks, bf16
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     uint16_t* tlds = reinterpret_cast<uint16_t*>(lds);                 // [32][2 kp] bf16, kept all along
-    uint8_t* xlds = lds + kTBytes;                                     // the two activation stages
+    uint8_t* xlds = lds + kTBytes;                                     // the activation stages (2, or NIP)
     float* red = reinterpret_cast<float*>(lds + kTBytes);              // reused after the main loop: [NWK-1][NWC][64][16]
 
     const int lane = threadIdx.x & 63;
@@ -198,20 +203,9 @@ __global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
             return tl < a.KT ? tl : a.KT - 1;                                // clamped re-read
         };
         const uint8_t* wrec = a.Wt + grp * a.KT * kWRecordBytes;
-        // Three weight records rotate through three register sets by name (the loop is unrolled by
-        // three); copying one set into another would make the wavefront wait for the newest load.
-        WRec wa, wb, wd;
-        {
-            u32x4 st[XL];
-            fetch_x(0, st);
-            wa = load_wrec(wrec + tile_at(0) * kWRecordBytes, lane);
-            wb = load_wrec(wrec + tile_at(1) * kWRecordBytes, lane);
-            finish_t();
-            store_x(st, 0);
-        }
-        auto mma_tile = [&](const WRec& cur, int64_t it) {
+        auto mma_tile = [&](const WRec& cur, int64_t it, int stage) {
             if (wk + NWK * it < a.KT) {
-                const uint8_t* xs = xlds + (int)(it & 1) * XT + rd_base;
+                const uint8_t* xs = xlds + stage * XT + rd_base;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
 #pragma unroll
@@ -225,6 +219,32 @@ __global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
                 }
             }
         };
+        if constexpr (NIP > 0) {
+            WRec w[NIP];
+            u32x4 st[NIP][XL];
+#pragma unroll
+            for (int i = 0; i < NIP; ++i) fetch_x(i, st[i]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < NIP; ++i) w[i] = load_wrec(wrec + tile_at(i) * kWRecordBytes, lane);
+            finish_t();
+#pragma unroll
+            for (int i = 0; i < NIP; ++i) store_x(st[i], i);
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < NIP; ++i) mma_tile(w[i], i, i);
+        } else {
+        // Three weight records rotate through three register sets by name (the loop is unrolled by
+        // three); copying one set into another would make the wavefront wait for the newest load.
+        WRec wa, wb, wd;
+        {
+            u32x4 st[XL];
+            fetch_x(0, st);
+            wa = load_wrec(wrec + tile_at(0) * kWRecordBytes, lane);
+            wb = load_wrec(wrec + tile_at(1) * kWRecordBytes, lane);
+            finish_t();
+            store_x(st, 0);
+        }
         // All loads of a full step are unconditional (indices clamped): a load inside a branch would
         // make the compiler's wait counts assume the worst case.  The last iteration is peeled off
         // instead and fetches nothing.
@@ -234,12 +254,12 @@ __global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
             fetch_x(it + 1, st);
             __builtin_amdgcn_sched_barrier(0);      // loads retire in order: activations stay ahead of weights
             fill = load_wrec(wrec + tile_at(it + 2) * kWRecordBytes, lane);
-            mma_tile(cur, it);
+            mma_tile(cur, it, (int)(it & 1));
             store_x(st, (int)((it + 1) & 1));    // waits for the activation loads only; `fill` stays in flight
         };
         auto last_step = [&](const WRec& cur, int64_t it) {
             __syncthreads();
-            mma_tile(cur, it);
+            mma_tile(cur, it, (int)(it & 1));
         };
         int64_t it = 0;
         for (; it + 3 < NI; it += 3) {
@@ -257,6 +277,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
             step(wa, wd, it);
             step(wb, wa, it + 1);
             last_step(wd, it + 2);
+        }
         }
     }
 
@@ -324,14 +345,14 @@ __global__ __launch_bounds__(64 * NWC * NWK) void skinny_kernel(SkinnyArgs a) {
 
 int skinny_max_rows() { return 32; }
 
-template <int NWC, int NWK, int LR>
+template <int NWC, int NWK, int LR, int NIP>
 static hipError_t launch_skinny_t(const SkinnyArgs& a, hipStream_t s) {
     constexpr int XT = NWK * (1 << LR) * 512;
-    constexpr int STAGING = 2 * XT;
+    constexpr int STAGING = (NIP > 0 ? NIP : 2) * XT;
     constexpr int REDUCE = (NWK - 1) * NWC * 4096;
     constexpr int LDS_BYTES = 32 * 128 * 2 + (STAGING > REDUCE ? STAGING : REDUCE);
     static_assert(LDS_BYTES <= 160 * 1024, "does not fit the 160 KB of LDS");
-    auto kern = skinny_kernel<NWC, NWK, LR>;
+    auto kern = skinny_kernel<NWC, NWK, LR, NIP>;
     static bool attr_set = false;
     if (!attr_set) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -344,14 +365,28 @@ static hipError_t launch_skinny_t(const SkinnyArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
+// picks the preloading form when the K range fits in 2 or 4 iterations and their stages fit LDS
+template <int NWC, int NWK, int LR>
+static hipError_t launch_skinny_k(const SkinnyArgs& a, hipStream_t s) {
+    constexpr int XT = NWK * (1 << LR) * 512;
+    const int64_t NI = (a.KT + NWK - 1) / NWK;
+    if constexpr (2 * XT <= 128 * 1024) {
+        if (NI <= 2) return launch_skinny_t<NWC, NWK, LR, 2>(a, s);
+    }
+    if constexpr (4 * XT <= 128 * 1024) {
+        if (NI <= 4) return launch_skinny_t<NWC, NWK, LR, 4>(a, s);
+    }
+    return launch_skinny_t<NWC, NWK, LR, 0>(a, s);
+}
+
 template <int NWC, int NWK>
 static hipError_t launch_skinny_rows(const SkinnyArgs& a, hipStream_t s) {
-    if (a.M <= 4) return launch_skinny_t<NWC, NWK, 2>(a, s);
+    if (a.M <= 4) return launch_skinny_k<NWC, NWK, 2>(a, s);
     if constexpr (NWK <= 8) {
-        if (a.M <= 16) return launch_skinny_t<NWC, NWK, 4>(a, s);
+        if (a.M <= 16) return launch_skinny_k<NWC, NWK, 4>(a, s);
     }
     if constexpr (NWK <= 4) {
-        return launch_skinny_t<NWC, NWK, 5>(a, s);
+        return launch_skinny_k<NWC, NWK, 5>(a, s);
     }
     return hipErrorInvalidValue;
 }
@@ -368,9 +403,9 @@ hipError_t launch_skinny(const Layer& L, int64_t M, const Workspace& ws, float* 
     // K slices: 16 token rows allow 8, 32 rows allow 4.
     int v = variant;
     if (v == 0) {
-        if (L.N32 >= 512) v = 404;
+        if (L.N32 >= 512) v = (M <= 16) ? 404 : 402;
         else if (L.N32 >= 256) v = 204;
-        else v = (M <= 4) ? 108 : (M <= 16 ? 204 : 104);
+        else v = (M <= 16) ? 108 : 104;
     }
     const int max_k = (M <= 4) ? 16 : (M <= 16 ? 8 : 4);
     if (v % 100 > max_k) return hipErrorInvalidValue;

@@ -132,9 +132,17 @@ __global__ __launch_bounds__(64 * WR * WC) void tiled_kernel(TiledArgs a) {
         for (int j = 0; j < LPT; ++j)
             *reinterpret_cast<u32x4*>(lds + stage * STAGE + ld_dst0 + j * ROWS_PER_PASS * 128) = st[j];
     };
-    // one 64-wide chunk of the main product: c = chunk index within its K tile = stage = register set
+    // one 64-wide chunk of the main product: c = chunk index within its K tile = stage = register set.
+    // The activation operands are read one MFMA step ahead: `xa` holds step 0 on entry and step 0
+    // of the next chunk on exit (that stage was completed two barriers ago, so it may be read
+    // before the next barrier).
+    Frag xa[TM];
+    auto read_xa = [&](Frag (&dst)[TM], int stage_idx, int s4) {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+            dst[tm].u = *reinterpret_cast<const u32x4*>(lds + stage_idx * STAGE + rd_off[s4] + tm * 4096);
+    };
     auto mma_chunk = [&](const WSet& w, const ESet& x, int c) {
-        const uint8_t* stage = lds + c * STAGE;
         float sc[TN][2];
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
@@ -144,16 +152,17 @@ __global__ __launch_bounds__(64 * WR * WC) void tiled_kernel(TiledArgs a) {
         }
 #pragma unroll
         for (int s4 = 0; s4 < 4; ++s4) {
-            Frag xa[TM];
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-                xa[tm].u = *reinterpret_cast<const u32x4*>(stage + rd_off[s4] + tm * 4096);
+            Frag xn[TM];
+            if (s4 < 3) read_xa(xn, c, s4 + 1);
+            else read_xa(xn, (c + 1) & 3, 0);
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
                 const bf16x8 wv = unpack_w8(w.c[tn][s4], sc[tn][s4 >> 1]);
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm) acc[tm][tn] = mfma32(wv, xa[tm].v, acc[tm][tn]);
             }
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) xa[tm] = xn[tm];
         }
     };
 
@@ -183,6 +192,7 @@ __global__ __launch_bounds__(64 * WR * WC) void tiled_kernel(TiledArgs a) {
     const int64_t last_chunk = chunks - 1, last_main = main_chunks - 1, last_tile = a.KT - 1;
     auto step = [&](const WSet& cur, const ESet& ecur, WSet& fill, ESet& enext, int64_t ch, int c) {
         __syncthreads();
+        if (ch == 0) read_xa(xa, 0, 0);          // later chunks find step 0 already read by the previous one
         u32x4 st[LPT];
         fetch_x(st, ch + 2 < last_chunk ? ch + 2 : last_chunk);
         // loads retire in order: keep the activation loads ahead of the weight loads, so that the
