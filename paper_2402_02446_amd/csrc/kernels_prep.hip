@@ -28,6 +28,7 @@ struct PrepArgs {
     uint16_t* Xh; int64_t ldxh;
     int64_t tail_cols;     // columns behind K_pad in Xh (T_hi | T_lo | zero padding)
     float* Tpart;
+    int lr;                // CELLS: log2 of the token rows per 16-byte cell column
 };
 
 __device__ __forceinline__ void split_bf16(float t, uint16_t& hi, uint16_t& lo) {
@@ -39,12 +40,15 @@ __device__ __forceinline__ void split_bf16(float t, uint16_t& hi, uint16_t& lo) 
 
 constexpr int kPrepWaves = 8;
 
-template <bool FROM_CODES, bool FINAL, int MAXG>
+// CELLS: the activations are stored for the streaming kernel, as 16-byte cells (8 consecutive K
+// elements) ordered [K / 8][token row]; otherwise row-major for the tiled kernel.
+template <bool FROM_CODES, bool FINAL, int MAXG, bool CELLS>
 __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
     __shared__ float red[kPrepWaves][MAXG][64][4];
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
+    const int nwaves = blockDim.x >> 6;              // 1 .. kPrepWaves
     const int t = lane & 15, q = lane >> 4;
     const int64_t row = (int64_t)blockIdx.x * 16 + t;
     const bool row_ok = row < a.M;
@@ -61,7 +65,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
     int64_t tile_end = tile_begin + a.tiles_per_slice;
     if (tile_end > a.KT) tile_end = a.KT;
 
-    for (int64_t tile = tile_begin + wave; tile < tile_end; tile += kPrepWaves) {
+    for (int64_t tile = tile_begin + wave; tile < tile_end; tile += nwaves) {
         Frag xf[4][2];                                       // [p][half]
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
@@ -116,9 +120,16 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
                 for (int i = 0; i < 4; ++i)
                     xf[p][h].u[i] = pack_bf16_exact(r[8 * h + 2 * i] * scale, r[8 * h + 2 * i + 1] * scale);
             if (store_x && row_ok) {
-                uint16_t* dst = a.Xh + row * a.ldxh + (tile * 16 + q + 4 * p) * 16;
-                *reinterpret_cast<u32x4*>(dst) = xf[p][0].u;
-                *reinterpret_cast<u32x4*>(dst + 8) = xf[p][1].u;
+                if (CELLS) {
+                    const int64_t cell = (tile * 16 + q + 4 * p) * 2;
+                    uint16_t* dst = a.Xh + (((cell << a.lr) + row) << 3);
+                    *reinterpret_cast<u32x4*>(dst) = xf[p][0].u;
+                    *reinterpret_cast<u32x4*>(dst + (8 << a.lr)) = xf[p][1].u;
+                } else {
+                    uint16_t* dst = a.Xh + row * a.ldxh + (tile * 16 + q + 4 * p) * 16;
+                    *reinterpret_cast<u32x4*>(dst) = xf[p][0].u;
+                    *reinterpret_cast<u32x4*>(dst + 8) = xf[p][1].u;
+                }
             }
         }
 #pragma unroll
@@ -147,11 +158,10 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
     for (int g = 0; g < MAXG; ++g)
         *reinterpret_cast<f32x4*>(&red[wave][g][lane][0]) = acc[g];
     __syncthreads();
-    for (int item = threadIdx.x; item < a.groups_per_wg * 64; item += 64 * kPrepWaves) {
+    for (int item = threadIdx.x; item < a.groups_per_wg * 64; item += blockDim.x) {
         const int g = item >> 6, l = item & 63;
         f32x4 s = *reinterpret_cast<const f32x4*>(&red[0][g][l][0]);
-#pragma unroll
-        for (int w = 1; w < kPrepWaves; ++w) {
+        for (int w = 1; w < nwaves; ++w) {
             const f32x4 o = *reinterpret_cast<const f32x4*>(&red[w][g][l][0]);
             s[0] += o[0]; s[1] += o[1]; s[2] += o[2]; s[3] += o[3];
         }
@@ -175,7 +185,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
     // zero the padding behind T_hi | T_lo so the main kernel can read whole 64-column chunks
     if (FINAL && blockIdx.z == 0) {
         const int pad = (int)(a.tail_cols - 2 * a.kp);
-        for (int item = threadIdx.x; item < 16 * pad; item += 64 * kPrepWaves) {
+        for (int item = threadIdx.x; item < 16 * pad; item += blockDim.x) {
             const int64_t orow = (int64_t)blockIdx.x * 16 + item / pad;
             if (orow < a.M) a.Xh[orow * a.ldxh + a.KT * kTileK + 2 * a.kp + item % pad] = 0;
         }
@@ -184,11 +194,11 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
 
 int prep_slices(const Layer& L, int64_t M, int path) {
     if (path != 1) return 1;
-    // streaming path: M <= 64 rows means at most 4 row groups; spread K over workgroups so the
-    // projection does not serialise on a handful of compute units.
-    int64_t s = L.KT / 2;
-    if (s < 1) s = 1;
+    // streaming path: at most two row groups, so K is spread over workgroups (the main kernel adds
+    // up to 8 partial sums); one wavefront per K tile of a slice, at most kPrepWaves.
+    int64_t s = L.KT;
     if (s > 8) s = 8;
+    if (s < 1) s = 1;
     return (int)s;
 }
 
@@ -200,25 +210,29 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     a.M = M; a.K = L.K; a.KT = L.KT;
     a.tiles_per_slice = (int)((L.KT + ws.S - 1) / ws.S);
     a.kp = L.kp; a.kp16 = L.kp16;
-    const bool split_groups = ws.S > 1 && L.kp16 > 1;
-    a.groups_per_wg = split_groups ? 1 : L.kp16;
+    a.groups_per_wg = L.kp16;
     a.At = L.At; a.Xh = ws.Xh; a.ldxh = ws.ldxh;
     a.tail_cols = ws.ldxh - L.KT * kTileK;
     a.Tpart = ws.Tpart;
-    dim3 grid((unsigned)((M + 15) / 16), (unsigned)ws.S, (unsigned)(split_groups ? L.kp16 : 1));
-    dim3 block(64 * kPrepWaves);
+    a.lr = ws.lr;
+    const bool cells = ws.cells;
+    int nwaves = cells ? a.tiles_per_slice : kPrepWaves;
+    if (nwaves > kPrepWaves) nwaves = kPrepWaves;
+    if (nwaves < 1) nwaves = 1;
+    dim3 grid((unsigned)((M + 15) / 16), (unsigned)ws.S, 1);
+    dim3 block(64 * nwaves);
     const bool from_codes = (Xc != nullptr);
-    const bool fin = (ws.S == 1);
-#define LQER_PREP(FC, FN, MG) hipLaunchKernelGGL((prep_kernel<FC, FN, MG>), grid, block, 0, s, a)
-    if (a.groups_per_wg <= 1) {
-        if (from_codes) { if (fin) LQER_PREP(true, true, 1); else LQER_PREP(true, false, 1); }
-        else            { if (fin) LQER_PREP(false, true, 1); else LQER_PREP(false, false, 1); }
-    } else if (a.groups_per_wg <= 4) {
-        if (from_codes) { if (fin) LQER_PREP(true, true, 4); else LQER_PREP(true, false, 4); }
-        else            { if (fin) LQER_PREP(false, true, 4); else LQER_PREP(false, false, 4); }
-    } else {
-        return hipErrorInvalidValue;      // kp > 64 is rejected at import
-    }
+    const bool fin = (ws.Tpart == nullptr);          // T final (hi/lo behind the row) or partial sums
+    if (cells && fin && L.kp > 0) return hipErrorInvalidValue;
+    if (a.groups_per_wg > 4) return hipErrorInvalidValue;      // kp > 64 is rejected at import
+#define LQER_PREP(FC, FN, MG, CL) hipLaunchKernelGGL((prep_kernel<FC, FN, MG, CL>), grid, block, 0, s, a)
+#define LQER_PREP_G(FC, FN, CL) do { if (a.groups_per_wg <= 1) LQER_PREP(FC, FN, 1, CL); else LQER_PREP(FC, FN, 4, CL); } while (0)
+#define LQER_PREP_C(FN, CL) do { if (from_codes) LQER_PREP_G(true, FN, CL); else LQER_PREP_G(false, FN, CL); } while (0)
+    if (cells) LQER_PREP_C(false, true);
+    else if (fin) LQER_PREP_C(true, false);
+    else LQER_PREP_C(false, false);
+#undef LQER_PREP_C
+#undef LQER_PREP_G
 #undef LQER_PREP
     return hipGetLastError();
 }

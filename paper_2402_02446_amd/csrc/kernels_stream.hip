@@ -1,0 +1,448 @@
+// Stage 2, small-M ("decode") form of Y = X_q W_q + T B_k (Eq. 3 / Eq. 6): a weight-streaming
+// kernel bound by HBM bandwidth.  Sec. 2.1 notes that few-token inference is memory-bound; the
+// whole job here is to read 0.5625 B per weight once, as contiguous 1 KiB wavefront loads, and to
+// hide everything else under that stream.
+//
+// What shapes the kernel is that on this chip every vector-memory instruction a compute unit
+// issues beside the weight stream costs bandwidth, even when it hits in cache: measured on an
+// 8192 x 28672 layer, two extra loads per weight record cost 5 %, eight cost 40 %.  So the
+// activations reach the MFMA through LDS, filled with as few, fully coalesced 1 KiB loads as
+// possible, and each operand read from LDS is used for G column groups.
+//
+// A workgroup is NWC x NWK wavefronts; wavefront (wc, wk) owns G column groups of 32 and, in step
+// it, the K tile NWK it + wk.  The projection kernel leaves the activations as 16-byte cells
+// [K / 8][token row] (bf16, exact dequantized X_q), so the NWK tiles of a step are one contiguous
+// range that the workgroup copies into one of two LDS stages.  A step walks its tile in four
+// 64-wide chunks; in chunk c every column group does four 32x32x16 MFMAs against the same four
+// operands read from LDS, and the registers that held chunk c of the weight records are refilled
+// at once with chunk c of the next tile, so a wavefront always has G whole records in flight and
+// loads are issued in the order their data is needed (vector-memory loads retire in order).
+// Per record a lane reads 64 B of packed codes (eight whole MXINT4 blocks) and their eight
+// exponent bytes, expands 8 codes to bf16 values code * 2^(e-2) with seven VALU instructions
+// (unpack_w8) and feeds them to the MFMA (tokens beyond M repeat the last one and are never
+// stored); products are exact, accumulation is fp32.  The rank-kp correction is 2*kp further
+// "K columns": T_hi and T_lo against B_k's codes, spread over the wavefronts.  T arrives as S
+// partial sums (one per K slice of the projection kernel) that the workgroup adds in slice order
+// and keeps in LDS as two bf16 terms.  At the end the NWK partial sums of every column group are
+// added through LDS in slice order.
+#include <type_traits>
+
+#include "lqer_internal.h"
+#include "mx_device.h"
+
+namespace lqer {
+
+struct StreamArgs {
+    const uint8_t* Wt; const uint8_t* Bt;
+    const uint8_t* Xcell;          // bf16 activations as 16-byte cells [KT*32][R rows]
+    const float* Tpart; int S;
+    float* Y; int64_t ldy;
+    int64_t M, N, KT, N32;
+    int kp, kp16;
+};
+
+// LR = log2 of the token rows per activation cell column (4, 16 or 32 rows).
+// ONE: the whole K range is a single step (KT <= NWK): one activation stage, no loop.
+template <int G, int NWC, int NWK, int DT, int LR, bool ONE>
+__global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
+    static_assert(DT == 1 || DT == 2, "weights one or two steps ahead");
+    static_assert(!ONE || DT == 1, "a single step prefetches nothing");
+    constexpr int NW = NWC * NWK;
+    constexpr int NG = NWC * G;                      // column groups of the workgroup
+    constexpr int R = 1 << LR;
+    constexpr int XT = NWK * R * 512;                // bytes of one stage: NWK tiles x R rows of bf16
+    constexpr int NL = XT / 1024;                    // 1 KiB loads per stage
+    constexpr int XL = (NL + NW - 1) / NW;           // ... per wavefront
+    static_assert(XT % 1024 == 0, "a stage is a whole number of wavefront loads");
+    constexpr int kTBytes = 32 * 128 * 2;            // T_hi | T_lo of up to 32 tokens x 64 ranks, bf16
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    uint16_t* tlds = reinterpret_cast<uint16_t*>(lds);                 // [32][2 kp] bf16, kept all along
+    uint8_t* xlds = lds + kTBytes;                                     // two activation stages
+    float* red = reinterpret_cast<float*>(lds + kTBytes);              // reused afterwards: [NWK][NG][64][16]
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wc = wave % NWC, wk = wave / NWC;
+    const int t = lane & 31, hh = lane >> 5;
+
+    // column groups of this wavefront (clamped; stores are masked)
+    const int64_t g0 = ((int64_t)blockIdx.x * NWC + wc) * G;
+    const uint8_t* wrec[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        int64_t grp = g0 + g;
+        if (grp >= a.N32) grp = a.N32 - 1;
+        wrec[g] = a.Wt + grp * a.KT * kWRecordBytes + lane * 16;
+    }
+    const int e_adj = -(lane * 8);                   // exponent words sit at lane * 8, not lane * 16
+    int trow = t;
+    if (trow >= a.M) trow = (int)a.M - 1;            // repeat a valid token; never stored
+
+    const int64_t NI = (a.KT + NWK - 1) / NWK;       // steps, the same for every wavefront
+    // Tiles past the last one are read again (clamped index) and their arithmetic is skipped.
+    auto tile_at = [&](int64_t it) {
+        const int64_t tl = wk + NWK * it;
+        return tl < a.KT ? tl : a.KT - 1;
+    };
+    // activation stage of step it: bytes [it XT, (it + 1) XT) of the cell array, clamped at its end
+    const int64_t x_last = (a.KT * 32 * R * 16) - 1024;            // last whole 1 KiB of the array
+    int st_off[XL];
+#pragma unroll
+    for (int x = 0; x < XL; ++x) {
+        const int j = wave + NW * x;
+        st_off[x] = (j < NL) ? j * 1024 + lane * 16 : -1;
+    }
+    // LDS placement of a cell: the two lane halves of an operand read are 4 cells apart, which is a
+    // multiple of the 256-byte bank period; flipping address bit 7 for the upper half's cells moves
+    // them to the other half of the banks.
+    auto swz = [](int off) { return off ^ (((off >> (6 + LR)) & 1) << 7); };
+    auto fetch_x = [&](u32x4 (&st)[XL], int64_t it) {
+#pragma unroll
+        for (int x = 0; x < XL; ++x) {
+            if (st_off[x] >= 0) {
+                int64_t off = it * XT + (st_off[x] - lane * 16);
+                if (off > x_last) off = x_last;
+                st[x] = *reinterpret_cast<const u32x4*>(a.Xcell + off + lane * 16);
+            }
+        }
+    };
+    auto store_x = [&](const u32x4 (&st)[XL], int buf) {
+#pragma unroll
+        for (int x = 0; x < XL; ++x)
+            if (st_off[x] >= 0) *reinterpret_cast<u32x4*>(xlds + buf * XT + swz(st_off[x])) = st[x];
+    };
+    // operand read: cell 32 wk + 8 c + 4 hh + s of the stage, token row trow
+    const int rd_base = (((32 * wk + 4 * hh) << LR) + trow) << 4;
+    const int rd_flip = hh << 7;                     // swz() of an operand address: its cell has bit 2 = hh
+
+    auto load_wc = [&](int g, int64_t tile, int c) {
+        return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrec[g] + tile * kWRecordBytes + c * 1024));
+    };
+    auto load_we = [&](int g, int64_t tile) {
+        return __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(wrec[g] + tile * kWRecordBytes + kWExpOffset + e_adj));
+    };
+
+    f32x16 acc[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[g][r] = 0.f;
+
+    // ---- rank-kp correction, part 1: fetch its operands first ---------------------------------------
+    // The correction is 2 kp more "K columns" in 64-wide chunks of [T_hi | T_lo].  Lane half hh owns
+    // rank blocks jb = 4 ch + 2 hh + {0, 1} of chunk ch: jb < kp16 is T_hi for ranks 16 jb..,
+    // otherwise T_lo for ranks 16 (jb - kp16)...  Job j = g * nchunks + ch of this wavefront's column
+    // groups goes to K slice j % NWK (every slice holds a partial sum of every group).
+    const int nb2 = 2 * a.kp16;
+    const int nchunks = (nb2 + 3) / 4;               // 0, 1 or 2
+    constexpr int NJ = (2 * G + NWK - 1) / NWK;
+    u32x4 tail_cw[NJ][2];
+    uint32_t tail_eb[NJ][2];
+#pragma unroll
+    for (int q = 0; q < NJ; ++q) {
+        const int job = wk + NWK * q;                // wave-uniform
+        const int g = nchunks ? job / nchunks : 0, ch = nchunks ? job % nchunks : 0;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            tail_cw[q][j] = u32x4{0, 0, 0, 0};
+            tail_eb[q][j] = 0;
+            const int jb = 4 * ch + 2 * hh + j;
+            if (job < G * nchunks && jb < nb2) {
+                const int rb = jb >= a.kp16 ? jb - a.kp16 : jb;
+                int64_t grp = g0 + g;
+                if (grp >= a.N32) grp = a.N32 - 1;
+                const uint8_t* rec = a.Bt + (grp * a.kp16 + rb) * kBRecordBytes;
+                tail_cw[q][j] = *reinterpret_cast<const u32x4*>(rec + t * 16);
+                tail_eb[q][j] = rec[512 + t];
+            }
+        }
+    }
+    // T: the workgroup adds the S (<= 8) partial sums of the projection kernel in slice order and
+    // leaves T_hi | T_lo as bf16 in LDS.  One item = 4 consecutive ranks of a token.
+    constexpr int TI = (32 * 16 + NW * 64 - 1) / (NW * 64);
+    constexpr int SMAX = 8;
+    const int t_rows = a.M < 32 ? (int)a.M : 32;
+    const int kp4 = a.kp >> 2;
+    const int t_items = t_rows * kp4;
+    // The loads are issued here; the sums are formed (finish_t) once the first weight loads are on
+    // their way, so that those do not wait for this round trip.
+    f32x4 tpart[TI][SMAX];
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+        const int item = threadIdx.x + i * NW * 64;
+#pragma unroll
+        for (int sl = 0; sl < SMAX; ++sl) {
+            tpart[i][sl] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (item < t_items && sl < a.S)
+                tpart[i][sl] = *reinterpret_cast<const f32x4*>(a.Tpart + (int64_t)sl * a.M * a.kp + 4 * item);
+        }
+    }
+    auto finish_t = [&]() {
+#pragma unroll
+        for (int i = 0; i < TI; ++i) {
+            const int item = threadIdx.x + i * NW * 64;
+            if (item >= t_items) continue;
+            const int row = item / kp4, r4 = item - row * kp4;
+            f32x4 sum = tpart[i][0];
+#pragma unroll
+            for (int sl = 1; sl < SMAX; ++sl) {
+                sum[0] += tpart[i][sl][0]; sum[1] += tpart[i][sl][1];
+                sum[2] += tpart[i][sl][2]; sum[3] += tpart[i][sl][3];
+            }
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t hb = f32_bits(sum[e]) & 0xFFFF0000u;
+                hi[e] = hb >> 16;
+                lo[e] = f32_bits(sum[e] - f32_from_bits(hb)) >> 16;
+            }
+            uint16_t* dst = tlds + row * 2 * a.kp + 4 * r4;
+            *reinterpret_cast<u32x2*>(dst) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+            *reinterpret_cast<u32x2*>(dst + a.kp) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+        }
+    };
+
+    // ---- main product ----------------------------------------------------------------------------
+    // DT register sets hold the weight records of DT consecutive steps; set it % DT serves step it and
+    // is refilled chunk by chunk with the tile of step it + DT.
+    {
+        u32x4 wcd[DT][G][4];         // packed codes, chunk by chunk
+        u32x2 wex[DT][G];            // exponent bytes
+        {
+            u32x4 st[XL];
+            fetch_x(st, 0);
+#pragma unroll
+            for (int g = 0; g < G; ++g) wex[0][g] = load_we(g, tile_at(0));
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int g = 0; g < G; ++g) wcd[0][g][c] = load_wc(g, tile_at(0), c);
+            if constexpr (DT == 2) {
+                if (NI > 1) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) wex[1][g] = load_we(g, tile_at(1));
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+#pragma unroll
+                        for (int g = 0; g < G; ++g) wcd[1][g][c] = load_wc(g, tile_at(1), c);
+                }
+            }
+            finish_t();
+            store_x(st, 0);
+        }
+        // PFX: the step fetches the activations of the next one; PFW: it refills its weight set
+        auto step = [&](u32x4 (&wc_)[G][4], u32x2 (&we_)[G], int64_t it, auto pfx, auto pfw) {
+            constexpr bool PFX = decltype(pfx)::value, PFW = decltype(pfw)::value;
+            __syncthreads();         // stage it % 2 is complete; the other one is free again
+            u32x4 st[XL];
+            u32x2 wen[G];
+            const int64_t nt = tile_at(it + DT);
+            if constexpr (PFX) fetch_x(st, it + 1);
+            if constexpr (PFW) {
+#pragma unroll
+                for (int g = 0; g < G; ++g) wen[g] = load_we(g, nt);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const bool live = wk + NWK * it < a.KT;
+            const uint8_t* xs = xlds + (ONE ? 0 : (int)(it & 1) * XT);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (live) {
+                    Frag xf[4];
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+                        {
+                        // for 16 rows and more the operand offsets are multiples of 256 B and leave bit 7 alone
+                        const int off = (8 * c + s) << (LR + 4);
+                        const int ad = (LR >= 4) ? ((rd_base ^ rd_flip) + off) : ((rd_base + off) ^ rd_flip);
+                        xf[s].u = *reinterpret_cast<const u32x4*>(xs + ad);
+                    }
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+#pragma unroll
+                        for (int s = 0; s < 4; ++s) {
+                            const uint32_t ew = we_[g][c >> 1] >> (16 * (c & 1) + 8 * (s >> 1));
+                            const bf16x8 wv = unpack_w8(wc_[g][c][s], w_scale(ew & 0xFFu));
+                            acc[g] = mfma32(wv, xf[s].v, acc[g]);
+                        }
+                    }
+                }
+                if constexpr (PFW) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) wc_[g][c] = load_wc(g, nt, c);
+                }
+            }
+            if constexpr (PFX) store_x(st, (int)((it + 1) & 1));    // waits for the activation loads only
+            if constexpr (PFW) {
+#pragma unroll
+                for (int g = 0; g < G; ++g) we_[g] = wen[g];
+            }
+        };
+        constexpr std::true_type Y_{};
+        constexpr std::false_type N_{};
+        if constexpr (ONE) {
+            step(wcd[0], wex[0], 0, N_, N_);
+        } else if constexpr (DT == 1) {
+            for (int64_t it = 0; it + 1 < NI; ++it) step(wcd[0], wex[0], it, Y_, Y_);
+            step(wcd[0], wex[0], NI - 1, N_, N_);
+        } else {
+            int64_t it = 0;
+            for (; it + 3 < NI; it += 2) {
+                step(wcd[0], wex[0], it, Y_, Y_);
+                step(wcd[1], wex[1], it + 1, Y_, Y_);
+            }
+            // one to three steps remain; the tile of step it + j sits in set j % 2
+            if (it + 1 == NI) {
+                step(wcd[0], wex[0], it, N_, N_);
+            } else if (it + 2 == NI) {
+                step(wcd[0], wex[0], it, Y_, N_);
+                step(wcd[1], wex[1], it + 1, N_, N_);
+            } else {
+                step(wcd[0], wex[0], it, Y_, Y_);
+                step(wcd[1], wex[1], it + 1, Y_, N_);
+                step(wcd[0], wex[0], it + 2, N_, N_);
+            }
+        }
+    }
+
+    // ---- rank-kp correction, part 2: the arithmetic ---------------------------------------------------
+#pragma unroll
+    for (int q = 0; q < NJ; ++q) {
+        const int job = wk + NWK * q;
+        if (job >= G * nchunks) continue;
+        const int g = job / nchunks, ch = job % nchunks;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int jb = 4 * ch + 2 * hh + j;
+            Frag ta[2];
+            ta[0].u = u32x4{0, 0, 0, 0};
+            ta[1].u = u32x4{0, 0, 0, 0};
+            if (jb < nb2) {
+                const uint16_t* src = tlds + trow * 2 * a.kp + 16 * jb;
+                ta[0].u = *reinterpret_cast<const u32x4*>(src);
+                ta[1].u = *reinterpret_cast<const u32x4*>(src + 8);
+            }
+            Frag bf[2];
+            int8x16_to_frags(tail_cw[q][j], h_scale(tail_eb[q][j]), bf[0], bf[1]);
+            // g is wave-uniform: pick the accumulator by unrolled comparison so all stay in registers
+#pragma unroll
+            for (int gg = 0; gg < G; ++gg) {
+                if (gg == g) {
+                    acc[gg] = mfma32(bf[0].v, ta[0].v, acc[gg]);
+                    acc[gg] = mfma32(bf[1].v, ta[1].v, acc[gg]);
+                }
+            }
+        }
+    }
+
+    // ---- add the K slices of every column group in slice order -----------------------------------------
+    // every wavefront leaves its partial sums in LDS; wavefront v then finishes unit v, v + NW, ... where
+    // unit u = (column group u / 4 of the workgroup, accumulator quarter u % 4)
+    __syncthreads();                                 // every wavefront is done with the activation stages
+    auto red_at = [&](int k, int q, int r4) {
+        return reinterpret_cast<f32x4*>(red + ((((size_t)k * NG + q) * 64 + lane) * 16 + 4 * r4));
+    };
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4)
+            *red_at(wk, wc * G + g, r4) = f32x4{acc[g][4 * r4], acc[g][4 * r4 + 1], acc[g][4 * r4 + 2], acc[g][4 * r4 + 3]};
+    __syncthreads();
+    for (int u = wave; u < NG * 4; u += NW) {
+        const int q = u >> 2, r4 = u & 3;
+        f32x4 v = *red_at(0, q, r4);
+#pragma unroll
+        for (int k = 1; k < NWK; ++k) {
+            const f32x4 o = *red_at(k, q, r4);
+            v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
+        }
+        const int64_t grp = (int64_t)blockIdx.x * NG + q;
+        if (grp < a.N32 && t < a.M) {
+            const int64_t n = grp * 32 + 8 * r4 + 4 * hh;              // this lane's 4 consecutive columns
+            float* dst = a.Y + (int64_t)t * a.ldy + n;
+            if (n + 3 < a.N) {
+                *reinterpret_cast<f32x4*>(dst) = v;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (n + j < a.N) dst[j] = v[j];
+            }
+        }
+    }
+}
+
+int stream_max_rows() { return 32; }
+int stream_cell_rows_log2(int64_t M) { return M <= 4 ? 2 : (M <= 16 ? 4 : 5); }
+
+template <int G, int NWC, int NWK, int DT, int LR, bool ONE>
+static hipError_t launch_stream_t(const StreamArgs& a, hipStream_t s) {
+    constexpr int STAGING = (ONE ? 1 : 2) * NWK * (1 << LR) * 512;
+    constexpr int REDUCE = NWK * NWC * G * 4096;
+    constexpr int LDS_BYTES = 32 * 128 * 2 + (STAGING > REDUCE ? STAGING : REDUCE);
+    if constexpr (LDS_BYTES > 160 * 1024) {
+        return hipErrorInvalidValue;                 // this shape does not fit the 160 KB of LDS
+    } else {
+        auto kern = stream_kernel<G, NWC, NWK, DT, LR, ONE>;
+        static bool attr_set = false;
+        if (!attr_set) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        dim3 grid((unsigned)((a.N32 + NWC * G - 1) / (NWC * G))), block(64 * NWC * NWK);
+        hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, s, a);
+        return hipGetLastError();
+    }
+}
+
+template <int G, int NWC, int NWK, int DT>
+static hipError_t launch_stream_rows(const StreamArgs& a, hipStream_t s) {
+    if constexpr (DT == 1) {
+        if (a.KT <= NWK) {
+            switch (stream_cell_rows_log2(a.M)) {
+                case 2: return launch_stream_t<G, NWC, NWK, 1, 2, true>(a, s);
+                case 4: return launch_stream_t<G, NWC, NWK, 1, 4, true>(a, s);
+                default: return launch_stream_t<G, NWC, NWK, 1, 5, true>(a, s);
+            }
+        }
+    }
+    switch (stream_cell_rows_log2(a.M)) {
+        case 2: return launch_stream_t<G, NWC, NWK, DT, 2, false>(a, s);
+        case 4: return launch_stream_t<G, NWC, NWK, DT, 4, false>(a, s);
+        default: return launch_stream_t<G, NWC, NWK, DT, 5, false>(a, s);
+    }
+}
+
+hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
+                         int variant, hipStream_t s) {
+    if (M == 0) return hipSuccess;
+    StreamArgs a;
+    a.Wt = L.Wt; a.Bt = L.Bt; a.Xcell = reinterpret_cast<const uint8_t*>(ws.Xh);
+    a.Tpart = ws.Tpart; a.S = ws.S;
+    a.Y = Y; a.ldy = ldy; a.M = M; a.N = L.N; a.KT = L.KT; a.N32 = L.N32; a.kp = L.kp; a.kp16 = L.kp16;
+    // variant = 10000 + 1000 G + 100 NWC + 10 (NWK % 16) + DT: G column groups per wavefront, NWC x NWK
+    // wavefronts per workgroup, weights DT steps ahead.  0 = automatic.
+    int v = variant;
+    if (v == 0) {
+        if ((L.N32 + 3) / 4 >= 200) v = 12241;       // wide layers
+        else if ((L.N32 + 1) / 2 >= 160) v = (M <= 16) ? 12181 : 12141;
+        else if (L.KT <= 16 && M <= 16) v = 11101;   // short and narrow: the whole K range in one step
+        else v = (M <= 16) ? 11181 : 11241;
+    }
+    switch (v) {
+        case 11441: return launch_stream_rows<1, 4, 4, 1>(a, s);
+        case 11421: return launch_stream_rows<1, 4, 2, 1>(a, s);
+        case 12241: return launch_stream_rows<2, 2, 4, 1>(a, s);
+        case 12242: return launch_stream_rows<2, 2, 4, 2>(a, s);
+        case 12181: return launch_stream_rows<2, 1, 8, 1>(a, s);
+        case 12141: return launch_stream_rows<2, 1, 4, 1>(a, s);
+        case 11181: return launch_stream_rows<1, 1, 8, 1>(a, s);
+        case 11101: return launch_stream_rows<1, 1, 16, 1>(a, s);
+        case 11281: return launch_stream_rows<1, 2, 8, 1>(a, s);
+        case 11241: return launch_stream_rows<1, 2, 4, 1>(a, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace lqer

@@ -32,8 +32,9 @@ struct TiledArgs {
     int group_m;
 };
 
-template <int TM, int TN, int WR, int WC, int NS>
-__global__ __launch_bounds__(64 * WR * WC) void tiled_kernel(TiledArgs a) {
+// MINW = wavefronts per SIMD the register allocation must allow (2 lets two four-wavefront workgroups share a compute unit)
+template <int TM, int TN, int WR, int WC, int NS, int MINW>
+__global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) {
     constexpr int BM = 32 * TM * WR;
     constexpr int NW = WR * WC;
     constexpr int STAGE = BM * 128;                // bytes: BM rows x 64 bf16
@@ -283,14 +284,14 @@ __global__ __launch_bounds__(64 * WR * WC) void tiled_kernel(TiledArgs a) {
     }
 }
 
-template <int TM, int TN, int WR, int WC, int NS>
+template <int TM, int TN, int WR, int WC, int NS, int MINW = 1>
 static hipError_t launch_tiled_t(TiledArgs a, int64_t M, hipStream_t s) {
     constexpr int BM = 32 * TM * WR, BN = 32 * TN * WC;
     constexpr int LDS_BYTES = NS * BM * 128;
     a.grid_m = (int)((M + BM - 1) / BM);
     a.grid_n = (int)((a.N + BN - 1) / BN);
     a.group_m = 8;
-    auto kern = tiled_kernel<TM, TN, WR, WC, NS>;
+    auto kern = tiled_kernel<TM, TN, WR, WC, NS, MINW>;
     static bool attr_set = false;
     if (!attr_set) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -336,6 +337,7 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
         case 5: return launch_tiled_t<2, 4, 4, 2, 4>(a, M, s);      // 256 x 256, eight wavefronts
         case 6: return launch_tiled_t<2, 2, 4, 2, 4>(a, M, s);      // 256 x 128, eight wavefronts
         case 7: return launch_tiled_t<2, 4, 2, 4, 4>(a, M, s);      // 128 x 512, eight wavefronts
+        case 8: return launch_tiled_t<2, 4, 2, 2, 4, 2>(a, M, s);   // 128 x 256, two workgroups per compute unit
         default: return hipErrorInvalidValue;
     }
 }

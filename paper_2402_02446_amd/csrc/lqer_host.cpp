@@ -238,23 +238,27 @@ static int download(const uint8_t* dev, size_t bytes, std::vector<uint8_t>& host
     return LQER_OK;
 }
 
+// path 1 = streaming kernel (activations as 16-byte cells, T as partial sums), 2 = tiled
 static Workspace plan_workspace(const Layer& L, int64_t M, int path, void* base) {
     Workspace ws;
     ws.ldxh = L.KT * kTileK + round_up(2 * (int64_t)L.kp, 64);
     ws.S = prep_slices(L, M, path);
+    ws.cells = (path == 1);
+    ws.lr = stream_cell_rows_log2(M);
     // the tiled kernel reads whole 256-row tiles of Xh (rows past M hold whatever was there)
-    const int64_t xh_rows = (path == 2) ? round_up(M, 256) : M;
+    const int64_t xh_rows = (path == 2) ? round_up(M, 256) : (ws.cells ? (int64_t)1 << ws.lr : M);
     const size_t xh_bytes = (size_t)round_up(xh_rows * ws.ldxh * 2, 256);
-    const size_t tp_bytes = (ws.S > 1) ? (size_t)round_up((int64_t)ws.S * M * L.kp * 4, 256) : 0;
+    const bool partial = (path == 1) && L.kp > 0;
+    const size_t tp_bytes = partial ? (size_t)round_up((int64_t)ws.S * M * L.kp * 4, 256) : 0;
     ws.Xh = (uint16_t*)base;
-    ws.Tpart = (ws.S > 1) ? (float*)((uint8_t*)base + xh_bytes) : nullptr;
+    ws.Tpart = partial ? (float*)((uint8_t*)base + xh_bytes) : nullptr;
     ws.bytes = xh_bytes + tp_bytes;
     return ws;
 }
 
 static int pick_path(const Layer& L, int64_t M) {
     (void)L;
-    return (M <= skinny_max_rows()) ? 1 : 2;
+    return (M <= stream_max_rows()) ? 1 : 2;
 }
 
 static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, const int8_t* Xc,
@@ -278,7 +282,7 @@ static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, co
     int stages = opts ? opts->stages : 0;
     if (path < 0 || path > 2 || (stages & ~3) != 0) return LQER_ERR_SHAPE;
     if (path == 0) path = pick_path(L, M);
-    if (path == 1 && M > skinny_max_rows()) return LQER_ERR_SHAPE;
+    if (path == 1 && M > stream_max_rows()) return LQER_ERR_SHAPE;
     if (stages == 0) stages = 3;
     if (!wsp || ((uintptr_t)wsp & 255) != 0) return LQER_ERR_WORKSPACE;
     const Workspace ws = plan_workspace(L, M, path, wsp);
@@ -288,7 +292,7 @@ static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, co
         if (launch_prep(L, X, ldx, Xc, Xe, M, ws, s) != hipSuccess) return LQER_ERR_HIP;
     }
     if (stages & 2) {
-        const hipError_t e = (path == 1) ? launch_skinny(L, M, ws, Y, ldy, variant, s)
+        const hipError_t e = (path == 1) ? launch_stream(L, M, ws, Y, ldy, variant, s)
                                          : launch_tiled(L, M, ws, Y, ldy, variant, s);
         if (e == hipErrorInvalidValue) return LQER_ERR_SHAPE;
         if (e != hipSuccess) return LQER_ERR_HIP;
@@ -419,7 +423,7 @@ size_t lqer_linear_workspace_bytes(const lqer_layer* layer, int64_t M) {
     if (!layer || M <= 0) return 0;
     const Layer& L = layer->L;
     size_t best = plan_workspace(L, M, 2, nullptr).bytes;
-    if (M <= skinny_max_rows()) {
+    if (M <= stream_max_rows()) {
         const size_t b1 = plan_workspace(L, M, 1, nullptr).bytes;
         if (b1 > best) best = b1;
     }

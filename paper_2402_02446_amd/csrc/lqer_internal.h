@@ -63,8 +63,10 @@ struct Layer {
 struct Workspace {
     int64_t ldxh;        // row stride of Xh in bf16 elements = KT*256 + roundup(2*kp, 64)
     int S;               // K slices of the T partial sums (1 = T final, written into Xh)
-    uint16_t* Xh;        // [M][ldxh] bf16 : dequantized X_q | T_hi | T_lo
-    float* Tpart;        // [S][M][kp] fp32 (only when S > 1)
+    uint16_t* Xh;        // [M][ldxh] bf16 : dequantized X_q | T_hi | T_lo; or cells (below)
+    float* Tpart;        // [S][M][kp] fp32 partial sums of T (streaming path), else null
+    bool cells;          // streaming kernel: Xh holds 16-byte cells [KT*32][1 << lr token rows]
+    int lr;
     size_t bytes;
 };
 
@@ -78,13 +80,14 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
                        int64_t M, const Workspace& ws, hipStream_t s);
 
 // Streaming (small M) main kernel.  variant 0 = automatic.
-hipError_t launch_skinny(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
+hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
                          int variant, hipStream_t s);
+int stream_max_rows();
+int stream_cell_rows_log2(int64_t M);
 // Tiled MFMA (large M) main kernel.
 hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
                         int variant, hipStream_t s);
 
-int skinny_max_rows();      // largest M the streaming kernel accepts
 int prep_slices(const Layer& L, int64_t M, int path);
 
 }  // namespace lqer

@@ -48,18 +48,34 @@ def test_streaming_kernel_row_counts(M):
     h.free()
 
 
+STREAM_VARIANTS = [11441, 11421, 12241, 12242, 12181, 12141, 11181, 11101, 11281, 11241]
+
+
 @pytest.mark.parametrize("K,N,k", [(48, 40, 0), (272, 100, 8), (1024, 272, 64), (2304, 528, 33), (4096, 64, 16)])
-@pytest.mark.parametrize("ng", [802, 404, 402, 208, 204, 116, 108, 104])
-def test_streaming_kernel_shapes(K, N, k, ng):
+@pytest.mark.parametrize("M", [3, 5, 20])
+@pytest.mark.parametrize("variant", STREAM_VARIANTS)
+def test_streaming_kernel_shapes(K, N, k, M, variant):
+    # variant = 10000 + 1000 G + 100 NWC + 10 (NWK % 16) + DT; a shape whose activation stages do not
+    # fit the 160 KB of LDS must be refused, every other one must match the oracle
+    from paper_2402_02446_amd import binding
+    nwk = (variant // 10) % 10 or 16
+    rows = 4 if M <= 4 else (16 if M <= 16 else 32)
+    kt = (K + 255) // 256
+    stages = 1 if (variant % 10 == 1 and kt <= nwk) else 2
+    g, nwc = (variant // 1000) % 10, (variant // 100) % 10
+    lds = 8192 + max(stages * nwk * rows * 512, nwk * nwc * g * 4096)
     layer, ch = oracle_layer_small(K, N, k, seed=K + k)
     h = upload(layer)
-    M = 3 if ng == 116 else 5            # 16 K slices only fit the 4-row staging buffers
     X = synth.gen_activations(np.random.default_rng(1), M, K, ch, 30.0)
-    _assert_close(_gpu_forward(h, X, path=1, variant=ng), forward.forward(X, layer))
+    if lds > 160 * 1024:
+        with pytest.raises(binding.LqerError):
+            _gpu_forward(h, X, path=1, variant=variant)
+    else:
+        _assert_close(_gpu_forward(h, X, path=1, variant=variant), forward.forward(X, layer))
     h.free()
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8])
 @pytest.mark.parametrize("M,K,N,k", [(16, 512, 512, 8), (300, 272, 200, 0), (513, 1024, 528, 64), (100, 2304, 40, 33)])
 def test_tiled_kernel_shapes(variant, M, K, N, k):
     layer, ch = oracle_layer_small(K, N, k, seed=M + variant)
