@@ -72,7 +72,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     for (int g = 0; g < G; ++g) {
         int64_t grp = g0 + g;
         if (grp >= a.N32) grp = a.N32 - 1;
-        wrec[g] = a.Wt + grp * a.KT * kWRecordBytes + lane * 16;
+        wrec[g] = a.Wt + grp * kWRecordBytes + lane * 16;
     }
     const int e_adj = -(lane * 8);                   // exponent words sit at lane * 8, not lane * 16
     int trow = t;
@@ -115,11 +115,12 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     const int rd_base = (((32 * wk + 4 * hh) << LR) + trow) << 4;
     const int rd_flip = hh << 7;                     // swz() of an operand address: its cell has bit 2 = hh
 
+    const int64_t tile_stride = a.N32 * kWRecordBytes;             // records are ordered [K tile][column group]
     auto load_wc = [&](int g, int64_t tile, int c) {
-        return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrec[g] + tile * kWRecordBytes + c * 1024));
+        return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrec[g] + tile * tile_stride + c * 1024));
     };
     auto load_we = [&](int g, int64_t tile) {
-        return __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(wrec[g] + tile * kWRecordBytes + kWExpOffset + e_adj));
+        return __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(wrec[g] + tile * tile_stride + kWExpOffset + e_adj));
     };
 
     f32x16 acc[G];

@@ -113,14 +113,14 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         const int cc = (int)(ch & 3);
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
-            const uint8_t* rec = a.Wt + (group_of(tn) * a.KT + tile) * kWRecordBytes;   // wave-uniform
+            const uint8_t* rec = a.Wt + (tile * a.N32 + group_of(tn)) * kWRecordBytes;   // wave-uniform
             w.c[tn] = *reinterpret_cast<const u32x4*>(rec + cc * 1024 + lane16);
         }
     };
     auto load_eset = [&](ESet& x, int64_t tile) {
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
-            const uint8_t* rec = a.Wt + (group_of(tn) * a.KT + tile) * kWRecordBytes;
+            const uint8_t* rec = a.Wt + (tile * a.N32 + group_of(tn)) * kWRecordBytes;
             x.e[tn] = *reinterpret_cast<const u32x2*>(rec + kWExpOffset + (lane16 >> 1));
         }
     };
@@ -312,20 +312,22 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
     a.M = M; a.N = L.N; a.KT = L.KT; a.N32 = L.N32; a.kp16 = L.kp16;
     a.grid_m = a.grid_n = 0; a.group_m = 8;
     if (variant == 0) {
-        // Pick the tile shape with the lowest estimated time: whole rounds of workgroups over the
-        // 256 compute units, times the tile area, over the rate that shape sustains when the chip
-        // is full (TFLOP/s measured on an 8192 x 28672 layer at M = 4096).
-        struct Shape { int id, bm, bn, per_cu; double rate; };
+        // Pick the tile shape with the lowest estimated time.  Tiles spread evenly over the 256
+        // compute units, so the busiest one gets n = ceil(tiles / 256) of them; a shape of which two
+        // workgroups share a compute unit runs them in pairs at rate `pair` and a last odd one at
+        // rate `single` (TFLOP/s of the whole chip, measured on an 8192 x 28672 layer at M = 4096).
+        struct Shape { int id, bm, bn, share; double pair, single; };
         static const Shape shapes[] = {
-            {1, 256, 256, 1, 1140.0}, {3, 128, 256, 1, 1076.0}, {4, 128, 128, 2, 1058.0},
-            {6, 256, 128, 1, 1009.0}, {7, 128, 512, 1, 1296.0},
+            {1, 256, 256, 1, 0.0, 1213.0}, {3, 128, 256, 1, 0.0, 1084.0}, {7, 128, 512, 1, 0.0, 1296.0},
+            {4, 128, 128, 2, 1058.0, 900.0}, {8, 128, 256, 2, 1261.0, 1084.0},
         };
         double best = 0.0;
         for (const Shape& sh : shapes) {
             const int64_t tiles = ((M + sh.bm - 1) / sh.bm) * ((L.N + sh.bn - 1) / sh.bn);
-            const int64_t slots = 256 * (int64_t)sh.per_cu;
-            const int64_t rounds = (tiles + slots - 1) / slots;
-            const double t = (double)rounds * sh.per_cu * sh.bm * sh.bn / sh.rate;
+            const int64_t n = (tiles + 255) / 256;
+            const double w = (double)sh.bm * sh.bn;
+            const double t = (sh.share == 2) ? (double)(n / 2) * 2.0 * w / sh.pair + (double)(n % 2) * w / sh.single
+                                             : (double)n * w / sh.single;
             if (variant == 0 || t < best) { best = t; variant = sh.id; }
         }
     }

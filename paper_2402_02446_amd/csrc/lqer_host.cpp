@@ -56,7 +56,7 @@ static int tile_weights(const Layer& L, const uint8_t* Wc, const uint8_t* We, st
     std::atomic<int> bad{0};
     parallel_for(L.N32, [&](int64_t g) {
         for (int64_t tile = 0; tile < L.KT; ++tile) {
-            uint8_t* rec = out.data() + (size_t)(g * L.KT + tile) * kWRecordBytes;
+            uint8_t* rec = out.data() + (size_t)(tile * L.N32 + g) * kWRecordBytes;
             for (int lane = 0; lane < 64; ++lane) {
                 const int i = lane & 31, hh = lane >> 5;
                 const int64_t n = g * 32 + i;
@@ -91,7 +91,7 @@ static void untile_weights(const Layer& L, const std::vector<uint8_t>& in, uint8
     const int64_t nblk = L.K / 16;
     parallel_for(L.N32, [&](int64_t g) {
         for (int64_t tile = 0; tile < L.KT; ++tile) {
-            const uint8_t* rec = in.data() + (size_t)(g * L.KT + tile) * kWRecordBytes;
+            const uint8_t* rec = in.data() + (size_t)(tile * L.N32 + g) * kWRecordBytes;
             for (int lane = 0; lane < 64; ++lane) {
                 const int i = lane & 31, hh = lane >> 5;
                 const int64_t n = g * 32 + i;

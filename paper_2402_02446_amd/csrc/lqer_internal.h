@@ -21,7 +21,8 @@ namespace lqer {
 //   codes[4 chunks][64 lanes][16 B]  lane's 16 B = blocks (4c + 2hh), (4c + 2hh + 1) of the tile,
 //                                    two 32-bit words (8 elements each) per block
 //   exps[64 lanes][8 B]              byte 2c + j = exponent byte of block 4c + 2hh + j
-//   records are ordered [column group][K tile].
+//   records are ordered [K tile][column group]: what the streaming kernel reads at one time is then one
+//   contiguous range (a few percent more HBM bandwidth than group-major order).
 //
 // A 32-bit code word holds 8 consecutive K elements e0..e7 as sign-magnitude nibbles placed so
 // that two mask operations yield fp8 (E4M3) subnormal bytes  s0000mmm = +-m * 2^-9:
