@@ -198,3 +198,58 @@ def test_cfg3_prefill_sampled_rows(name):
     _assert_close(Y[rows], oracle_rows(X[rows], layer))
     assert np.all(np.isfinite(Y))
     h.free()
+
+
+def test_cfg4_70b_shape_sampled():
+    # LLaMA-2-70B-shaped MLP (8192 x 28672, k = 64) at M = 1, 16 (streaming kernel) and 4096 (tiled):
+    # seeded packed bytes, the oracle evaluated on sampled rows and columns (every tile edge included)
+    import torch
+    from paper_2402_02446_amd import binding
+    from helpers import oracle_forward_cols
+    K, N, k = 8192, 28672, 64
+    rng = np.random.default_rng(4)
+    d = synth.random_packed_layer(rng, K, N, k)
+    layer = factors.PackedLayer(**d)
+    h = upload(layer)
+    ch = synth.gen_outlier_channels(rng, K, round(0.01 * K))
+    cols = np.unique(np.r_[0, 31, 32, 127, 128, 255, 256, 511, 512, N - 33, N - 1, rng.integers(0, N, 40)])
+    for M in (1, 16, 4096):
+        X = synth.gen_activations(np.random.default_rng(M), M, K, ch, 50.0)
+        assert binding.lqer_linear_path(h, M) == (1 if M <= 32 else 2)
+        Y = _gpu_forward(h, X)
+        assert np.all(np.isfinite(Y))
+        rows = np.arange(M) if M <= 16 else np.unique(np.r_[0, 127, 128, 2047, 2048, M - 1, rng.integers(0, M, 10)])
+        _assert_close(Y[np.ix_(rows, cols)], oracle_forward_cols(X[rows], layer, cols))
+    h.free()
+
+
+def test_forward_in_hip_graph_replays():
+    # The forward pass allocates nothing and uses only the caller's stream, so it can be captured in a
+    # HIP graph (the benchmark times it that way).  Every replay must reproduce the eager result,
+    # with eager work and synchronisations between the replays.
+    import torch
+    from paper_2402_02446_amd import binding
+    layer, ch = oracle_layer_small(1024, 272, 32, seed=12)
+    h = upload(layer)
+    for M in (5, 200):
+        X = torch.from_numpy(synth.gen_activations(np.random.default_rng(M), M, 1024, ch, 30.0)).cuda()
+        X2 = torch.from_numpy(synth.gen_activations(np.random.default_rng(M + 1), M, 1024, ch, 30.0)).cuda()
+        Y_eager = binding.lqer_linear_forward(h, X).clone()
+        Y2_eager = binding.lqer_linear_forward(h, X2).clone()
+        torch.cuda.synchronize()
+        Xg = X.clone()
+        Yg = torch.empty_like(Y_eager)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            binding.lqer_linear_forward(h, Xg, Y=Yg)
+        for rep, (src, want) in enumerate([(X, Y_eager), (X2, Y2_eager), (X, Y_eager)]):
+            Xg.copy_(src)
+            Yg.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(Yg, want), f"replay {rep} differs from the eager result (M={M})"
+            _ = binding.lqer_linear_forward(h, X2)       # eager work between replays
+            torch.cuda.synchronize()
+        del g
+    h.free()
