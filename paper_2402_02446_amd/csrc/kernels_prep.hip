@@ -28,6 +28,7 @@ struct PrepArgs {
     uint16_t* Xh; int64_t ldxh;
     int64_t tail_cols;     // columns behind K_pad in Xh (T_hi | T_lo | zero padding)
     float* Tpart;
+    int64_t tp_rows;       // rows per slice of Tpart
     int lr;                // CELLS: log2 of the token rows per 16-byte cell column
 };
 
@@ -178,7 +179,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
                 *reinterpret_cast<u32x2*>(base + a.kp + r0) =
                     u32x2{(uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)};
             } else {
-                *reinterpret_cast<f32x4*>(a.Tpart + ((int64_t)slice * a.M + orow) * a.kp + r0) = s;
+                *reinterpret_cast<f32x4*>(a.Tpart + ((int64_t)slice * a.tp_rows + orow) * a.kp + r0) = s;
             }
         }
     }
@@ -193,7 +194,14 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
 }
 
 int prep_slices(const Layer& L, int64_t M, int path) {
-    if (path != 1) return 1;
+    if (path != 1) {
+        // tiled path: one workgroup per 16 token rows; when that leaves compute units idle, split K
+        // as well (each slice keeps at least two tiles) and let the tiled kernel add the partial T
+        const int64_t rg = (M + 15) / 16;
+        int64_t s = 1;
+        while (rg * s < 512 && s < 8 && L.KT / (2 * s) >= 2) s *= 2;
+        return (int)s;
+    }
     // streaming path: at most two row groups, so K is spread over workgroups (the main kernel adds
     // up to 8 partial sums); one wavefront per K tile of a slice, at most kPrepWaves.
     int64_t s = L.KT;
@@ -214,9 +222,10 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     a.At = L.At; a.Xh = ws.Xh; a.ldxh = ws.ldxh;
     a.tail_cols = ws.ldxh - L.KT * kTileK;
     a.Tpart = ws.Tpart;
+    a.tp_rows = ws.tp_rows;
     a.lr = ws.lr;
     const bool cells = ws.cells;
-    int nwaves = cells ? a.tiles_per_slice : kPrepWaves;
+    int nwaves = a.tiles_per_slice;
     if (nwaves > kPrepWaves) nwaves = kPrepWaves;
     if (nwaves < 1) nwaves = 1;
     dim3 grid((unsigned)((M + 15) / 16), (unsigned)ws.S, 1);

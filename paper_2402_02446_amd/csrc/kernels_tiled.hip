@@ -25,9 +25,10 @@ namespace lqer {
 struct TiledArgs {
     const uint8_t* Wt; const uint8_t* Bt;
     const uint16_t* Xh; int64_t ldxh;
+    const float* Tpart; int S; int64_t tp_stride;    // S > 1: T as S fp32 partial sums [S][tp_stride / kp rows][kp]
     float* Y; int64_t ldy;
     int64_t M, N, KT, N32;
-    int kp16;
+    int kp, kp16;
     int grid_m, grid_n;
     int group_m;
 };
@@ -128,6 +129,41 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
 #pragma unroll
         for (int j = 0; j < LPT; ++j) st[j] = *reinterpret_cast<const u32x4*>(ld_base + j * ld_stride + ch * 64);
     };
+    // Correction chunk tc when the projection kernel left T as S partial sums (it split K over
+    // workgroups): add them in slice order and form the bf16 term this cell holds - T_hi for tail
+    // columns below kp, T_lo for the next kp, zero behind.
+    auto fetch_t = [&](u32x4 (&st)[LPT], int64_t tc) {
+        const int col = (int)tc * 64 + 8 * (tid & 7);
+        const bool lo = col >= a.kp;
+        const int r0 = lo ? col - a.kp : col;
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            float sum[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum[e] = 0.f;
+            if (col < 2 * a.kp) {
+                const float* src = a.Tpart + (m0 + ld_row0 + j * ROWS_PER_PASS) * a.kp + r0;
+                for (int sl = 0; sl < a.S; ++sl) {
+                    const f32x4 p0 = *reinterpret_cast<const f32x4*>(src + sl * a.tp_stride);
+                    const f32x4 p1 = *reinterpret_cast<const f32x4*>(src + sl * a.tp_stride + 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { sum[e] += p0[e]; sum[4 + e] += p1[e]; }
+                }
+            }
+            uint32_t h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t hb = f32_bits(sum[e]) & 0xFFFF0000u;
+                h[e] = lo ? f32_bits(sum[e] - f32_from_bits(hb)) >> 16 : hb >> 16;
+            }
+            st[j] = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+        }
+    };
+    // any chunk of the activation row: a main one or a correction chunk in either form
+    auto fetch_any = [&](u32x4 (&st)[LPT], int64_t ch) {
+        if (ch < a.KT * 4 || a.S <= 1) fetch_x(st, ch);
+        else fetch_t(st, ch - a.KT * 4);
+    };
     auto store_x = [&](const u32x4 (&st)[LPT], int stage) {
 #pragma unroll
         for (int j = 0; j < LPT; ++j)
@@ -190,12 +226,12 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     // Every load below is issued unconditionally, with its index clamped at the end of the range:
     // a load inside a branch would make the compiler's wait counts assume the worst case and the
     // LDS write at the end of the chunk would wait for the newest weights as well.
-    const int64_t last_chunk = chunks - 1, last_main = main_chunks - 1, last_tile = a.KT - 1;
+    const int64_t last_main = main_chunks - 1, last_tile = a.KT - 1;
     auto step = [&](const WSet& cur, const ESet& ecur, WSet& fill, ESet& enext, int64_t ch, int c) {
         __syncthreads();
         if (ch == 0) read_xa(xa, 0, 0);          // later chunks find step 0 already read by the previous one
         u32x4 st[LPT];
-        fetch_x(st, ch + 2 < last_chunk ? ch + 2 : last_chunk);
+        fetch_x(st, ch + 2 < last_main ? ch + 2 : last_main);
         // loads retire in order: keep the activation loads ahead of the weight loads, so that the
         // LDS write at the end of this chunk does not have to wait for the weights of chunk ch+2
         __builtin_amdgcn_sched_barrier(0);
@@ -218,13 +254,19 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     }
 
     // ---- rank-kp correction: [T_hi | T_lo | 0] against B_k ---------------------------------------
+    // The (at most two) correction chunks are fetched here rather than ahead from the main loop: B_k's
+    // records are needed at the same moment and cost the same memory round trip.  Stages 0 and 1 are
+    // free: every wavefront is past the barrier of the last main chunk, which reads stage 3.
     // lane half hh owns rank blocks jb = 4 cc + 2 hh + {0, 1} of tail chunk cc
-    for (int cc = 0; cc < tail_chunks; ++cc) {
-        const int64_t ch = main_chunks + cc;
+    if (tail_chunks > 0) {
+        u32x4 tst[2][LPT];
+        fetch_any(tst[0], main_chunks);
+        if (tail_chunks > 1) fetch_any(tst[1], main_chunks + 1);
+        store_x(tst[0], 0);
+        if (tail_chunks > 1) store_x(tst[1], 1);
         __syncthreads();
-        u32x4 st[LPT];
-        const bool more_x = ch + 2 < chunks;
-        if (more_x) fetch_x(st, ch + 2);
+    }
+    for (int cc = 0; cc < tail_chunks; ++cc) {
         const uint8_t* stage = lds + (cc & 3) * STAGE;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -255,7 +297,6 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
                     for (int tm = 0; tm < TM; ++tm) acc[tm][tn] = mfma32(bf[tn][h].v, xa[tm].v, acc[tm][tn]);
             }
         }
-        if (more_x) store_x(st, (cc + 2) & 3);
     }
 
     // ---- store: lane (t, hh) holds columns 8 r4 + 4 hh .. + 3 of token t for every MFMA tile ------
@@ -309,7 +350,8 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
     if (M == 0) return hipSuccess;
     TiledArgs a;
     a.Wt = L.Wt; a.Bt = L.Bt; a.Xh = ws.Xh; a.ldxh = ws.ldxh; a.Y = Y; a.ldy = ldy;
-    a.M = M; a.N = L.N; a.KT = L.KT; a.N32 = L.N32; a.kp16 = L.kp16;
+    a.Tpart = ws.Tpart; a.S = ws.S; a.tp_stride = ws.tp_rows * L.kp;
+    a.M = M; a.N = L.N; a.KT = L.KT; a.N32 = L.N32; a.kp = L.kp; a.kp16 = L.kp16;
     a.grid_m = a.grid_n = 0; a.group_m = 8;
     if (variant == 0) {
         // Pick the tile shape with the lowest estimated time.  Tiles spread evenly over the 256

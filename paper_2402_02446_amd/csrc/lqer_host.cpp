@@ -248,8 +248,10 @@ static Workspace plan_workspace(const Layer& L, int64_t M, int path, void* base)
     // the tiled kernel reads whole 256-row tiles of Xh (rows past M hold whatever was there)
     const int64_t xh_rows = (path == 2) ? round_up(M, 256) : (ws.cells ? (int64_t)1 << ws.lr : M);
     const size_t xh_bytes = (size_t)round_up(xh_rows * ws.ldxh * 2, 256);
-    const bool partial = (path == 1) && L.kp > 0;
-    const size_t tp_bytes = partial ? (size_t)round_up((int64_t)ws.S * M * L.kp * 4, 256) : 0;
+    // T travels as partial sums on the streaming path and whenever the projection kernel splits K
+    const bool partial = L.kp > 0 && (path == 1 || ws.S > 1);
+    ws.tp_rows = (path == 2) ? xh_rows : M;
+    const size_t tp_bytes = partial ? (size_t)round_up((int64_t)ws.S * ws.tp_rows * L.kp * 4, 256) : 0;
     ws.Xh = (uint16_t*)base;
     ws.Tpart = partial ? (float*)((uint8_t*)base + xh_bytes) : nullptr;
     ws.bytes = xh_bytes + tp_bytes;

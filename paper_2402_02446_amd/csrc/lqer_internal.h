@@ -65,7 +65,8 @@ struct Workspace {
     int64_t ldxh;        // row stride of Xh in bf16 elements = KT*256 + roundup(2*kp, 64)
     int S;               // K slices of the T partial sums (1 = T final, written into Xh)
     uint16_t* Xh;        // [M][ldxh] bf16 : dequantized X_q | T_hi | T_lo; or cells (below)
-    float* Tpart;        // [S][M][kp] fp32 partial sums of T (streaming path), else null
+    float* Tpart;        // [S][tp_rows][kp] fp32 partial sums of T, or null when T is final in Xh
+    int64_t tp_rows;     // rows per slice of Tpart (M, or M padded to the tile height for the tiled kernel)
     bool cells;          // streaming kernel: Xh holds 16-byte cells [KT*32][1 << lr token rows]
     int lr;
     size_t bytes;
