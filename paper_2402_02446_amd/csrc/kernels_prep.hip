@@ -68,6 +68,22 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
 
     for (int64_t tile = tile_begin + wave; tile < tile_end; tile += nwaves) {
         Frag xf[4][2];                                       // [p][half]
+        // Few-token calls are bound by latency, not bandwidth: request A_k's records before the
+        // activations are even loaded, so that one memory round trip covers both.
+        Frag apre[CELLS ? MAXG : 1][4][2];
+        if constexpr (CELLS) {
+#pragma unroll
+            for (int g = 0; g < MAXG; ++g) {
+                if (g < a.groups_per_wg) {
+                    const uint8_t* rec = a.At + ((int64_t)(g0 + g) * a.KT + tile) * kARecordBytes;
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        apre[g][p][0].u = *reinterpret_cast<const u32x4*>(rec + (2 * p) * 1024 + lane * 16);
+                        apre[g][p][1].u = *reinterpret_cast<const u32x4*>(rec + (2 * p + 1) * 1024 + lane * 16);
+                    }
+                }
+            }
+        }
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int64_t kb = tile * 16 + q + 4 * p;        // block index along K
@@ -140,8 +156,13 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
                     Frag af[2];
-                    af[0].u = *reinterpret_cast<const u32x4*>(rec + (2 * p) * 1024 + lane * 16);
-                    af[1].u = *reinterpret_cast<const u32x4*>(rec + (2 * p + 1) * 1024 + lane * 16);
+                    if constexpr (CELLS) {
+                        af[0] = apre[g][p][0];
+                        af[1] = apre[g][p][1];
+                    } else {
+                        af[0].u = *reinterpret_cast<const u32x4*>(rec + (2 * p) * 1024 + lane * 16);
+                        af[1].u = *reinterpret_cast<const u32x4*>(rec + (2 * p + 1) * 1024 + lane * 16);
+                    }
                     acc[g] = mfma16(af[0].v, xf[p][0].v, acc[g]);
                     acc[g] = mfma16(af[1].v, xf[p][1].v, acc[g]);
                 }
