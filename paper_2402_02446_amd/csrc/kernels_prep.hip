@@ -30,6 +30,7 @@ struct PrepArgs {
     float* Tpart;
     int64_t tp_rows;       // rows per slice of Tpart
     int lr;                // CELLS: log2 of the token rows per 16-byte cell column
+    float* Yz; int64_t ldy, N;   // Yz != null: clear Y[M][N] for a main kernel that adds into it
 };
 
 __device__ __forceinline__ void split_bf16(float t, uint16_t& hi, uint16_t& lo) {
@@ -61,6 +62,21 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
     f32x4 acc[MAXG];
 #pragma unroll
     for (int g = 0; g < MAXG; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (a.Yz) {                                      // grid-stride clear, four columns at a time
+        const int64_t n4 = (a.N + 3) / 4;
+        const int64_t nthreads = (int64_t)gridDim.x * gridDim.y * blockDim.x;
+        const int64_t me = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
+        for (int64_t i = me; i < a.M * n4; i += nthreads) {
+            const int64_t r = i / n4, c = 4 * (i - r * n4);
+            float* dst = a.Yz + r * a.ldy + c;
+            if (c + 3 < a.N) {
+                *reinterpret_cast<f32x4*>(dst) = f32x4{0.f, 0.f, 0.f, 0.f};
+            } else {
+                for (int64_t j = c; j < a.N; ++j) a.Yz[r * a.ldy + j] = 0.f;
+            }
+        }
+    }
 
     const int64_t tile_begin = (int64_t)slice * a.tiles_per_slice;
     int64_t tile_end = tile_begin + a.tiles_per_slice;
@@ -232,7 +248,7 @@ int prep_slices(const Layer& L, int64_t M, int path) {
 }
 
 hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t* Xc, const uint8_t* Xe,
-                       int64_t M, const Workspace& ws, hipStream_t s) {
+                       int64_t M, const Workspace& ws, float* y_zero, int64_t ldy, hipStream_t s) {
     if (M == 0) return hipSuccess;
     PrepArgs a;
     a.X = X; a.ldx = ldx; a.Xc = Xc; a.Xe = Xe;
@@ -245,6 +261,7 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     a.Tpart = ws.Tpart;
     a.tp_rows = ws.tp_rows;
     a.lr = ws.lr;
+    a.Yz = y_zero; a.ldy = ldy; a.N = L.N;
     const bool cells = ws.cells;
     int nwaves = a.tiles_per_slice;
     if (nwaves > kPrepWaves) nwaves = kPrepWaves;

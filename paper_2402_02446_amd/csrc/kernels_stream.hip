@@ -42,9 +42,14 @@ struct StreamArgs {
 };
 
 // LR = log2 of the token rows per activation cell column (4, 16 or 32 rows).
-// ONE: the whole K range is a single step (KT <= NWK): one activation stage, no loop.
-template <int G, int NWC, int NWK, int DT, int LR, bool ONE>
+// ONE: the whole K range of the workgroup is a single step: one activation stage, no loop.
+// KSP: workgroups per column block.  KSP = 2 gives narrow layers twice the workgroups: the pair
+//      takes alternate steps of the K range and both add their sums into Y, which the projection
+//      kernel has zeroed, with hardware fp32 atomics.  0 + a + b does not depend on which of the two
+//      arrives first, so the result is the same bits on every run.
+template <int G, int NWC, int NWK, int DT, int LR, bool ONE, int KSP>
 __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
+    static_assert(KSP == 1 || KSP == 2, "one workgroup per column block, or a pair");
     static_assert(DT == 1 || DT == 2, "weights one or two steps ahead");
     static_assert(!ONE || DT == 1, "a single step prefetches nothing");
     constexpr int NW = NWC * NWK;
@@ -53,6 +58,9 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     constexpr int XT = NWK * R * 512;                // bytes of one stage: NWK tiles x R rows of bf16
     constexpr int NL = XT / 1024;                    // 1 KiB loads per stage
     constexpr int XL = (NL + NW - 1) / NW;           // ... per wavefront
+    // array length for the staging registers: an aggregate of exactly 32 dwords is turned into one
+    // 1024-bit register tuple by the compiler, which costs over a hundred registers here
+    constexpr int XLA = (XL == 8) ? 9 : XL;
     static_assert(XT % 1024 == 0, "a stage is a whole number of wavefront loads");
     constexpr int kTBytes = 32 * 128 * 2;            // T_hi | T_lo of up to 32 tokens x 64 ranks, bf16
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
@@ -66,7 +74,9 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     const int t = lane & 31, hh = lane >> 5;
 
     // column groups of this wavefront (clamped; stores are masked)
-    const int64_t g0 = ((int64_t)blockIdx.x * NWC + wc) * G;
+    const int64_t cb = blockIdx.x / KSP;             // column block
+    const int kh = blockIdx.x % KSP;                 // which of the KSP workgroups of the block
+    const int64_t g0 = (cb * NWC + wc) * G;
     const uint8_t* wrec[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -78,38 +88,42 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     int trow = t;
     if (trow >= a.M) trow = (int)a.M - 1;            // repeat a valid token; never stored
 
-    const int64_t NI = (a.KT + NWK - 1) / NWK;       // steps, the same for every wavefront
+    const int64_t NI = (a.KT + NWK * KSP - 1) / (NWK * KSP);       // steps, the same for every wavefront
+    // step it of this workgroup covers the tiles NWK (it KSP + kh) + 0 .. NWK - 1
+    auto tile_raw = [&](int64_t it) { return wk + NWK * (it * KSP + kh); };
     // Tiles past the last one are read again (clamped index) and their arithmetic is skipped.
     auto tile_at = [&](int64_t it) {
-        const int64_t tl = wk + NWK * it;
+        const int64_t tl = tile_raw(it);
         return tl < a.KT ? tl : a.KT - 1;
     };
-    // activation stage of step it: bytes [it XT, (it + 1) XT) of the cell array, clamped at its end
+    // activation stage of step it: XT bytes of the cell array from (it KSP + kh) XT on, clamped at its end
     const int64_t x_last = (a.KT * 32 * R * 16) - 1024;            // last whole 1 KiB of the array
-    int st_off[XL];
-#pragma unroll
-    for (int x = 0; x < XL; ++x) {
-        const int j = wave + NW * x;
-        st_off[x] = (j < NL) ? j * 1024 + lane * 16 : -1;
-    }
+    // load x of this wavefront is 1 KiB number j = wave + NW x of the stage (wave-uniform, so the
+    // address arithmetic stays in scalar registers); its lane writes 16 bytes at swz(1024 j + 16 lane)
+    auto swz = [](int off) { return off ^ (((off >> (6 + LR)) & 1) << 7); };
     // LDS placement of a cell: the two lane halves of an operand read are 4 cells apart, which is a
     // multiple of the 256-byte bank period; flipping address bit 7 for the upper half's cells moves
     // them to the other half of the banks.
-    auto swz = [](int off) { return off ^ (((off >> (6 + LR)) & 1) << 7); };
-    auto fetch_x = [&](u32x4 (&st)[XL], int64_t it) {
+    int st_dst[XL];
+#pragma unroll
+    for (int x = 0; x < XL; ++x) st_dst[x] = swz((wave + NW * x) * 1024 + lane * 16);
+    const uint8_t* xlane = a.Xcell + lane * 16;
+    auto fetch_x = [&](u32x4 (&st)[XLA], int64_t it) {
+        const int64_t base = (it * KSP + kh) * XT;
 #pragma unroll
         for (int x = 0; x < XL; ++x) {
-            if (st_off[x] >= 0) {
-                int64_t off = it * XT + (st_off[x] - lane * 16);
+            const int j = wave + NW * x;
+            if (j < NL) {
+                int64_t off = base + j * 1024;
                 if (off > x_last) off = x_last;
-                st[x] = *reinterpret_cast<const u32x4*>(a.Xcell + off + lane * 16);
+                st[x] = *reinterpret_cast<const u32x4*>(xlane + off);
             }
         }
     };
-    auto store_x = [&](const u32x4 (&st)[XL], int buf) {
+    auto store_x = [&](const u32x4 (&st)[XLA], int buf) {
 #pragma unroll
         for (int x = 0; x < XL; ++x)
-            if (st_off[x] >= 0) *reinterpret_cast<u32x4*>(xlds + buf * XT + swz(st_off[x])) = st[x];
+            if (wave + NW * x < NL) *reinterpret_cast<u32x4*>(xlds + buf * XT + st_dst[x]) = st[x];
     };
     // operand read: cell 32 wk + 8 c + 4 hh + s of the stage, token row trow
     const int rd_base = (((32 * wk + 4 * hh) << LR) + trow) << 4;
@@ -134,7 +148,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     // rank blocks jb = 4 ch + 2 hh + {0, 1} of chunk ch: jb < kp16 is T_hi for ranks 16 jb..,
     // otherwise T_lo for ranks 16 (jb - kp16)...  Job j = g * nchunks + ch of this wavefront's column
     // groups goes to K slice j % NWK (every slice holds a partial sum of every group).
-    const int nb2 = 2 * a.kp16;
+    const int nb2 = (kh == 0) ? 2 * a.kp16 : 0;      // the correction is added once: by workgroup 0 of a pair
     const int nchunks = (nb2 + 3) / 4;               // 0, 1 or 2
     constexpr int NJ = (2 * G + NWK - 1) / NWK;
     u32x4 tail_cw[NJ][2];
@@ -164,7 +178,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     constexpr int SMAX = 8;
     const int t_rows = a.M < 32 ? (int)a.M : 32;
     const int kp4 = a.kp >> 2;
-    const int t_items = t_rows * kp4;
+    const int t_items = (kh == 0) ? t_rows * kp4 : 0;
     // The loads are issued here; the sums are formed (finish_t) once the first weight loads are on
     // their way, so that those do not wait for this round trip.
     f32x4 tpart[TI][SMAX];
@@ -210,7 +224,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
         u32x4 wcd[DT][G][4];         // packed codes, chunk by chunk
         u32x2 wex[DT][G];            // exponent bytes
         {
-            u32x4 st[XL];
+            u32x4 st[XLA];
             fetch_x(st, 0);
 #pragma unroll
             for (int g = 0; g < G; ++g) wex[0][g] = load_we(g, tile_at(0));
@@ -228,14 +242,14 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
                         for (int g = 0; g < G; ++g) wcd[1][g][c] = load_wc(g, tile_at(1), c);
                 }
             }
-            finish_t();
             store_x(st, 0);
+            finish_t();
         }
         // PFX: the step fetches the activations of the next one; PFW: it refills its weight set
         auto step = [&](u32x4 (&wc_)[G][4], u32x2 (&we_)[G], int64_t it, auto pfx, auto pfw) {
             constexpr bool PFX = decltype(pfx)::value, PFW = decltype(pfw)::value;
             __syncthreads();         // stage it % 2 is complete; the other one is free again
-            u32x4 st[XL];
+            u32x4 st[XLA];
             u32x2 wen[G];
             const int64_t nt = tile_at(it + DT);
             if constexpr (PFX) fetch_x(st, it + 1);
@@ -244,7 +258,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
                 for (int g = 0; g < G; ++g) wen[g] = load_we(g, nt);
             }
             __builtin_amdgcn_sched_barrier(0);
-            const bool live = wk + NWK * it < a.KT;
+            const bool live = tile_raw(it) < a.KT;
             const uint8_t* xs = xlds + (ONE ? 0 : (int)(it & 1) * XT);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -357,11 +371,15 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
             const f32x4 o = *red_at(k, q, r4);
             v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
         }
-        const int64_t grp = (int64_t)blockIdx.x * NG + q;
+        const int64_t grp = cb * NG + q;
         if (grp < a.N32 && t < a.M) {
             const int64_t n = grp * 32 + 8 * r4 + 4 * hh;              // this lane's 4 consecutive columns
             float* dst = a.Y + (int64_t)t * a.ldy + n;
-            if (n + 3 < a.N) {
+            if constexpr (KSP == 2) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (n + j < a.N) unsafeAtomicAdd(dst + j, v[j]);
+            } else if (n + 3 < a.N) {
                 *reinterpret_cast<f32x4*>(dst) = v;
             } else {
 #pragma unroll
@@ -375,7 +393,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
 int stream_max_rows() { return 32; }
 int stream_cell_rows_log2(int64_t M) { return M <= 4 ? 2 : (M <= 16 ? 4 : 5); }
 
-template <int G, int NWC, int NWK, int DT, int LR, bool ONE>
+template <int G, int NWC, int NWK, int DT, int LR, bool ONE, int KSP>
 static hipError_t launch_stream_t(const StreamArgs& a, hipStream_t s) {
     constexpr int STAGING = (ONE ? 1 : 2) * NWK * (1 << LR) * 512;
     constexpr int REDUCE = NWK * NWC * G * 4096;
@@ -383,7 +401,7 @@ static hipError_t launch_stream_t(const StreamArgs& a, hipStream_t s) {
     if constexpr (LDS_BYTES > 160 * 1024) {
         return hipErrorInvalidValue;                 // this shape does not fit the 160 KB of LDS
     } else {
-        auto kern = stream_kernel<G, NWC, NWK, DT, LR, ONE>;
+        auto kern = stream_kernel<G, NWC, NWK, DT, LR, ONE, KSP>;
         static bool attr_set = false;
         if (!attr_set) {
             const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -391,29 +409,43 @@ static hipError_t launch_stream_t(const StreamArgs& a, hipStream_t s) {
             if (e != hipSuccess) return e;
             attr_set = true;
         }
-        dim3 grid((unsigned)((a.N32 + NWC * G - 1) / (NWC * G))), block(64 * NWC * NWK);
+        dim3 grid((unsigned)((a.N32 + NWC * G - 1) / (NWC * G) * KSP)), block(64 * NWC * NWK);
         hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, s, a);
         return hipGetLastError();
     }
 }
 
-template <int G, int NWC, int NWK, int DT>
+template <int G, int NWC, int NWK, int DT, int KSP = 1>
 static hipError_t launch_stream_rows(const StreamArgs& a, hipStream_t s) {
     if constexpr (DT == 1) {
-        if (a.KT <= NWK) {
+        if (a.KT <= NWK * KSP) {
             switch (stream_cell_rows_log2(a.M)) {
-                case 2: return launch_stream_t<G, NWC, NWK, 1, 2, true>(a, s);
-                case 4: return launch_stream_t<G, NWC, NWK, 1, 4, true>(a, s);
-                default: return launch_stream_t<G, NWC, NWK, 1, 5, true>(a, s);
+                case 2: return launch_stream_t<G, NWC, NWK, 1, 2, true, KSP>(a, s);
+                case 4: return launch_stream_t<G, NWC, NWK, 1, 4, true, KSP>(a, s);
+                default: return launch_stream_t<G, NWC, NWK, 1, 5, true, KSP>(a, s);
             }
         }
     }
     switch (stream_cell_rows_log2(a.M)) {
-        case 2: return launch_stream_t<G, NWC, NWK, DT, 2, false>(a, s);
-        case 4: return launch_stream_t<G, NWC, NWK, DT, 4, false>(a, s);
-        default: return launch_stream_t<G, NWC, NWK, DT, 5, false>(a, s);
+        case 2: return launch_stream_t<G, NWC, NWK, DT, 2, false, KSP>(a, s);
+        case 4: return launch_stream_t<G, NWC, NWK, DT, 4, false, KSP>(a, s);
+        default: return launch_stream_t<G, NWC, NWK, DT, 5, false, KSP>(a, s);
     }
 }
+
+// variant = 10000 KSP + 1000 G + 100 NWC + 10 (NWK % 16) + DT: KSP workgroups per column block, G
+// column groups per wavefront, NWC x NWK wavefronts per workgroup, weights DT steps ahead.
+int stream_variant(const Layer& L, int64_t M, int variant) {
+    if (variant != 0) return variant;
+    if ((L.N32 + 3) / 4 >= 200) return 12241;        // wide layers
+    if ((L.N32 + 1) / 2 >= 160) return (M <= 16) ? 12181 : 12141;
+    // narrow layers: one column group per workgroup, and a pair of workgroups per group when that
+    // still leaves half of the compute units idle and the K range is worth sharing (the atomic adds of
+    // a pair cost about as much as half of a 4096-long K range at 16 tokens)
+    if (L.N32 <= 160 && (L.KT >= 32 || (M <= 4 && L.KT >= 8))) return (M <= 16) ? 21181 : 21141;
+    return (M <= 16) ? 11181 : 11241;
+}
+bool stream_variant_adds_into_y(int variant) { return variant / 10000 == 2; }
 
 hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
                          int variant, hipStream_t s) {
@@ -422,15 +454,7 @@ hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* 
     a.Wt = L.Wt; a.Bt = L.Bt; a.Xcell = reinterpret_cast<const uint8_t*>(ws.Xh);
     a.Tpart = ws.Tpart; a.S = ws.S;
     a.Y = Y; a.ldy = ldy; a.M = M; a.N = L.N; a.KT = L.KT; a.N32 = L.N32; a.kp = L.kp; a.kp16 = L.kp16;
-    // variant = 10000 + 1000 G + 100 NWC + 10 (NWK % 16) + DT: G column groups per wavefront, NWC x NWK
-    // wavefronts per workgroup, weights DT steps ahead.  0 = automatic.
-    int v = variant;
-    if (v == 0) {
-        if ((L.N32 + 3) / 4 >= 200) v = 12241;       // wide layers
-        else if ((L.N32 + 1) / 2 >= 160) v = (M <= 16) ? 12181 : 12141;
-        else if (L.KT <= 16 && M <= 16) v = 11101;   // short and narrow: the whole K range in one step
-        else v = (M <= 16) ? 11181 : 11241;
-    }
+    const int v = stream_variant(L, M, variant);
     switch (v) {
         case 11441: return launch_stream_rows<1, 4, 4, 1>(a, s);
         case 11421: return launch_stream_rows<1, 4, 2, 1>(a, s);
@@ -442,6 +466,10 @@ hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* 
         case 11101: return launch_stream_rows<1, 1, 16, 1>(a, s);
         case 11281: return launch_stream_rows<1, 2, 8, 1>(a, s);
         case 11241: return launch_stream_rows<1, 2, 4, 1>(a, s);
+        case 21181: return launch_stream_rows<1, 1, 8, 1, 2>(a, s);
+        case 21141: return launch_stream_rows<1, 1, 4, 1, 2>(a, s);
+        case 22181: return launch_stream_rows<2, 1, 8, 1, 2>(a, s);
+        case 21101: return launch_stream_rows<1, 1, 16, 1, 2>(a, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -291,7 +291,8 @@ static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, co
     if (ws.bytes > ws_bytes) return LQER_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     if (stages & 1) {
-        if (launch_prep(L, X, ldx, Xc, Xe, M, ws, s) != hipSuccess) return LQER_ERR_HIP;
+        const bool zero_y = (path == 1) && stream_variant_adds_into_y(stream_variant(L, M, variant));
+        if (launch_prep(L, X, ldx, Xc, Xe, M, ws, zero_y ? Y : nullptr, ldy, s) != hipSuccess) return LQER_ERR_HIP;
     }
     if (stages & 2) {
         const hipError_t e = (path == 1) ? launch_stream(L, M, ws, Y, ldy, variant, s)

@@ -78,13 +78,16 @@ hipError_t launch_quantize_mx(const float* x, int64_t rows, int64_t cols, int64_
 
 // Quantize X (or take codes) -> Xh bf16, and T = X_q A_k.  S == 1 writes T_hi/T_lo into Xh,
 // S > 1 writes fp32 partial sums per K slice.
+// y_zero != null: also clears Y[M][N] (row stride ldy) for a main kernel that adds into it.
 hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t* Xc, const uint8_t* Xe,
-                       int64_t M, const Workspace& ws, hipStream_t s);
+                       int64_t M, const Workspace& ws, float* y_zero, int64_t ldy, hipStream_t s);
 
 // Streaming (small M) main kernel.  variant 0 = automatic.
 hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
                          int variant, hipStream_t s);
 int stream_max_rows();
+int stream_variant(const Layer& L, int64_t M, int variant);      // resolves 0 = automatic
+bool stream_variant_adds_into_y(int variant);                    // Y must be zero before the launch
 int stream_cell_rows_log2(int64_t M);
 // Tiled MFMA (large M) main kernel.
 hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,

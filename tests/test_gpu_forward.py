@@ -48,20 +48,22 @@ def test_streaming_kernel_row_counts(M):
     h.free()
 
 
-STREAM_VARIANTS = [11441, 11421, 12241, 12242, 12181, 12141, 11181, 11101, 11281, 11241]
+STREAM_VARIANTS = [11441, 11421, 12241, 12242, 12181, 12141, 11181, 11101, 11281, 11241,
+                   21181, 21141, 22181, 21101]
 
 
 @pytest.mark.parametrize("K,N,k", [(48, 40, 0), (272, 100, 8), (1024, 272, 64), (2304, 528, 33), (4096, 64, 16)])
 @pytest.mark.parametrize("M", [3, 5, 20])
 @pytest.mark.parametrize("variant", STREAM_VARIANTS)
 def test_streaming_kernel_shapes(K, N, k, M, variant):
-    # variant = 10000 + 1000 G + 100 NWC + 10 (NWK % 16) + DT; a shape whose activation stages do not
-    # fit the 160 KB of LDS must be refused, every other one must match the oracle
+    # variant = 10000 KSP + 1000 G + 100 NWC + 10 (NWK % 16) + DT; a shape whose activation stages do
+    # not fit the 160 KB of LDS must be refused, every other one must match the oracle
     from paper_2402_02446_amd import binding
     nwk = (variant // 10) % 10 or 16
     rows = 4 if M <= 4 else (16 if M <= 16 else 32)
     kt = (K + 255) // 256
-    stages = 1 if (variant % 10 == 1 and kt <= nwk) else 2
+    ksp = variant // 10000
+    stages = 1 if (variant % 10 == 1 and kt <= nwk * ksp) else 2
     g, nwc = (variant // 1000) % 10, (variant // 100) % 10
     lds = 8192 + max(stages * nwk * rows * 512, nwk * nwc * g * 4096)
     layer, ch = oracle_layer_small(K, N, k, seed=K + k)
@@ -220,6 +222,23 @@ def test_cfg4_70b_shape_sampled():
         assert np.all(np.isfinite(Y))
         rows = np.arange(M) if M <= 16 else np.unique(np.r_[0, 127, 128, 2047, 2048, M - 1, rng.integers(0, M, 10)])
         _assert_close(Y[np.ix_(rows, cols)], oracle_forward_cols(X[rows], layer, cols))
+    h.free()
+
+
+def test_paired_workgroups_give_the_same_bits_every_run():
+    # Narrow layers run two workgroups per column block that both add into Y with fp32 atomics; with
+    # exactly two addends on top of zero the sum does not depend on the order of arrival.
+    import torch
+    from paper_2402_02446_amd import binding
+    layer, ch = oracle_layer_big(4096, 4096, 32, seed=3)
+    h = upload(layer)
+    for M in (1, 16, 32):
+        X = torch.from_numpy(synth.gen_activations(np.random.default_rng(M), M, 4096, ch, 50.0)).cuda()
+        first = binding.lqer_linear_forward(h, X).clone()
+        for _ in range(20):
+            Y = torch.full_like(first, 3.0)               # stale contents must not leak into the sum
+            binding.lqer_linear_forward(h, X, Y=Y)
+            assert torch.equal(Y, first)
     h.free()
 
 
