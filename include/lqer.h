@@ -119,7 +119,9 @@ int lqer_layer_free(lqer_layer* layer);
  *                  bytes, 256-byte aligned, caller-owned; its contents are scratch.
  * Steps, all in this library's kernels: quantize X to MXINT8 (Sec. 4.1), T = X_q A_k,
  * Y = X_q W_q + T B_k accumulated in fp32 in one pass over Y.  M == 0 is a no-op.
- * Calls on different streams need distinct workspaces.  The library allocates nothing here.
+ * Calls on different streams need distinct workspaces.  The library allocates nothing here,
+ * uses only the given stream and no host synchronisation, so the call can be captured in a HIP
+ * graph.  Results are the same bits on every run.
  * lqer_linear_forward_q takes activations that are already quantized
  * (Xc int8 [M][K], Xe uint8 [M][K/16], canonical, device).
  */
@@ -138,7 +140,9 @@ int lqer_linear_forward_q(const lqer_layer* layer, const int8_t* Xc_dev, const u
  *   variant 0 = automatic, otherwise a tile-shape index of the chosen path
  *   stages  bit 0 = quantize + T, bit 1 = main product; 0 = both
  * Same contract as lqer_linear_forward otherwise.  Running stage bit 1 alone reuses
- * what an earlier call with bit 0 left in the same workspace.
+ * what an earlier call with bit 0 left in the same workspace - with the same M, path and
+ * variant - and, on narrow layers where the streaming kernel runs pairs of workgroups that
+ * add into Y, needs the Y that call cleared: run alone a second time it adds onto the result.
  */
 typedef struct {
     int path;
