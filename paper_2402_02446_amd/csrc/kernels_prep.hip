@@ -30,7 +30,8 @@ struct PrepArgs {
     float* Tpart;
     int64_t tp_rows;       // rows per slice of Tpart
     int lr;                // CELLS: log2 of the token rows per 16-byte cell column
-    float* Yz; int64_t ldy, N;   // Yz != null: clear Y[M][N] for a main kernel that adds into it
+    float* Yz; int64_t ldy, N;   // Yz != null: extra workgroups clear Y[M][N] for a main kernel that adds into it
+    int nslices;                 // K slices = the part of grid.y that does the projection
 };
 
 __device__ __forceinline__ void split_bf16(float t, uint16_t& hi, uint16_t& lo) {
@@ -63,10 +64,12 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
 #pragma unroll
     for (int g = 0; g < MAXG; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    if (a.Yz) {                                      // grid-stride clear, four columns at a time
+    // Workgroups behind the a.nslices K slices (grid.y) only clear Y for a main kernel that adds into it,
+    // so the clearing runs beside the projection instead of in front of it.
+    if ((int)blockIdx.y >= a.nslices) {
         const int64_t n4 = (a.N + 3) / 4;
-        const int64_t nthreads = (int64_t)gridDim.x * gridDim.y * blockDim.x;
-        const int64_t me = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
+        const int64_t nthreads = (int64_t)gridDim.x * (gridDim.y - a.nslices) * blockDim.x;
+        const int64_t me = ((int64_t)(blockIdx.y - a.nslices) * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
         for (int64_t i = me; i < a.M * n4; i += nthreads) {
             const int64_t r = i / n4, c = 4 * (i - r * n4);
             float* dst = a.Yz + r * a.ldy + c;
@@ -76,6 +79,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
                 for (int64_t j = c; j < a.N; ++j) a.Yz[r * a.ldy + j] = 0.f;
             }
         }
+        return;
     }
 
     const int64_t tile_begin = (int64_t)slice * a.tiles_per_slice;
@@ -262,12 +266,16 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     a.tp_rows = ws.tp_rows;
     a.lr = ws.lr;
     a.Yz = y_zero; a.ldy = ldy; a.N = L.N;
+    a.nslices = ws.S;
     const bool cells = ws.cells;
     int nwaves = a.tiles_per_slice;
     if (nwaves > kPrepWaves) nwaves = kPrepWaves;
     if (nwaves < 1) nwaves = 1;
-    dim3 grid((unsigned)((M + 15) / 16), (unsigned)ws.S, 1);
     dim3 block(64 * nwaves);
+    // clearing workgroups: about four 16-byte stores per thread
+    const int64_t rg = (M + 15) / 16;
+    const int64_t zero_wgs = y_zero ? (M * ((L.N + 3) / 4) + 4 * block.x * rg - 1) / (4 * block.x * rg) : 0;
+    dim3 grid((unsigned)rg, (unsigned)(ws.S + zero_wgs), 1);
     const bool from_codes = (Xc != nullptr);
     const bool fin = (ws.Tpart == nullptr);          // T final (hi/lo behind the row) or partial sums
     if (cells && fin && L.kp > 0) return hipErrorInvalidValue;

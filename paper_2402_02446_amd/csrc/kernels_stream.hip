@@ -363,6 +363,11 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
         for (int r4 = 0; r4 < 4; ++r4)
             *red_at(wk, wc * G + g, r4) = f32x4{acc[g][4 * r4], acc[g][4 * r4 + 1], acc[g][4 * r4 + 2], acc[g][4 * r4 + 3]};
     __syncthreads();
+    // A pair of workgroups adds into Y with atomics.  They are issued so that one instruction covers two
+    // rows of 32 consecutive columns (two cache lines) instead of 64 scattered dwords: the finished
+    // sums go through LDS once more (the region of T, free by now) to change the lane order.
+    float* yt = reinterpret_cast<float*>(lds);                         // [NG][32 rows][32 columns]
+    static_assert(KSP == 1 || NG * 4096 <= kTBytes, "the transposed tile must fit the region of T");
     for (int u = wave; u < NG * 4; u += NW) {
         const int q = u >> 2, r4 = u & 3;
         f32x4 v = *red_at(0, q, r4);
@@ -371,21 +376,32 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
             const f32x4 o = *red_at(k, q, r4);
             v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
         }
-        const int64_t grp = cb * NG + q;
-        if (grp < a.N32 && t < a.M) {
-            const int64_t n = grp * 32 + 8 * r4 + 4 * hh;              // this lane's 4 consecutive columns
-            float* dst = a.Y + (int64_t)t * a.ldy + n;
-            if constexpr (KSP == 2) {
+        if constexpr (KSP == 2) {
+            *reinterpret_cast<f32x4*>(yt + (q * 32 + t) * 32 + 8 * r4 + 4 * hh) = v;
+        } else {
+            const int64_t grp = cb * NG + q;
+            if (grp < a.N32 && t < a.M) {
+                const int64_t n = grp * 32 + 8 * r4 + 4 * hh;              // this lane's 4 consecutive columns
+                float* dst = a.Y + (int64_t)t * a.ldy + n;
+                if (n + 3 < a.N) {
+                    *reinterpret_cast<f32x4*>(dst) = v;
+                } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (n + j < a.N) unsafeAtomicAdd(dst + j, v[j]);
-            } else if (n + 3 < a.N) {
-                *reinterpret_cast<f32x4*>(dst) = v;
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (n + j < a.N) dst[j] = v[j];
+                    for (int j = 0; j < 4; ++j)
+                        if (n + j < a.N) dst[j] = v[j];
+                }
             }
+        }
+    }
+    if constexpr (KSP == 2) {
+        __syncthreads();
+        const int pairs = ((int)a.M + 1) >> 1;                         // row pairs per column group
+        for (int item = wave; item < NG * pairs; item += NW) {
+            const int q = item / pairs, row = 2 * (item - q * pairs) + hh;
+            const int64_t grp = cb * NG + q;
+            const int64_t n = grp * 32 + t;
+            if (grp < a.N32 && row < a.M && n < a.N)
+                unsafeAtomicAdd(a.Y + (int64_t)row * a.ldy + n, yt[(q * 32 + row) * 32 + t]);
         }
     }
 }
@@ -440,9 +456,8 @@ int stream_variant(const Layer& L, int64_t M, int variant) {
     if ((L.N32 + 3) / 4 >= 200) return 12241;        // wide layers
     if ((L.N32 + 1) / 2 >= 160) return (M <= 16) ? 12181 : 12141;
     // narrow layers: one column group per workgroup, and a pair of workgroups per group when that
-    // still leaves half of the compute units idle and the K range is worth sharing (the atomic adds of
-    // a pair cost about as much as half of a 4096-long K range at 16 tokens)
-    if (L.N32 <= 160 && (L.KT >= 32 || (M <= 4 && L.KT >= 8))) return (M <= 16) ? 21181 : 21141;
+    // still leaves half of the compute units idle and the K range is worth sharing
+    if (L.N32 <= 160 && L.KT >= 8) return (M <= 16) ? 21181 : 21141;
     return (M <= 16) ? 11181 : 11241;
 }
 bool stream_variant_adds_into_y(int variant) { return variant / 10000 == 2; }
