@@ -32,6 +32,8 @@
 
 namespace lqer {
 
+constexpr int kStreamTBytes = 9 * 1024;          // 32 rows x (128 + 8) bf16, rounded up to keep what follows 1 KiB aligned
+
 struct StreamArgs {
     const uint8_t* Wt; const uint8_t* Bt;
     const uint8_t* Xcell;          // bf16 activations as 16-byte cells [KT*32][R rows]
@@ -62,11 +64,14 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     // 1024-bit register tuple by the compiler, which costs over a hundred registers here
     constexpr int XLA = (XL == 8) ? 9 : XL;
     static_assert(XT % 1024 == 0, "a stage is a whole number of wavefront loads");
-    constexpr int kTBytes = 32 * 128 * 2;            // T_hi | T_lo of up to 32 tokens x 64 ranks, bf16
+    // T_hi | T_lo of up to 32 tokens x 64 ranks, bf16; a row is padded by 16 bytes so that the token rows
+    // of one operand read fall into different banks
+    constexpr int kTBytes = kStreamTBytes;
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
-    uint16_t* tlds = reinterpret_cast<uint16_t*>(lds);                 // [32][2 kp] bf16, kept all along
+    uint16_t* tlds = reinterpret_cast<uint16_t*>(lds);                 // [32][2 kp + 8] bf16, kept all along
+    const int t_ld = 2 * a.kp + 8;                                     // row stride of tlds in elements
     uint8_t* xlds = lds + kTBytes;                                     // two activation stages
-    float* red = reinterpret_cast<float*>(lds + kTBytes);              // reused afterwards: [NWK][NG][64][16]
+    float* red = reinterpret_cast<float*>(lds + kTBytes);              // reused afterwards: [NWK][NG][4][64 lanes][4]
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -211,7 +216,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
                 hi[e] = hb >> 16;
                 lo[e] = f32_bits(sum[e] - f32_from_bits(hb)) >> 16;
             }
-            uint16_t* dst = tlds + row * 2 * a.kp + 4 * r4;
+            uint16_t* dst = tlds + row * t_ld + 4 * r4;
             *reinterpret_cast<u32x2*>(dst) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
             *reinterpret_cast<u32x2*>(dst + a.kp) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
         }
@@ -333,7 +338,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
             ta[0].u = u32x4{0, 0, 0, 0};
             ta[1].u = u32x4{0, 0, 0, 0};
             if (jb < nb2) {
-                const uint16_t* src = tlds + trow * 2 * a.kp + 16 * jb;
+                const uint16_t* src = tlds + trow * t_ld + 16 * jb;
                 ta[0].u = *reinterpret_cast<const u32x4*>(src);
                 ta[1].u = *reinterpret_cast<const u32x4*>(src + 8);
             }
@@ -354,8 +359,8 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     // every wavefront leaves its partial sums in LDS; wavefront v then finishes unit v, v + NW, ... where
     // unit u = (column group u / 4 of the workgroup, accumulator quarter u % 4)
     __syncthreads();                                 // every wavefront is done with the activation stages
-    auto red_at = [&](int k, int q, int r4) {
-        return reinterpret_cast<f32x4*>(red + ((((size_t)k * NG + q) * 64 + lane) * 16 + 4 * r4));
+    auto red_at = [&](int k, int q, int r4) {          // lanes side by side: no bank conflicts
+        return reinterpret_cast<f32x4*>(red + (((((size_t)k * NG + q) * 4 + r4) * 64 + lane) * 4));
     };
 #pragma unroll
     for (int g = 0; g < G; ++g)
@@ -413,7 +418,7 @@ template <int G, int NWC, int NWK, int DT, int LR, bool ONE, int KSP>
 static hipError_t launch_stream_t(const StreamArgs& a, hipStream_t s) {
     constexpr int STAGING = (ONE ? 1 : 2) * NWK * (1 << LR) * 512;
     constexpr int REDUCE = NWK * NWC * G * 4096;
-    constexpr int LDS_BYTES = 32 * 128 * 2 + (STAGING > REDUCE ? STAGING : REDUCE);
+    constexpr int LDS_BYTES = kStreamTBytes + (STAGING > REDUCE ? STAGING : REDUCE);
     if constexpr (LDS_BYTES > 160 * 1024) {
         return hipErrorInvalidValue;                 // this shape does not fit the 160 KB of LDS
     } else {

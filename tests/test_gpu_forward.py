@@ -65,7 +65,7 @@ def test_streaming_kernel_shapes(K, N, k, M, variant):
     ksp = variant // 10000
     stages = 1 if (variant % 10 == 1 and kt <= nwk * ksp) else 2
     g, nwc = (variant // 1000) % 10, (variant // 100) % 10
-    lds = 8192 + max(stages * nwk * rows * 512, nwk * nwc * g * 4096)
+    lds = 9216 + max(stages * nwk * rows * 512, nwk * nwc * g * 4096)
     layer, ch = oracle_layer_small(K, N, k, seed=K + k)
     h = upload(layer)
     X = synth.gen_activations(np.random.default_rng(1), M, K, ch, 30.0)
