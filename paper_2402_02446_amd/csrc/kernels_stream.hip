@@ -370,9 +370,8 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     __syncthreads();
     // A pair of workgroups adds into Y with atomics.  They are issued so that one instruction covers two
     // rows of 32 consecutive columns (two cache lines) instead of 64 scattered dwords: the finished
-    // sums go through LDS once more (the region of T, free by now) to change the lane order.
-    float* yt = reinterpret_cast<float*>(lds);                         // [NG][32 rows][32 columns]
-    static_assert(KSP == 1 || NG * 4096 <= kTBytes, "the transposed tile must fit the region of T");
+    // sums go through LDS once more to change the lane order.
+    float* yt = red + NWK * NG * 1024;                                 // [NG][32 rows][32 columns], behind the partial sums
     for (int u = wave; u < NG * 4; u += NW) {
         const int q = u >> 2, r4 = u & 3;
         f32x4 v = *red_at(0, q, r4);
@@ -417,7 +416,7 @@ int stream_cell_rows_log2(int64_t M) { return M <= 4 ? 2 : (M <= 16 ? 4 : 5); }
 template <int G, int NWC, int NWK, int DT, int LR, bool ONE, int KSP>
 static hipError_t launch_stream_t(const StreamArgs& a, hipStream_t s) {
     constexpr int STAGING = (ONE ? 1 : 2) * NWK * (1 << LR) * 512;
-    constexpr int REDUCE = NWK * NWC * G * 4096;
+    constexpr int REDUCE = NWK * NWC * G * 4096 + (KSP == 2 ? NWC * G * 4096 : 0);
     constexpr int LDS_BYTES = kStreamTBytes + (STAGING > REDUCE ? STAGING : REDUCE);
     if constexpr (LDS_BYTES > 160 * 1024) {
         return hipErrorInvalidValue;                 // this shape does not fit the 160 KB of LDS
@@ -489,6 +488,8 @@ hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* 
         case 21181: return launch_stream_rows<1, 1, 8, 1, 2>(a, s);
         case 21141: return launch_stream_rows<1, 1, 4, 1, 2>(a, s);
         case 22181: return launch_stream_rows<2, 1, 8, 1, 2>(a, s);
+        case 22421: return launch_stream_rows<2, 4, 2, 1, 2>(a, s);
+        case 21441: return launch_stream_rows<1, 4, 4, 1, 2>(a, s);
         case 21101: return launch_stream_rows<1, 1, 16, 1, 2>(a, s);
         default: return hipErrorInvalidValue;
     }

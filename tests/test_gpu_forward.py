@@ -49,7 +49,7 @@ def test_streaming_kernel_row_counts(M):
 
 
 STREAM_VARIANTS = [11441, 11421, 12241, 12242, 12181, 12141, 11181, 11101, 11281, 11241,
-                   21181, 21141, 22181, 21101]
+                   21181, 21141, 22181, 21101, 22421, 21441]
 
 
 @pytest.mark.parametrize("K,N,k", [(48, 40, 0), (272, 100, 8), (1024, 272, 64), (2304, 528, 33), (4096, 64, 16)])
@@ -65,7 +65,7 @@ def test_streaming_kernel_shapes(K, N, k, M, variant):
     ksp = variant // 10000
     stages = 1 if (variant % 10 == 1 and kt <= nwk * ksp) else 2
     g, nwc = (variant // 1000) % 10, (variant // 100) % 10
-    lds = 9216 + max(stages * nwk * rows * 512, nwk * nwc * g * 4096)
+    lds = 9216 + max(stages * nwk * rows * 512, nwk * nwc * g * 4096 + (nwc * g * 4096 if ksp == 2 else 0))
     layer, ch = oracle_layer_small(K, N, k, seed=K + k)
     h = upload(layer)
     X = synth.gen_activations(np.random.default_rng(1), M, K, ch, 30.0)
