@@ -239,6 +239,35 @@ def run_cfg5(steps, rng):
     return out
 
 
+def run_crossover(rng, steps=10):
+    """cfg4: the 70B-shaped MLP layer swept over M = 1 .. 4096 to locate where the forward pass stops
+    being bound by the weight stream (Sec. 2.1: memory-bound few-token regime against compute-bound
+    prefill).  One layer (132 MB of weights, so successive steps may find part of it in the 256 MB
+    last-level cache: this sweep compares M against M, it is not a bandwidth claim)."""
+    import torch
+    from paper_2402_02446_amd import binding, synth
+    K, N, k = 8192, 28672, 64
+    d = synth.random_packed_layer(rng, K, N, k)
+    layer = binding.lqer_layer_import(K, N, k, d["Wc"], d["We"], d["Ac"], d["Ae"], d["Bc"], d["Be"])
+    out = []
+    for M in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096):
+        X = torch.randn((M, K), device="cuda", dtype=torch.float32)
+        Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        f = lambda i: binding.lqer_linear_forward(layer, X, Y=Y)
+        f(0)
+        torch.cuda.synchronize()
+        ms = _graph_ms(f, steps)
+        out.append({"M": M, "path": "streaming" if binding.lqer_linear_path(layer, M) == 1 else "tiled",
+                    "ms_per_step": ms, "tflops": flops_forward(M, K, N, layer.kp) / (ms * 1e-3) / 1e12,
+                    "gbs": bytes_forward(M, K, N, layer.kp) / (ms * 1e-3) / 1e9})
+        del X, Y
+    layer.free()
+    # the ridge: smallest M whose step takes 1.5 x the M = 1 step or more
+    base = out[0]["ms_per_step"]
+    ridge = next((r["M"] for r in out if r["ms_per_step"] >= 1.5 * base), None)
+    return {"workload": "cfg4: 8192 x 28672, k = 64, whole step", "sweep": out, "first_M_at_1p5x_of_M1": ridge}
+
+
 def time_build_factors(rng):
     """Wall time of the offline step (lqer_build_factors, host fp64 + upload) per layer shape of cfg5."""
     from paper_2402_02446_amd import binding, synth
@@ -375,6 +404,7 @@ def main():
             cases.extend(res)
         cases.append(run_quantizer_case(32 * 2048, 4096, ksteps, rng))
     if args.cases == "full":
+        extra["crossover"] = run_crossover(rng)
         extra["cfg5"] = run_cfg5(3, rng)
         extra["build_factors_seconds_per_layer"] = time_build_factors(rng)
     kp = 32

@@ -360,8 +360,7 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
         // rate `single` (TFLOP/s of the whole chip, measured on an 8192 x 28672 layer at M = 4096).
         struct Shape { int id, bm, bn, share; double pair, single; };
         static const Shape shapes[] = {
-            {1, 256, 256, 1, 0.0, 1213.0}, {3, 128, 256, 1, 0.0, 1084.0}, {7, 128, 512, 1, 0.0, 1296.0},
-            {4, 128, 128, 2, 1058.0, 900.0}, {8, 128, 256, 2, 1261.0, 1084.0},
+            {11, 128, 512, 1, 0.0, 1372.0}, {12, 128, 256, 2, 1309.0, 1136.0}, {4, 128, 128, 2, 1058.0, 900.0},
         };
         double best = 0.0;
         for (const Shape& sh : shapes) {
@@ -375,13 +374,13 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
     }
     switch (variant) {
         case 1: return launch_tiled_t<4, 4, 2, 2, 4>(a, M, s);      // 256 x 256
-        case 2: return launch_tiled_t<4, 2, 2, 2, 4>(a, M, s);      // 256 x 128
         case 3: return launch_tiled_t<2, 4, 2, 2, 4>(a, M, s);      // 128 x 256
         case 4: return launch_tiled_t<2, 2, 2, 2, 4>(a, M, s);      // 128 x 128
-        case 5: return launch_tiled_t<2, 4, 4, 2, 4>(a, M, s);      // 256 x 256, eight wavefronts
-        case 6: return launch_tiled_t<2, 2, 4, 2, 4>(a, M, s);      // 256 x 128, eight wavefronts
         case 7: return launch_tiled_t<2, 4, 2, 4, 4>(a, M, s);      // 128 x 512, eight wavefronts
         case 8: return launch_tiled_t<2, 4, 2, 2, 4, 2>(a, M, s);   // 128 x 256, two workgroups per compute unit
+        case 11: return launch_tiled_t<4, 2, 1, 8, 4>(a, M, s);     // 128 x 512, eight wavefronts, each 128 x 64
+        case 12: return launch_tiled_t<4, 2, 1, 4, 4, 2>(a, M, s);  // 128 x 256, four wavefronts each 128 x 64, two workgroups per compute unit
+        case 13: return launch_tiled_t<4, 2, 1, 4, 4>(a, M, s);     // 128 x 256, four wavefronts each 128 x 64
         default: return hipErrorInvalidValue;
     }
 }

@@ -245,8 +245,8 @@ static Workspace plan_workspace(const Layer& L, int64_t M, int path, void* base)
     ws.S = prep_slices(L, M, path);
     ws.cells = (path == 1);
     ws.lr = stream_cell_rows_log2(M);
-    // the tiled kernel reads whole 256-row tiles of Xh (rows past M hold whatever was there)
-    const int64_t xh_rows = (path == 2) ? round_up(M, 256) : (ws.cells ? (int64_t)1 << ws.lr : M);
+    // the tiled kernel reads whole tiles of Xh, 96 to 256 rows high (rows past M hold whatever was there)
+    const int64_t xh_rows = (path == 2) ? round_up(M + 95, 256) : (ws.cells ? (int64_t)1 << ws.lr : M);
     const size_t xh_bytes = (size_t)round_up(xh_rows * ws.ldxh * 2, 256);
     // T travels as partial sums on the streaming path and whenever the projection kernel splits K
     const bool partial = L.kp > 0 && (path == 1 || ws.S > 1);

@@ -77,7 +77,7 @@ def test_streaming_kernel_shapes(K, N, k, M, variant):
     h.free()
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("variant", [1, 3, 4, 7, 8, 11, 12, 13])
 @pytest.mark.parametrize("M,K,N,k", [(16, 512, 512, 8), (300, 272, 200, 0), (513, 1024, 528, 64), (100, 2304, 40, 33)])
 def test_tiled_kernel_shapes(variant, M, K, N, k):
     layer, ch = oracle_layer_small(K, N, k, seed=M + variant)
