@@ -323,26 +323,33 @@ def cpu_baseline(ctx, M, K, N, kp, budget_s=12.0):
 PMC_COPY_BYTES = 1 << 30
 
 
-def pmc_probe(rng):
-    """Workload for the two `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE): a plain copy of
-    known size (the calibration of the counter) followed by the headline ring."""
+def pmc_probe(rng, which):
+    """Workload for `rocprofv3 --pmc` runs.  `headline`: a plain copy of known size (the calibration of
+    FETCH_SIZE / WRITE_SIZE) followed by the headline ring; `cfg4_decode` / `cfg4_prefill`: the
+    70B-shaped layer at M = 16 / M = 4096 (ring of layers for the decode case), for the counters
+    that show what the streaming and the tiled kernel wait for."""
     import torch
     from paper_2402_02446_amd import binding, synth
-    src = torch.ones(PMC_COPY_BYTES // 4, dtype=torch.float32, device="cuda")
-    dst = torch.empty_like(src)
-    for _ in range(3):
-        torch.add(src, 1.0, out=dst)          # one elementwise kernel: reads and writes PMC_COPY_BYTES
-    torch.cuda.synchronize()
-    M, K, N, k = 16, 4096, 4096, 32
-    layers, _ = make_ring(rng, K, N, k, 1.25 * LLC_BYTES)
+    if which == "headline":
+        src = torch.ones(PMC_COPY_BYTES // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)          # one elementwise kernel: reads and writes PMC_COPY_BYTES
+        torch.cuda.synchronize()
+        M, K, N, k, ring, reps = 16, 4096, 4096, 32, 1.25 * LLC_BYTES, 3
+    elif which == "cfg4_decode":
+        M, K, N, k, ring, reps = 16, 8192, 28672, 64, 2.1 * LLC_BYTES, 5
+    else:
+        M, K, N, k, ring, reps = 4096, 8192, 28672, 64, 0, 6
+    layers, _ = make_ring(rng, K, N, k, ring)
     ch = synth.gen_outlier_channels(rng, K, max(1, round(0.01 * K)))
     X = torch.from_numpy(synth.gen_activations(rng, M, K, ch, 50.0)).cuda()
     Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
-    for rep in range(3):
+    for rep in range(reps):
         for l in layers:
             binding.lqer_linear_forward(l, X, Y=Y)
     torch.cuda.synchronize()
-    print("pmc-probe done: copy of %d bytes x3, %d-layer ring x3" % (PMC_COPY_BYTES, len(layers)))
+    print("pmc-probe %s done: %d-layer ring x%d at M=%d" % (which, len(layers), reps, M))
 
 
 def read_pmc_traffic(kernel):
@@ -366,8 +373,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--cases", default="all", choices=["headline", "all", "full"],
                     help="headline: cfg2 only; all: + cfg3, cfg4 and the quantizer; full: + cfg5 and build_factors timing")
-    ap.add_argument("--pmc-probe", action="store_true",
-                    help="run a plain 1 GiB copy and the headline ring a few times, for rocprofv3 --pmc runs")
+    ap.add_argument("--pmc-probe", nargs="?", const="headline", default=None,
+                    choices=["headline", "cfg4_decode", "cfg4_prefill"],
+                    help="run one workload a few times and exit, for rocprofv3 --pmc runs (headline: after a "
+                         "plain 1 GiB copy that calibrates the byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (the layer's sharding "
@@ -382,7 +391,7 @@ def main():
     rng = np.random.default_rng(0)
 
     if args.pmc_probe:
-        pmc_probe(rng)
+        pmc_probe(rng, args.pmc_probe)
         return
 
     M, K, N, k = 16, 4096, 4096, 32
