@@ -52,6 +52,9 @@ struct StreamArgs {
 template <int G, int NWC, int NWK, int DT, int LR, bool ONE, int KSP>
 __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     static_assert(KSP == 1 || KSP == 2, "one workgroup per column block, or a pair");
+    // 64 token rows are two blocks of 32: every expanded weight operand then feeds two MFMAs
+    constexpr int MB = (LR == 6) ? 2 : 1;
+    static_assert(MB == 1 || KSP == 1, "pairs of workgroups take at most 32 tokens");
     static_assert(DT == 1 || DT == 2, "weights one or two steps ahead");
     static_assert(!ONE || DT == 1, "a single step prefetches nothing");
     constexpr int NW = NWC * NWK;
@@ -66,7 +69,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     static_assert(XT % 1024 == 0, "a stage is a whole number of wavefront loads");
     // T_hi | T_lo of up to 32 tokens x 64 ranks, bf16; a row is padded by 16 bytes so that the token rows
     // of one operand read fall into different banks
-    constexpr int kTBytes = kStreamTBytes;
+    constexpr int kTBytes = kStreamTBytes * MB;
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     uint16_t* tlds = reinterpret_cast<uint16_t*>(lds);                 // [32][2 kp + 8] bf16, kept all along
     const int t_ld = 2 * a.kp + 8;                                     // row stride of tlds in elements
@@ -90,8 +93,12 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
         wrec[g] = a.Wt + grp * kWRecordBytes + lane * 16;
     }
     const int e_adj = -(lane * 8);                   // exponent words sit at lane * 8, not lane * 16
-    int trow = t;
-    if (trow >= a.M) trow = (int)a.M - 1;            // repeat a valid token; never stored
+    int trow[MB];
+#pragma unroll
+    for (int b = 0; b < MB; ++b) {
+        trow[b] = t + 32 * b;
+        if (trow[b] >= a.M) trow[b] = (int)a.M - 1;  // repeat a valid token; never stored
+    }
 
     const int64_t NI = (a.KT + NWK * KSP - 1) / (NWK * KSP);       // steps, the same for every wavefront
     // step it of this workgroup covers the tiles NWK (it KSP + kh) + 0 .. NWK - 1
@@ -131,7 +138,9 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
             if (wave + NW * x < NL) *reinterpret_cast<u32x4*>(xlds + buf * XT + st_dst[x]) = st[x];
     };
     // operand read: cell 32 wk + 8 c + 4 hh + s of the stage, token row trow
-    const int rd_base = (((32 * wk + 4 * hh) << LR) + trow) << 4;
+    int rd_base[MB];
+#pragma unroll
+    for (int b = 0; b < MB; ++b) rd_base[b] = (((32 * wk + 4 * hh) << LR) + trow[b]) << 4;
     const int rd_flip = hh << 7;                     // swz() of an operand address: its cell has bit 2 = hh
 
     const int64_t tile_stride = a.N32 * kWRecordBytes;             // records are ordered [K tile][column group]
@@ -142,11 +151,13 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
         return __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(wrec[g] + tile * tile_stride + kWExpOffset + e_adj));
     };
 
-    f32x16 acc[G];
+    f32x16 acc[G][MB];
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[g][r] = 0.f;
+        for (int b = 0; b < MB; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[g][b][r] = 0.f;
 
     // ---- rank-kp correction, part 1: fetch its operands first ---------------------------------------
     // The correction is 2 kp more "K columns" in 64-wide chunks of [T_hi | T_lo].  Lane half hh owns
@@ -179,9 +190,9 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     }
     // T: the workgroup adds the S (<= 8) partial sums of the projection kernel in slice order and
     // leaves T_hi | T_lo as bf16 in LDS.  One item = 4 consecutive ranks of a token.
-    constexpr int TI = (32 * 16 + NW * 64 - 1) / (NW * 64);
+    constexpr int TI = (32 * MB * 16 + NW * 64 - 1) / (NW * 64);
     constexpr int SMAX = 8;
-    const int t_rows = a.M < 32 ? (int)a.M : 32;
+    const int t_rows = a.M < 32 * MB ? (int)a.M : 32 * MB;
     const int kp4 = a.kp >> 2;
     const int t_items = (kh == 0) ? t_rows * kp4 : 0;
     // The loads are issued here; the sums are formed (finish_t) once the first weight loads are on
@@ -268,22 +279,24 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 if (live) {
-                    Frag xf[4];
+                    Frag xf[MB][4];
 #pragma unroll
-                    for (int s = 0; s < 4; ++s)
-                        {
-                        // for 16 rows and more the operand offsets are multiples of 256 B and leave bit 7 alone
-                        const int off = (8 * c + s) << (LR + 4);
-                        const int ad = (LR >= 4) ? ((rd_base ^ rd_flip) + off) : ((rd_base + off) ^ rd_flip);
-                        xf[s].u = *reinterpret_cast<const u32x4*>(xs + ad);
-                    }
+                    for (int b = 0; b < MB; ++b)
+#pragma unroll
+                        for (int s = 0; s < 4; ++s) {
+                            // for 16 rows and more the operand offsets are multiples of 256 B and leave bit 7 alone
+                            const int off = (8 * c + s) << (LR + 4);
+                            const int ad = (LR >= 4) ? ((rd_base[b] ^ rd_flip) + off) : ((rd_base[b] + off) ^ rd_flip);
+                            xf[b][s].u = *reinterpret_cast<const u32x4*>(xs + ad);
+                        }
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
 #pragma unroll
                         for (int s = 0; s < 4; ++s) {
                             const uint32_t ew = we_[g][c >> 1] >> (16 * (c & 1) + 8 * (s >> 1));
                             const bf16x8 wv = unpack_w8(wc_[g][c][s], w_scale(ew & 0xFFu));
-                            acc[g] = mfma32(wv, xf[s].v, acc[g]);
+#pragma unroll
+                            for (int b = 0; b < MB; ++b) acc[g][b] = mfma32(wv, xf[b][s].v, acc[g][b]);
                         }
                     }
                 }
@@ -334,13 +347,16 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int jb = 4 * ch + 2 * hh + j;
-            Frag ta[2];
-            ta[0].u = u32x4{0, 0, 0, 0};
-            ta[1].u = u32x4{0, 0, 0, 0};
-            if (jb < nb2) {
-                const uint16_t* src = tlds + trow * t_ld + 16 * jb;
-                ta[0].u = *reinterpret_cast<const u32x4*>(src);
-                ta[1].u = *reinterpret_cast<const u32x4*>(src + 8);
+            Frag ta[MB][2];
+#pragma unroll
+            for (int b = 0; b < MB; ++b) {
+                ta[b][0].u = u32x4{0, 0, 0, 0};
+                ta[b][1].u = u32x4{0, 0, 0, 0};
+                if (jb < nb2) {
+                    const uint16_t* src = tlds + trow[b] * t_ld + 16 * jb;
+                    ta[b][0].u = *reinterpret_cast<const u32x4*>(src);
+                    ta[b][1].u = *reinterpret_cast<const u32x4*>(src + 8);
+                }
             }
             Frag bf[2];
             int8x16_to_frags(tail_cw[q][j], h_scale(tail_eb[q][j]), bf[0], bf[1]);
@@ -348,8 +364,11 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
 #pragma unroll
             for (int gg = 0; gg < G; ++gg) {
                 if (gg == g) {
-                    acc[gg] = mfma32(bf[0].v, ta[0].v, acc[gg]);
-                    acc[gg] = mfma32(bf[1].v, ta[1].v, acc[gg]);
+#pragma unroll
+                    for (int b = 0; b < MB; ++b) {
+                        acc[gg][b] = mfma32(bf[0].v, ta[b][0].v, acc[gg][b]);
+                        acc[gg][b] = mfma32(bf[1].v, ta[b][1].v, acc[gg][b]);
+                    }
                 }
             }
         }
@@ -357,36 +376,41 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
 
     // ---- add the K slices of every column group in slice order -----------------------------------------
     // every wavefront leaves its partial sums in LDS; wavefront v then finishes unit v, v + NW, ... where
-    // unit u = (column group u / 4 of the workgroup, accumulator quarter u % 4)
+    // unit u = (column group, token block, accumulator quarter u % 4)
+    constexpr int NGV = NG * MB;                     // (column group, token block) pairs of the workgroup
     __syncthreads();                                 // every wavefront is done with the activation stages
     auto red_at = [&](int k, int q, int r4) {          // lanes side by side: no bank conflicts
-        return reinterpret_cast<f32x4*>(red + (((((size_t)k * NG + q) * 4 + r4) * 64 + lane) * 4));
+        return reinterpret_cast<f32x4*>(red + (((((size_t)k * NGV + q) * 4 + r4) * 64 + lane) * 4));
     };
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4)
-            *red_at(wk, wc * G + g, r4) = f32x4{acc[g][4 * r4], acc[g][4 * r4 + 1], acc[g][4 * r4 + 2], acc[g][4 * r4 + 3]};
+        for (int b = 0; b < MB; ++b)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4)
+                *red_at(wk, (wc * G + g) * MB + b, r4) =
+                    f32x4{acc[g][b][4 * r4], acc[g][b][4 * r4 + 1], acc[g][b][4 * r4 + 2], acc[g][b][4 * r4 + 3]};
     __syncthreads();
     // A pair of workgroups adds into Y with atomics.  They are issued so that one instruction covers two
     // rows of 32 consecutive columns (two cache lines) instead of 64 scattered dwords: the finished
     // sums go through LDS once more to change the lane order.
-    float* yt = red + NWK * NG * 1024;                                 // [NG][32 rows][32 columns], behind the partial sums
-    for (int u = wave; u < NG * 4; u += NW) {
-        const int q = u >> 2, r4 = u & 3;
-        f32x4 v = *red_at(0, q, r4);
+    float* yt = red + NWK * NGV * 1024;                                // [NG][32 rows][32 columns], behind the partial sums
+    for (int u = wave; u < NGV * 4; u += NW) {
+        const int qv = u >> 2, r4 = u & 3;
+        const int q = qv / MB, row = t + 32 * (qv % MB);
+        f32x4 v = *red_at(0, qv, r4);
 #pragma unroll
         for (int k = 1; k < NWK; ++k) {
-            const f32x4 o = *red_at(k, q, r4);
+            const f32x4 o = *red_at(k, qv, r4);
             v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
         }
         if constexpr (KSP == 2) {
             *reinterpret_cast<f32x4*>(yt + (q * 32 + t) * 32 + 8 * r4 + 4 * hh) = v;
         } else {
             const int64_t grp = cb * NG + q;
-            if (grp < a.N32 && t < a.M) {
+            if (grp < a.N32 && row < a.M) {
                 const int64_t n = grp * 32 + 8 * r4 + 4 * hh;              // this lane's 4 consecutive columns
-                float* dst = a.Y + (int64_t)t * a.ldy + n;
+                float* dst = a.Y + (int64_t)row * a.ldy + n;
                 if (n + 3 < a.N) {
                     *reinterpret_cast<f32x4*>(dst) = v;
                 } else {
@@ -410,15 +434,16 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     }
 }
 
-int stream_max_rows() { return 32; }
-int stream_cell_rows_log2(int64_t M) { return M <= 4 ? 2 : (M <= 16 ? 4 : 5); }
+int stream_max_rows() { return 64; }
+int stream_cell_rows_log2(int64_t M) { return M <= 4 ? 2 : (M <= 16 ? 4 : (M <= 32 ? 5 : 6)); }
 
 template <int G, int NWC, int NWK, int DT, int LR, bool ONE, int KSP>
 static hipError_t launch_stream_t(const StreamArgs& a, hipStream_t s) {
     constexpr int STAGING = (ONE ? 1 : 2) * NWK * (1 << LR) * 512;
-    constexpr int REDUCE = NWK * NWC * G * 4096 + (KSP == 2 ? NWC * G * 4096 : 0);
-    constexpr int LDS_BYTES = kStreamTBytes + (STAGING > REDUCE ? STAGING : REDUCE);
-    if constexpr (LDS_BYTES > 160 * 1024) {
+    constexpr int MB = (LR == 6) ? 2 : 1;
+    constexpr int REDUCE = NWK * NWC * G * MB * 4096 + (KSP == 2 ? NWC * G * 4096 : 0);
+    constexpr int LDS_BYTES = kStreamTBytes * MB + (STAGING > REDUCE ? STAGING : REDUCE);
+    if constexpr (LDS_BYTES > 160 * 1024 || (MB == 2 && KSP == 2)) {
         return hipErrorInvalidValue;                 // this shape does not fit the 160 KB of LDS
     } else {
         auto kern = stream_kernel<G, NWC, NWK, DT, LR, ONE, KSP>;
@@ -442,14 +467,16 @@ static hipError_t launch_stream_rows(const StreamArgs& a, hipStream_t s) {
             switch (stream_cell_rows_log2(a.M)) {
                 case 2: return launch_stream_t<G, NWC, NWK, 1, 2, true, KSP>(a, s);
                 case 4: return launch_stream_t<G, NWC, NWK, 1, 4, true, KSP>(a, s);
-                default: return launch_stream_t<G, NWC, NWK, 1, 5, true, KSP>(a, s);
+                case 5: return launch_stream_t<G, NWC, NWK, 1, 5, true, KSP>(a, s);
+                default: return launch_stream_t<G, NWC, NWK, 1, 6, true, KSP>(a, s);
             }
         }
     }
     switch (stream_cell_rows_log2(a.M)) {
         case 2: return launch_stream_t<G, NWC, NWK, DT, 2, false, KSP>(a, s);
         case 4: return launch_stream_t<G, NWC, NWK, DT, 4, false, KSP>(a, s);
-        default: return launch_stream_t<G, NWC, NWK, DT, 5, false, KSP>(a, s);
+        case 5: return launch_stream_t<G, NWC, NWK, DT, 5, false, KSP>(a, s);
+        default: return launch_stream_t<G, NWC, NWK, DT, 6, false, KSP>(a, s);
     }
 }
 
@@ -457,6 +484,7 @@ static hipError_t launch_stream_rows(const StreamArgs& a, hipStream_t s) {
 // column groups per wavefront, NWC x NWK wavefronts per workgroup, weights DT steps ahead.
 int stream_variant(const Layer& L, int64_t M, int variant) {
     if (variant != 0) return variant;
+    if (M > 32) return 11421;                        // 33 to 64 tokens: two blocks of 32 per wavefront, two K slices
     if ((L.N32 + 3) / 4 >= 200) return 12241;        // wide layers
     if ((L.N32 + 1) / 2 >= 160) return (M <= 16) ? 12181 : 12141;
     // narrow layers: one column group per workgroup, and a pair of workgroups per group when that

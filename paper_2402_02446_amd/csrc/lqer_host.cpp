@@ -259,8 +259,11 @@ static Workspace plan_workspace(const Layer& L, int64_t M, int path, void* base)
 }
 
 static int pick_path(const Layer& L, int64_t M) {
-    (void)L;
-    return (M <= stream_max_rows()) ? 1 : 2;
+    // The streaming kernel takes up to 32 tokens for any layer, and up to 64 (two blocks of 32 per
+    // wavefront) for layers wide enough to fill the chip with four column groups per workgroup.
+    if (M <= 32) return 1;
+    if (M <= stream_max_rows() && L.N32 >= 512) return 1;
+    return 2;
 }
 
 static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, const int8_t* Xc,

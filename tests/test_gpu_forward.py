@@ -53,19 +53,23 @@ STREAM_VARIANTS = [11441, 11421, 12241, 12242, 12181, 12141, 11181, 11101, 11281
 
 
 @pytest.mark.parametrize("K,N,k", [(48, 40, 0), (272, 100, 8), (1024, 272, 64), (2304, 528, 33), (4096, 64, 16)])
-@pytest.mark.parametrize("M", [3, 5, 20])
+@pytest.mark.parametrize("M", [3, 5, 20, 40, 64])
 @pytest.mark.parametrize("variant", STREAM_VARIANTS)
 def test_streaming_kernel_shapes(K, N, k, M, variant):
     # variant = 10000 KSP + 1000 G + 100 NWC + 10 (NWK % 16) + DT; a shape whose activation stages do
     # not fit the 160 KB of LDS must be refused, every other one must match the oracle
     from paper_2402_02446_amd import binding
     nwk = (variant // 10) % 10 or 16
-    rows = 4 if M <= 4 else (16 if M <= 16 else 32)
+    rows = 4 if M <= 4 else (16 if M <= 16 else (32 if M <= 32 else 64))
+    mb = rows // 32 or 1                                     # token blocks of 32 per wavefront
     kt = (K + 255) // 256
     ksp = variant // 10000
     stages = 1 if (variant % 10 == 1 and kt <= nwk * ksp) else 2
     g, nwc = (variant // 1000) % 10, (variant // 100) % 10
-    lds = 9216 + max(stages * nwk * rows * 512, nwk * nwc * g * 4096 + (nwc * g * 4096 if ksp == 2 else 0))
+    lds = 9216 * mb + max(stages * nwk * rows * 512,
+                          nwk * nwc * g * mb * 4096 + (nwc * g * 4096 if ksp == 2 else 0))
+    if mb == 2 and ksp == 2:
+        lds = 1 << 20                                        # pairs of workgroups take at most 32 tokens
     layer, ch = oracle_layer_small(K, N, k, seed=K + k)
     h = upload(layer)
     X = synth.gen_activations(np.random.default_rng(1), M, K, ch, 30.0)
