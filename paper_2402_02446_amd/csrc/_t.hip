@@ -1,0 +1,558 @@
+// Stage 2, large-M ("prefill") form of Y = X_q W_q + T B_k (Eq. 3 / Eq. 6): an MFMA-bound tiled
+// GEMM.  Sec. 2.1 observes that run-time dequantization is what costs weight-only schemes in the
+// compute-bound regime, so here the weight expansion is kept to seven VALU instructions per 8
+// elements (unpack_w8) and runs beside the matrix pipe.
+//
+// Workgroup tile BM x BN, WR x WC wavefronts, each owning TM x TN tiles of the 32x32x16 bf16
+// MFMA (the shape one wavefront per SIMD can keep close to the matrix pipe's peak).  The
+// contraction axis is walked in chunks of 64 = four MFMA steps; lane half hh owns blocks 2hh and
+// 2hh+1 of a chunk for every operand, so block scales never cross lanes.
+//   activations (bf16, exact dequantized X_q, then T_hi | T_lo): global -> registers two chunks
+//       ahead -> a ring of four LDS stages of XOR-swizzled 16-byte cells -> ds_read_b128 operands
+//       shared by the wavefronts of a row;
+//   weights: each wavefront loads the packed MXINT4 records of its own columns straight into
+//       registers (fully coalesced 16-byte loads), two chunks ahead, into four register sets used
+//       by name in turn (a copy between sets would force a wait on the newest load), and expands
+//       them there;
+//   the rank-kp correction is ceil(2 kp / 64) more chunks whose weight operand comes from B_k.
+// MFMA operands are swapped (weights first) so a lane ends up with runs of four consecutive
+// output columns of one token and stores each as one 16-byte write.
+//
+// Work split.  The launch is either one workgroup per output tile, or - when the tiles do not fill
+// whole rounds of the chip - as many workgroups as the chip holds at once, each taking its share of
+// whole tiles first and then an equal share of the K tiles of the remaining output tiles (those are
+// cut wherever a share ends).  A workgroup whose share starts inside an output tile leaves its
+// accumulators in a workspace slot of its own and raises a flag; the workgroup that has the start
+// of that output tile adds the later pieces in K order and stores.  A share is one contiguous range,
+// so only its first piece can be handed over and only its last piece can wait, and the waiting
+// piece needs pieces that are computed first by the workgroups they belong to: no wait depends on
+// another wait.  The sum order is fixed by the split, so the result has the same bits every run.
+#include "lqer_internal.h"
+#include "mx_device.h"
+
+namespace lqer {
+
+struct TiledArgs {
+    const uint8_t* Wt; const uint8_t* Bt;
+    const uint16_t* Xh; int64_t ldxh;
+    const float* Tpart; int S; int64_t tp_stride;    // S > 1: T as S fp32 partial sums [S][tp_stride / kp rows][kp]
+    float* Y; int64_t ldy;
+    int64_t M, N, KT, N32;
+    int kp, kp16;
+    int grid_m, grid_n;
+    int group_m;
+    // work split (see the head of this file)
+    int64_t dp_tiles;          // output tiles taken whole, tile i by workgroup i % gridDim.x
+    int64_t sk_units;          // K tiles of the remaining output tiles, shared out in ranges of ...
+    int64_t sk_share;          // ... this many per workgroup
+    float* Part;               // [gridDim.x][BM * BN] accumulators handed over
+    uint32_t* flags;           // [gridDim.x], zero before the launch; 1 = slot written
+    int spin_limit;            // polls of a flag before the waiting workgroup gives up (and stores NaN)
+};
+
+// MINW = wavefronts per SIMD the register allocation must allow (2 lets two four-wavefront workgroups share a compute unit)
+template <int TM, int TN, int WR, int WC, int NS, int MINW>
+__global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) {
+    constexpr int BM = 32 * TM * WR;
+    constexpr int NW = WR * WC;
+    constexpr int STAGE = BM * 128;                // bytes: BM rows x 64 bf16
+    constexpr int NT = 64 * NW;
+    constexpr int LPT = BM * 8 / NT;               // 16-byte cells each thread moves per chunk
+    static_assert((BM * 8) % NT == 0, "loader must divide evenly");
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction
+    const int wr = wave / WC, wc = wave % WC;
+    const int t = lane & 31, hh = lane >> 5;
+
+    // ---- workgroup -> position in the work split: consecutive positions land on one XCD ----------
+    int lin;
+    {
+        const int nwg = gridDim.x;
+        const int pid = blockIdx.x;
+        const int xcd = pid & 7, local = pid >> 3;
+        const int per = nwg >> 3, rem = nwg & 7;
+        lin = (xcd < rem) ? xcd * (per + 1) + local : rem * (per + 1) + (xcd - rem) * per + local;
+    }
+    __shared__ int wait_ok;
+    const int64_t main_chunks = a.KT * 4;
+    const int nb2 = 2 * a.kp16;
+    const int tail_chunks = (nb2 + 3) / 4;
+    static_assert(NS == 4, "stage and register-set indices below assume rings of four");
+    constexpr int ROWS_PER_PASS = NT / 8;
+    static_assert(ROWS_PER_PASS % 16 == 0, "swizzle must not depend on the pass");
+    const int ld_row0 = tid >> 3;
+    // (row >> 1) & 7 is the same for every pass because ROWS_PER_PASS is a multiple of 16
+    const int ld_dst0 = ld_row0 * 128 + (((tid & 7) ^ ((ld_row0 >> 1) & 7)) << 4);
+    // ---- operand reader: in step s this lane reads logical cell 4 hh + s of its TM rows -----------
+    // row = (wr TM + tm) 32 + t, so the swizzle term depends on t only
+    int rd_off[4];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4)
+        rd_off[s4] = (wr * TM * 32 + t) * 128 + (((4 * hh + s4) ^ ((t >> 1) & 7)) << 4);
+    const int lane16 = lane * 16;
+
+    int64_t dp_next = lin;                                     // next whole tile of this workgroup
+    int64_t u = a.sk_share * lin;                              // its range of the shared K tiles
+    int64_t u_end = u + a.sk_share;
+    if (u_end > a.sk_units) u_end = a.sk_units;
+    bool first_piece = true;
+  for (;;) {
+    // ---- next piece: output tile and K tiles [kt0, kt1) -------------------------------------------
+    int64_t tile_lin;
+    int64_t kt0, kt1;
+    if (dp_next < a.dp_tiles) {
+        tile_lin = dp_next; kt0 = 0; kt1 = a.KT;
+        dp_next += gridDim.x;
+    } else if (u < u_end) {
+        const int64_t rt = u / a.KT;
+        tile_lin = a.dp_tiles + rt;
+        kt0 = u - rt * a.KT;
+        kt1 = kt0 + (u_end - u);
+        if (kt1 > a.KT) kt1 = a.KT;
+        u += kt1 - kt0;
+    } else {
+        break;
+    }
+    const bool owner = (kt0 == 0);                             // this piece stores the tile
+    if (!first_piece) __syncthreads();                         // every wavefront is done with the LDS stages
+    first_piece = false;
+    // output tiles are walked in bands of group_m tile rows
+    int tile_m, tile_n;
+    {
+        const int64_t width = (int64_t)a.group_m * a.grid_n;
+        const int grp = (int)(tile_lin / width);
+        const int in = (int)(tile_lin - grp * width);
+        const int first_m = grp * a.group_m;
+        const int gsize = (a.grid_m - first_m < a.group_m) ? a.grid_m - first_m : a.group_m;
+        tile_m = first_m + in % gsize;
+        tile_n = in / gsize;
+    }
+    const int64_t m0 = (int64_t)tile_m * BM;
+    // ---- activation loader: thread -> 16-byte cells of a stage -----------------------------------
+    // Cell j of this thread is row (tid >> 3) + j * (NT / 8), 16-byte column tid & 7.  Rows past M are
+    // read as they are (the workspace rows are padded to the tile height) and never stored.
+    const uint16_t* ld_base = a.Xh + (m0 + ld_row0) * a.ldxh + 8 * (tid & 7);
+    const int64_t ld_stride = (int64_t)ROWS_PER_PASS * a.ldxh;           // elements between passes
+    const int64_t g0 = ((int64_t)tile_n * WC + wc) * TN;       // first column group of this wavefront
+    auto group_of = [&](int tn) {
+        const int64_t g = g0 + tn;
+        return g < a.N32 ? g : a.N32 - 1;                      // clamp; the store is masked
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
+
+    struct WSet {                // packed codes of one chunk for this wavefront's TN column groups
+        u32x4 c[TN];
+    };
+    struct ESet {                // exponent bytes of one K tile (four chunks) for the same groups
+        u32x2 e[TN];
+    };
+    auto load_wset = [&](WSet& w, int64_t ch) {
+        const int64_t tile = ch >> 2;
+        const int cc = (int)(ch & 3);
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const uint8_t* rec = a.Wt + (tile * a.N32 + group_of(tn)) * kWRecordBytes;   // wave-uniform
+            w.c[tn] = *reinterpret_cast<const u32x4*>(rec + cc * 1024 + lane16);
+        }
+    };
+    auto load_eset = [&](ESet& x, int64_t tile) {
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const uint8_t* rec = a.Wt + (tile * a.N32 + group_of(tn)) * kWRecordBytes;
+            x.e[tn] = *reinterpret_cast<const u32x2*>(rec + kWExpOffset + (lane16 >> 1));
+        }
+    };
+    auto fetch_x = [&](u32x4 (&st)[LPT], int64_t ch) {
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) st[j] = *reinterpret_cast<const u32x4*>(ld_base + j * ld_stride + ch * 64);
+    };
+    // Correction chunk tc when the projection kernel left T as S partial sums (it split K over
+    // workgroups): add them in slice order and form the bf16 term this cell holds - T_hi for tail
+    // columns below kp, T_lo for the next kp, zero behind.
+    auto fetch_t = [&](u32x4 (&st)[LPT], int64_t tc) {
+        const int col = (int)tc * 64 + 8 * (tid & 7);
+        const bool lo = col >= a.kp;
+        const int r0 = lo ? col - a.kp : col;
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            float sum[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum[e] = 0.f;
+            if (col < 2 * a.kp) {
+                const float* src = a.Tpart + (m0 + ld_row0 + j * ROWS_PER_PASS) * a.kp + r0;
+                for (int sl = 0; sl < a.S; ++sl) {
+                    const f32x4 p0 = *reinterpret_cast<const f32x4*>(src + sl * a.tp_stride);
+                    const f32x4 p1 = *reinterpret_cast<const f32x4*>(src + sl * a.tp_stride + 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { sum[e] += p0[e]; sum[4 + e] += p1[e]; }
+                }
+            }
+            uint32_t h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t hb = f32_bits(sum[e]) & 0xFFFF0000u;
+                h[e] = lo ? f32_bits(sum[e] - f32_from_bits(hb)) >> 16 : hb >> 16;
+            }
+            st[j] = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+        }
+    };
+    // any chunk of the activation row: a main one or a correction chunk in either form
+    auto fetch_any = [&](u32x4 (&st)[LPT], int64_t ch) {
+        if (ch < a.KT * 4 || a.S <= 1) fetch_x(st, ch);
+        else fetch_t(st, ch - a.KT * 4);
+    };
+    auto store_x = [&](const u32x4 (&st)[LPT], int stage) {
+#pragma unroll
+        for (int j = 0; j < LPT; ++j)
+            *reinterpret_cast<u32x4*>(lds + stage * STAGE + ld_dst0 + j * ROWS_PER_PASS * 128) = st[j];
+    };
+    // one 64-wide chunk of the main product: c = chunk index within its K tile = stage = register set.
+    // The activation operands are read one MFMA step ahead: `xa` holds step 0 on entry and step 0
+    // of the next chunk on exit (that stage was completed two barriers ago, so it may be read
+    // before the next barrier).
+    Frag xa[TM];
+    auto read_xa = [&](Frag (&dst)[TM], int stage_idx, int s4) {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+            dst[tm].u = *reinterpret_cast<const u32x4*>(lds + stage_idx * STAGE + rd_off[s4] + tm * 4096);
+    };
+    auto mma_chunk = [&](const WSet& w, const ESet& x, int c) {
+        float sc[TN][2];
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const uint32_t ew = x.e[tn][c >> 1] >> (16 * (c & 1));
+            sc[tn][0] = w_scale(ew & 0xFFu);
+            sc[tn][1] = w_scale((ew >> 8) & 0xFFu);
+        }
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+            Frag xn[TM];
+            if (s4 < 3) read_xa(xn, c, s4 + 1);
+            else read_xa(xn, (c + 1) & 3, 0);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const bf16x8 wv = unpack_w8(w.c[tn][s4], sc[tn][s4 >> 1]);
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) acc[tm][tn] = mfma32(wv, xa[tm].v, acc[tm][tn]);
+            }
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) xa[tm] = xn[tm];
+        }
+    };
+
+    // prologue: activations of the piece's first two chunks into stages 0 and 1, and their weights
+    // (a K tile is four chunks, so a piece has at least four)
+    const int64_t first_ch = kt0 * 4;
+    WSet w0, w1, w2, w3;
+    ESet ea, eb;
+    {
+        u32x4 st[LPT];
+        fetch_x(st, first_ch);
+        load_eset(ea, kt0);
+        load_wset(w0, first_ch);
+        store_x(st, 0);
+        fetch_x(st, first_ch + 1);
+        load_wset(w1, first_ch + 1);
+        store_x(st, 1);
+    }
+
+    // ---- main product -----------------------------------------------------------------------------
+    // chunk ch: barrier; fetch activations and weights of chunk ch+2; arithmetic of chunk ch;
+    // write the fetched activations into stage (ch+2)%4, which was last read two barriers ago.
+    // Exponent bytes of the next tile are fetched during the second chunk of a tile.
+    // Every load below is issued unconditionally, with its index clamped at the end of the range:
+    // a load inside a branch would make the compiler's wait counts assume the worst case and the
+    // LDS write at the end of the chunk would wait for the newest weights as well.
+    const int64_t last_main = kt1 * 4 - 1, last_tile = kt1 - 1;
+    auto step = [&](const WSet& cur, const ESet& ecur, WSet& fill, ESet& enext, int64_t ch, int c) {
+        __syncthreads();
+        if (ch == first_ch) read_xa(xa, 0, 0);   // later chunks find step 0 already read by the previous one
+        u32x4 st[LPT];
+        fetch_x(st, ch + 2 < last_main ? ch + 2 : last_main);
+        // loads retire in order: keep the activation loads ahead of the weight loads, so that the
+        // LDS write at the end of this chunk does not have to wait for the weights of chunk ch+2
+        __builtin_amdgcn_sched_barrier(0);
+        load_wset(fill, ch + 2 < last_main ? ch + 2 : last_main);
+        if (c == 1) load_eset(enext, (ch >> 2) + 1 < last_tile ? (ch >> 2) + 1 : last_tile);
+        mma_chunk(cur, ecur, c);
+        store_x(st, (c + 2) & 3);      // stage (ch+2)%4: free since two barriers ago, also for a clamped re-write
+    };
+    for (int64_t tile = kt0; tile < kt1; tile += 2) {
+        step(w0, ea, w2, eb, tile * 4 + 0, 0);
+        step(w1, ea, w3, eb, tile * 4 + 1, 1);
+        step(w2, ea, w0, eb, tile * 4 + 2, 2);
+        step(w3, ea, w1, eb, tile * 4 + 3, 3);
+        if (tile + 1 < kt1) {
+            step(w0, eb, w2, ea, tile * 4 + 4, 0);
+            step(w1, eb, w3, ea, tile * 4 + 5, 1);
+            step(w2, eb, w0, ea, tile * 4 + 6, 2);
+            step(w3, eb, w1, ea, tile * 4 + 7, 3);
+        }
+    }
+
+    // ---- rank-kp correction: [T_hi | T_lo | 0] against B_k ---------------------------------------
+    // The (at most two) correction chunks are fetched here rather than ahead from the main loop: B_k's
+    // records are needed at the same moment and cost the same memory round trip.  Stages 0 and 1 are
+    // free: every wavefront is past the barrier of the last main chunk, which reads stage 3.
+    // lane half hh owns rank blocks jb = 4 cc + 2 hh + {0, 1} of tail chunk cc
+    const int my_tail = owner ? tail_chunks : 0;              // the piece that stores the tile adds the correction
+    if (my_tail > 0) {
+        u32x4 tst[2][LPT];
+        fetch_any(tst[0], main_chunks);
+        if (tail_chunks > 1) fetch_any(tst[1], main_chunks + 1);
+        store_x(tst[0], 0);
+        if (tail_chunks > 1) store_x(tst[1], 1);
+        __syncthreads();
+    }
+    for (int cc = 0; cc < my_tail; ++cc) {
+        const uint8_t* stage = lds + (cc & 3) * STAGE;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int jb = 4 * cc + 2 * hh + j;
+            const bool live = jb < nb2;
+            const int rb = live ? (jb < a.kp16 ? jb : jb - a.kp16) : 0;
+            Frag bf[TN][2];
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                u32x4 cw = u32x4{0, 0, 0, 0};
+                uint32_t eb = 0;
+                if (live) {
+                    const uint8_t* rec = a.Bt + (group_of(tn) * a.kp16 + rb) * kBRecordBytes;
+                    cw = *reinterpret_cast<const u32x4*>(rec + t * 16);
+                    eb = rec[512 + t];
+                }
+                int8x16_to_frags(cw, h_scale(eb), bf[tn][0], bf[tn][1]);
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                Frag xa[TM];
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+                    xa[tm].u = *reinterpret_cast<const u32x4*>(stage + rd_off[2 * j + h] + tm * 4096);
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) acc[tm][tn] = mfma32(bf[tn][h].v, xa[tm].v, acc[tm][tn]);
+            }
+        }
+    }
+
+    // ---- a piece that starts inside the tile hands its accumulators over ---------------------------
+    constexpr int64_t PART_FLOATS = (int64_t)NW * TM * TN * 1024;          // = BM x BN
+    if (false) {
+        float* slot = a.Part + (int64_t)lin * PART_FLOATS + ((int64_t)wave * TM * TN * 4 * 64 + lane) * 4;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4)
+                    *reinterpret_cast<f32x4*>(slot + ((tm * TN + tn) * 4 + r4) * 256) =
+                        f32x4{acc[tm][tn][4 * r4], acc[tm][tn][4 * r4 + 1], acc[tm][tn][4 * r4 + 2], acc[tm][tn][4 * r4 + 3]};
+        __threadfence();                                       // the slot is visible to the whole device ...
+        __syncthreads();
+        if (tid == 0)                                          // ... before the flag is
+            __hip_atomic_store(a.flags + lin, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        continue;
+    }
+    // ---- the piece with the start of the tile adds the later pieces, in K order --------------------
+    if (false) {
+        const int64_t rt = tile_lin - a.dp_tiles;
+        const int64_t last_wg = ((rt + 1) * a.KT - 1) / a.sk_share;        // workgroup with the tile's last K tile
+        for (int64_t w = lin + 1; w <= last_wg; ++w) {
+            if (tid == 0) {
+                int polls = 0;
+                while (__hip_atomic_load(a.flags + w, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == 0u &&
+                       polls < a.spin_limit) {
+                    __builtin_amdgcn_s_sleep(32);
+                    ++polls;
+                }
+                wait_ok = (polls < a.spin_limit) ? 1 : 0;
+            }
+            __syncthreads();
+            const bool ok = wait_ok != 0;
+            __threadfence();                                   // nothing cached from before the flag was seen
+            const float* slot = a.Part + w * PART_FLOATS + ((int64_t)wave * TM * TN * 4 * 64 + lane) * 4;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        f32x4 v = *reinterpret_cast<const f32x4*>(slot + ((tm * TN + tn) * 4 + r4) * 256);
+                        // a piece that never arrived must not pass for a result
+                        if (!ok) v = f32x4{__builtin_nanf(""), __builtin_nanf(""), __builtin_nanf(""), __builtin_nanf("")};
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc[tm][tn][4 * r4 + j] += v[j];
+                        // keep the loads from being hoisted into one group: 32 of them would need 128 registers
+                        if (r4 == 3) __builtin_amdgcn_sched_barrier(0);
+                    }
+            __syncthreads();                                   // wait_ok may be rewritten
+        }
+    }
+
+    // ---- store: lane (t, hh) holds columns 8 r4 + 4 hh .. + 3 of token t for every MFMA tile ------
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int64_t row = m0 + (wr * TM + tm) * 32 + t;
+        if (row >= a.M) continue;
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const int64_t cg = g0 + tn;
+            if (cg >= a.N32) continue;
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int64_t n = cg * 32 + 8 * r4 + 4 * hh;
+                float* dst = a.Y + row * a.ldy + n;
+                const f32x4 v = f32x4{acc[tm][tn][4 * r4], acc[tm][tn][4 * r4 + 1], acc[tm][tn][4 * r4 + 2], acc[tm][tn][4 * r4 + 3]};
+                if (n + 3 < a.N) {
+                    *reinterpret_cast<f32x4*>(dst) = v;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (n + j < a.N) dst[j] = v[j];
+                }
+            }
+        }
+    }
+  }   // pieces
+}
+
+// Time estimates (arbitrary unit: tile area / TFLOP/s) for one tile shape, launched as one workgroup
+// per tile or with the work split described at the head of this file.
+struct TileShape { int id, bm, bn, share; double pair, single; };
+// whole-chip TFLOP/s measured on an 8192 x 28672 layer at M = 4096: `pair` with `share` workgroups on
+// every compute unit, `single` with one
+static const TileShape kShapes[] = {
+    {11, 128, 512, 1, 1372.0, 1372.0}, {12, 128, 256, 2, 1309.0, 1136.0}, {4, 128, 128, 2, 1058.0, 900.0},
+};
+
+struct Split { int64_t grid, dp_tiles, sk_units, sk_share; };
+
+static Split whole_tiles(int64_t tiles) { return Split{tiles, tiles, 0, 1}; }
+
+// slots = workgroups the chip holds at once
+static Split split_tiles(int64_t tiles, int64_t KT, int64_t slots) {
+    Split sp;
+    sp.grid = slots;
+    sp.dp_tiles = (tiles / slots) * slots;
+    sp.sk_units = (tiles - sp.dp_tiles) * KT;
+    sp.sk_share = (sp.sk_units + slots - 1) / slots;
+    if (sp.sk_share < 2) sp.sk_share = 2;                    // a piece is worth its hand-over
+    if (sp.sk_units == 0) return whole_tiles(tiles);
+    return sp;
+}
+
+static double time_whole(const TileShape& sh, int64_t tiles, int cus) {
+    const int64_t n = (tiles + cus - 1) / cus;               // tiles of the busiest compute unit
+    const double w = (double)sh.bm * sh.bn;
+    return (sh.share == 2) ? (double)(n / 2) * 2.0 * w / sh.pair + (double)(n % 2) * w / sh.single
+                           : (double)n * w / sh.single;
+}
+
+static double time_split(const TileShape& sh, int64_t tiles, int64_t KT, int cus) {
+    const Split sp = split_tiles(tiles, KT, (int64_t)cus * sh.share);
+    const double w = (double)sh.bm * sh.bn;
+    const double rounds = (double)(sp.dp_tiles / sp.grid);
+    // every workgroup: its whole tiles, then its share of K tiles, then one hand-over (about a K tile's worth)
+    const double busiest = rounds + ((double)sp.sk_share + (sp.sk_units ? 1.0 : 0.0)) / (double)KT;
+    return busiest * (double)sh.share * w / sh.pair;
+}
+
+template <int TM, int TN, int WR, int WC, int NS, int MINW = 1>
+static hipError_t launch_tiled_t(TiledArgs a, int64_t M, int mode, int cus, hipStream_t s) {
+    constexpr int BM = 32 * TM * WR, BN = 32 * TN * WC;
+    constexpr int LDS_BYTES = NS * BM * 128;
+    a.grid_m = (int)((M + BM - 1) / BM);
+    a.grid_n = (int)((a.N + BN - 1) / BN);
+    a.group_m = 8;
+    const int64_t tiles = (int64_t)a.grid_m * a.grid_n;
+    TileShape me = {0, BM, BN, MINW, 1.0, 1.0};
+    for (const TileShape& sh : kShapes)
+        if (sh.bm == BM && sh.bn == BN && sh.share == MINW) me = sh;
+    const int64_t slots = (int64_t)cus * MINW;
+    // mode 0: split when the estimate says so; 1: never; 2: whenever there is a remainder to split
+    bool split = false;
+    if (a.Part != nullptr && (int64_t)BM * BN * 4 * slots <= kTiledPartBytesPerCu * (int64_t)cus && slots <= kTiledFlags) {
+        if (mode == 2) split = true;
+        else if (mode == 0) split = time_split(me, tiles, a.KT, cus) < time_whole(me, tiles, cus);
+    }
+    const Split sp = split ? split_tiles(tiles, a.KT, slots) : whole_tiles(tiles);
+    a.dp_tiles = sp.dp_tiles; a.sk_units = sp.sk_units; a.sk_share = sp.sk_share;
+    auto kern = tiled_kernel<TM, TN, WR, WC, NS, MINW>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((unsigned)sp.grid), block(64 * WR * WC);
+    hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, s, a);
+    return hipGetLastError();
+}
+
+int compute_units() {
+    static int cus = 0;                                      // one kind of device per process
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cus = n;
+    }
+    return cus;
+}
+
+hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
+                        int variant, hipStream_t s) {
+    if (M == 0) return hipSuccess;
+    TiledArgs a;
+    a.Wt = L.Wt; a.Bt = L.Bt; a.Xh = ws.Xh; a.ldxh = ws.ldxh; a.Y = Y; a.ldy = ldy;
+    a.Tpart = ws.Tpart; a.S = ws.S; a.tp_stride = ws.tp_rows * L.kp;
+    a.M = M; a.N = L.N; a.KT = L.KT; a.N32 = L.N32; a.kp = L.kp; a.kp16 = L.kp16;
+    a.grid_m = a.grid_n = 0; a.group_m = 8;
+    a.Part = ws.Part; a.flags = ws.flags;
+    a.spin_limit = 1 << 21;                                  // about a second of polling
+    a.dp_tiles = a.sk_units = 0; a.sk_share = 1;
+    const int cus = compute_units();
+    // variant = 100 * mode + tile shape; mode 0 = split the work when the estimate says so, 1 = never, 2 = always
+    int mode = variant / 100;
+    variant %= 100;
+    if (mode < 0 || mode > 2) return hipErrorInvalidValue;
+    if (variant == 0) {
+        // pick the tile shape (and the split) with the lowest estimated time
+        double best = 0.0;
+        for (const TileShape& sh : kShapes) {
+            const int64_t tiles = ((M + sh.bm - 1) / sh.bm) * ((L.N + sh.bn - 1) / sh.bn);
+            double t = time_whole(sh, tiles, cus);
+            if (mode != 1 && ws.Part != nullptr) {
+                const double ts = time_split(sh, tiles, L.KT, cus);
+                if (mode == 2 || ts < t) t = ts;
+            }
+            if (variant == 0 || t < best) { best = t; variant = sh.id; }
+        }
+    }
+    switch (variant) {
+        case 1: return launch_tiled_t<4, 4, 2, 2, 4>(a, M, mode, cus, s);      // 256 x 256
+        case 3: return launch_tiled_t<2, 4, 2, 2, 4>(a, M, mode, cus, s);      // 128 x 256
+        case 4: return launch_tiled_t<2, 2, 2, 2, 4, 2>(a, M, mode, cus, s);   // 128 x 128, two workgroups per compute unit
+        case 7: return launch_tiled_t<2, 4, 2, 4, 4>(a, M, mode, cus, s);      // 128 x 512, eight wavefronts
+        case 8: return launch_tiled_t<2, 4, 2, 2, 4, 2>(a, M, mode, cus, s);   // 128 x 256, two workgroups per compute unit
+        case 11: return launch_tiled_t<4, 2, 1, 8, 4>(a, M, mode, cus, s);     // 128 x 512, eight wavefronts, each 128 x 64
+        case 12: return launch_tiled_t<4, 2, 1, 4, 4, 2>(a, M, mode, cus, s);  // 128 x 256, four wavefronts each 128 x 64, two workgroups per compute unit
+        case 13: return launch_tiled_t<4, 2, 1, 4, 4>(a, M, mode, cus, s);     // 128 x 256, four wavefronts each 128 x 64
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace lqer

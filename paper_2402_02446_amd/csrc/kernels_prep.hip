@@ -32,6 +32,7 @@ struct PrepArgs {
     int lr;                // CELLS: log2 of the token rows per 16-byte cell column
     float* Yz; int64_t ldy, N;   // Yz != null: extra workgroups clear Y[M][N] for a main kernel that adds into it
     int nslices;                 // K slices = the part of grid.y that does the projection
+    uint32_t* flags; int nflags; // flags != null: words the first workgroup clears for the main kernel
 };
 
 __device__ __forceinline__ void split_bf16(float t, uint16_t& hi, uint16_t& lo) {
@@ -63,6 +64,9 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
     f32x4 acc[MAXG];
 #pragma unroll
     for (int g = 0; g < MAXG; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (a.flags != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
+        for (int i = threadIdx.x; i < a.nflags; i += blockDim.x) a.flags[i] = 0u;
 
     // Workgroups behind the a.nslices K slices (grid.y) only clear Y for a main kernel that adds into it,
     // so the clearing runs beside the projection instead of in front of it.
@@ -267,6 +271,7 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     a.lr = ws.lr;
     a.Yz = y_zero; a.ldy = ldy; a.N = L.N;
     a.nslices = ws.S;
+    a.flags = ws.flags; a.nflags = ws.flags ? kTiledFlags : 0;
     const bool cells = ws.cells;
     int nwaves = a.tiles_per_slice;
     if (nwaves > kPrepWaves) nwaves = kPrepWaves;

@@ -17,6 +17,16 @@
 //   the rank-kp correction is ceil(2 kp / 64) more chunks whose weight operand comes from B_k.
 // MFMA operands are swapped (weights first) so a lane ends up with runs of four consecutive
 // output columns of one token and stores each as one 16-byte write.
+//
+// Work split.  The launch is either one workgroup per output tile, or - when the tiles do not fill
+// whole rounds of the chip - as many workgroups as the chip holds at once, each taking its share of
+// whole tiles and, before them, an equal share of the K tiles of the remaining output tiles (those
+// are cut wherever a share ends).  A workgroup whose share starts inside an output tile leaves its
+// accumulators in a workspace slot of its own and raises a flag; the workgroup that has the start
+// of that output tile adds the later pieces in K order and stores.  A share is one contiguous range,
+// so only its first piece can be handed over and only its last piece can wait, and the waiting
+// piece needs pieces that are computed first by the workgroups they belong to: no wait depends on
+// another wait.  The sum order is fixed by the split, so the result has the same bits every run.
 #include "lqer_internal.h"
 #include "mx_device.h"
 
@@ -31,6 +41,13 @@ struct TiledArgs {
     int kp, kp16;
     int grid_m, grid_n;
     int group_m;
+    // work split (see the head of this file)
+    int64_t dp_tiles;          // output tiles taken whole, tile i by workgroup i % gridDim.x
+    int64_t sk_units;          // K tiles of the remaining output tiles, shared out in ranges of ...
+    int64_t sk_share;          // ... this many per workgroup
+    float* Part;               // [gridDim.x][BM * BN] accumulators handed over
+    uint32_t* flags;           // [gridDim.x], zero before the launch; 1 = slot written
+    int spin_limit;            // polls of a flag before the waiting workgroup gives up (and stores NaN)
 };
 
 // MINW = wavefronts per SIMD the register allocation must allow (2 lets two four-wavefront workgroups share a compute unit)
@@ -50,31 +67,24 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     const int wr = wave / WC, wc = wave % WC;
     const int t = lane & 31, hh = lane >> 5;
 
-    // ---- workgroup -> tile: consecutive ids land on one XCD, tiles are walked in bands ------
-    int tile_m, tile_n;
+    // ---- workgroup -> position in the work split: consecutive positions land on one XCD ----------
+    int lin;
     {
-        const int nwg = a.grid_m * a.grid_n;
+        const int nwg = gridDim.x;
         const int pid = blockIdx.x;
         const int xcd = pid & 7, local = pid >> 3;
         const int per = nwg >> 3, rem = nwg & 7;
-        const int lin = (xcd < rem) ? xcd * (per + 1) + local : rem * (per + 1) + (xcd - rem) * per + local;
-        const int width = a.group_m * a.grid_n;
-        const int grp = lin / width;
-        const int first_m = grp * a.group_m;
-        const int gsize = (a.grid_m - first_m < a.group_m) ? a.grid_m - first_m : a.group_m;
-        tile_m = first_m + (lin % width) % gsize;
-        tile_n = (lin % width) / gsize;
+        lin = (xcd < rem) ? xcd * (per + 1) + local : rem * (per + 1) + (xcd - rem) * per + local;
     }
-    const int64_t m0 = (int64_t)tile_m * BM;
-    // ---- activation loader: thread -> 16-byte cells of a stage -----------------------------------
-    // Cell j of this thread is row (tid >> 3) + j * (NT / 8), 16-byte column tid & 7.  Rows past M are
-    // read as they are (the workspace rows are padded to the tile height) and never stored.
+    __shared__ int wait_ok;
+    const int64_t main_chunks = a.KT * 4;
+    const int nb2 = 2 * a.kp16;
+    const int tail_chunks = (nb2 + 3) / 4;
+    static_assert(NS == 4, "stage and register-set indices below assume rings of four");
     constexpr int ROWS_PER_PASS = NT / 8;
-    const int ld_row0 = tid >> 3;
-    const uint16_t* ld_base = a.Xh + (m0 + ld_row0) * a.ldxh + 8 * (tid & 7);
-    const int64_t ld_stride = (int64_t)ROWS_PER_PASS * a.ldxh;           // elements between passes
-    // (row >> 1) & 7 is the same for every pass because ROWS_PER_PASS is a multiple of 16
     static_assert(ROWS_PER_PASS % 16 == 0, "swizzle must not depend on the pass");
+    const int ld_row0 = tid >> 3;
+    // (row >> 1) & 7 is the same for every pass because ROWS_PER_PASS is a multiple of 16
     const int ld_dst0 = ld_row0 * 128 + (((tid & 7) ^ ((ld_row0 >> 1) & 7)) << 4);
     // ---- operand reader: in step s this lane reads logical cell 4 hh + s of its TM rows -----------
     // row = (wr TM + tm) 32 + t, so the swizzle term depends on t only
@@ -82,12 +92,57 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4)
         rd_off[s4] = (wr * TM * 32 + t) * 128 + (((4 * hh + s4) ^ ((t >> 1) & 7)) << 4);
+    const int lane16 = lane * 16;
+
+    int64_t dp_next = lin;                                     // next whole tile of this workgroup
+    int64_t u = a.sk_share * lin;                              // its range of the shared K tiles
+    int64_t u_end = u + a.sk_share;
+    if (u_end > a.sk_units) u_end = a.sk_units;
+    bool first_piece = true;
+  for (;;) {
+    // ---- next piece: output tile and K tiles [kt0, kt1) -------------------------------------------
+    int64_t tile_lin;
+    int64_t kt0, kt1;
+    // The shared K tiles come first: the hand-over between workgroups then overlaps with the whole
+    // tiles of other workgroups instead of ending the kernel.
+    if (u < u_end) {
+        const int64_t rt = u / a.KT;
+        tile_lin = a.dp_tiles + rt;
+        kt0 = u - rt * a.KT;
+        kt1 = kt0 + (u_end - u);
+        if (kt1 > a.KT) kt1 = a.KT;
+        u += kt1 - kt0;
+    } else if (dp_next < a.dp_tiles) {
+        tile_lin = dp_next; kt0 = 0; kt1 = a.KT;
+        dp_next += gridDim.x;
+    } else {
+        break;
+    }
+    const bool owner = (kt0 == 0);                             // this piece stores the tile
+    if (!first_piece) __syncthreads();                         // every wavefront is done with the LDS stages
+    first_piece = false;
+    // output tiles are walked in bands of group_m tile rows
+    int tile_m, tile_n;
+    {
+        const int64_t width = (int64_t)a.group_m * a.grid_n;
+        const int grp = (int)(tile_lin / width);
+        const int in = (int)(tile_lin - grp * width);
+        const int first_m = grp * a.group_m;
+        const int gsize = (a.grid_m - first_m < a.group_m) ? a.grid_m - first_m : a.group_m;
+        tile_m = first_m + in % gsize;
+        tile_n = in / gsize;
+    }
+    const int64_t m0 = (int64_t)tile_m * BM;
+    // ---- activation loader: thread -> 16-byte cells of a stage -----------------------------------
+    // Cell j of this thread is row (tid >> 3) + j * (NT / 8), 16-byte column tid & 7.  Rows past M are
+    // read as they are (the workspace rows are padded to the tile height) and never stored.
+    const uint16_t* ld_base = a.Xh + (m0 + ld_row0) * a.ldxh + 8 * (tid & 7);
+    const int64_t ld_stride = (int64_t)ROWS_PER_PASS * a.ldxh;           // elements between passes
     const int64_t g0 = ((int64_t)tile_n * WC + wc) * TN;       // first column group of this wavefront
     auto group_of = [&](int tn) {
         const int64_t g = g0 + tn;
         return g < a.N32 ? g : a.N32 - 1;                      // clamp; the store is masked
     };
-    const int lane16 = lane * 16;
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -96,12 +151,6 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
-
-    const int64_t main_chunks = a.KT * 4;
-    const int nb2 = 2 * a.kp16;
-    const int tail_chunks = (nb2 + 3) / 4;
-    const int64_t chunks = main_chunks + tail_chunks;
-    static_assert(NS == 4, "stage and register-set indices below assume rings of four");
 
     struct WSet {                // packed codes of one chunk for this wavefront's TN column groups
         u32x4 c[TN];
@@ -203,20 +252,20 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         }
     };
 
-    // prologue: activations of chunks 0 and 1 into stages 0 and 1, weights of chunks 0 and 1
+    // prologue: activations of the piece's first two chunks into stages 0 and 1, and their weights
+    // (a K tile is four chunks, so a piece has at least four)
+    const int64_t first_ch = kt0 * 4;
     WSet w0, w1, w2, w3;
     ESet ea, eb;
     {
         u32x4 st[LPT];
-        fetch_x(st, 0);
-        load_eset(ea, 0);
-        load_wset(w0, 0);
+        fetch_x(st, first_ch);
+        load_eset(ea, kt0);
+        load_wset(w0, first_ch);
         store_x(st, 0);
-        if (chunks > 1) {
-            fetch_x(st, 1);
-            if (main_chunks > 1) load_wset(w1, 1);
-            store_x(st, 1);
-        }
+        fetch_x(st, first_ch + 1);
+        load_wset(w1, first_ch + 1);
+        store_x(st, 1);
     }
 
     // ---- main product -----------------------------------------------------------------------------
@@ -226,10 +275,10 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     // Every load below is issued unconditionally, with its index clamped at the end of the range:
     // a load inside a branch would make the compiler's wait counts assume the worst case and the
     // LDS write at the end of the chunk would wait for the newest weights as well.
-    const int64_t last_main = main_chunks - 1, last_tile = a.KT - 1;
+    const int64_t last_main = kt1 * 4 - 1, last_tile = kt1 - 1;
     auto step = [&](const WSet& cur, const ESet& ecur, WSet& fill, ESet& enext, int64_t ch, int c) {
         __syncthreads();
-        if (ch == 0) read_xa(xa, 0, 0);          // later chunks find step 0 already read by the previous one
+        if (ch == first_ch) read_xa(xa, 0, 0);   // later chunks find step 0 already read by the previous one
         u32x4 st[LPT];
         fetch_x(st, ch + 2 < last_main ? ch + 2 : last_main);
         // loads retire in order: keep the activation loads ahead of the weight loads, so that the
@@ -240,12 +289,12 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         mma_chunk(cur, ecur, c);
         store_x(st, (c + 2) & 3);      // stage (ch+2)%4: free since two barriers ago, also for a clamped re-write
     };
-    for (int64_t tile = 0; tile < a.KT; tile += 2) {
+    for (int64_t tile = kt0; tile < kt1; tile += 2) {
         step(w0, ea, w2, eb, tile * 4 + 0, 0);
         step(w1, ea, w3, eb, tile * 4 + 1, 1);
         step(w2, ea, w0, eb, tile * 4 + 2, 2);
         step(w3, ea, w1, eb, tile * 4 + 3, 3);
-        if (tile + 1 < a.KT) {
+        if (tile + 1 < kt1) {
             step(w0, eb, w2, ea, tile * 4 + 4, 0);
             step(w1, eb, w3, ea, tile * 4 + 5, 1);
             step(w2, eb, w0, ea, tile * 4 + 6, 2);
@@ -258,7 +307,13 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     // records are needed at the same moment and cost the same memory round trip.  Stages 0 and 1 are
     // free: every wavefront is past the barrier of the last main chunk, which reads stage 3.
     // lane half hh owns rank blocks jb = 4 cc + 2 hh + {0, 1} of tail chunk cc
-    if (tail_chunks > 0) {
+    // Lane indices for everything behind the main loop come through an opaque copy: address terms
+    // built from them would otherwise be computed once in front of the loop over pieces and
+    // occupy registers all through the main product.
+    int t_e = t, hh_e = hh, lane_e = lane;
+    asm volatile("" : "+v"(t_e), "+v"(hh_e), "+v"(lane_e));
+    const int my_tail = owner ? tail_chunks : 0;              // the piece that stores the tile adds the correction
+    if (my_tail > 0) {
         u32x4 tst[2][LPT];
         fetch_any(tst[0], main_chunks);
         if (tail_chunks > 1) fetch_any(tst[1], main_chunks + 1);
@@ -266,11 +321,11 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         if (tail_chunks > 1) store_x(tst[1], 1);
         __syncthreads();
     }
-    for (int cc = 0; cc < tail_chunks; ++cc) {
+    for (int cc = 0; cc < my_tail; ++cc) {
         const uint8_t* stage = lds + (cc & 3) * STAGE;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int jb = 4 * cc + 2 * hh + j;
+            const int jb = 4 * cc + 2 * hh_e + j;
             const bool live = jb < nb2;
             const int rb = live ? (jb < a.kp16 ? jb : jb - a.kp16) : 0;
             Frag bf[TN][2];
@@ -280,8 +335,8 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
                 uint32_t eb = 0;
                 if (live) {
                     const uint8_t* rec = a.Bt + (group_of(tn) * a.kp16 + rb) * kBRecordBytes;
-                    cw = *reinterpret_cast<const u32x4*>(rec + t * 16);
-                    eb = rec[512 + t];
+                    cw = *reinterpret_cast<const u32x4*>(rec + t_e * 16);
+                    eb = rec[512 + t_e];
                 }
                 int8x16_to_frags(cw, h_scale(eb), bf[tn][0], bf[tn][1]);
             }
@@ -299,10 +354,75 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         }
     }
 
+    // ---- a piece that starts inside the tile hands its accumulators over ---------------------------
+    // The slot is written and read with device-scope relaxed atomic accesses of 8 bytes: they pass
+    // through the XCD's L2 to where every XCD sees them, so neither side needs a cache write-back or
+    // invalidate (which would also throw out the weights and activations other workgroups share there).
+    constexpr int64_t PART_FLOATS = (int64_t)NW * TM * TN * 1024;          // = BM x BN
+    typedef unsigned long long u64;
+    union Pair { u64 q; float f[2]; };
+    if (!owner) {
+        u64* slot = reinterpret_cast<u64*>(a.Part + (int64_t)lin * PART_FLOATS) + (int64_t)wave * TM * TN * 8 * 64 + lane_e;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int h8 = 0; h8 < 8; ++h8) {
+                    Pair p;
+                    p.f[0] = acc[tm][tn][2 * h8]; p.f[1] = acc[tm][tn][2 * h8 + 1];
+                    __hip_atomic_store(slot + ((tm * TN + tn) * 8 + h8) * 64, p.q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");          // this wavefront's stores have completed ...
+        __syncthreads();                                                 // ... and everyone else's
+        if (tid == 0) __hip_atomic_store(a.flags + lin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        continue;
+    }
+    // ---- the piece with the start of the tile adds the later pieces, in K order --------------------
+    if (kt1 < a.KT) {
+        const int64_t rt = tile_lin - a.dp_tiles;
+        const int64_t last_wg = ((rt + 1) * a.KT - 1) / a.sk_share;        // workgroup with the tile's last K tile
+        for (int64_t w = lin + 1; w <= last_wg; ++w) {
+            if (tid == 0) {
+                int polls = 0;
+                while (__hip_atomic_load(a.flags + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u &&
+                       polls < a.spin_limit) {
+                    __builtin_amdgcn_s_sleep(8);
+                    ++polls;
+                }
+                wait_ok = (polls < a.spin_limit) ? 1 : 0;
+            }
+            __syncthreads();
+            const bool ok = wait_ok != 0;
+            const u64* slot = reinterpret_cast<const u64*>(a.Part + w * PART_FLOATS) + (int64_t)wave * TM * TN * 8 * 64 + lane_e;
+            // groups of 32 loads: enough in flight to cover the round trip, few enough to fit beside the accumulators
+            constexpr int PER = TM * TN * 8;                   // 8-byte words of this lane in the slot
+            constexpr int GRP = PER < 32 ? PER : 32;
+            static_assert(PER % GRP == 0, "whole groups");
+#pragma unroll
+            for (int g0 = 0; g0 < PER; g0 += GRP) {
+                Pair p[GRP];
+#pragma unroll
+                for (int i = 0; i < GRP; ++i)
+                    p[i].q = __hip_atomic_load(slot + (g0 + i) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int i = 0; i < GRP; ++i) {
+                    const int mt = (g0 + i) / 8, h8 = (g0 + i) % 8;
+                    // a piece that never arrived must not pass for a result
+                    if (!ok) p[i].f[0] = p[i].f[1] = __builtin_nanf("");
+                    acc[mt / TN][mt % TN][2 * h8] += p[i].f[0];
+                    acc[mt / TN][mt % TN][2 * h8 + 1] += p[i].f[1];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __syncthreads();                                   // wait_ok may be rewritten
+        }
+    }
+
     // ---- store: lane (t, hh) holds columns 8 r4 + 4 hh .. + 3 of token t for every MFMA tile ------
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
-        const int64_t row = m0 + (wr * TM + tm) * 32 + t;
+        const int64_t row = m0 + (wr * TM + tm) * 32 + t_e;
         if (row >= a.M) continue;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
@@ -310,7 +430,7 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
             if (cg >= a.N32) continue;
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
-                const int64_t n = cg * 32 + 8 * r4 + 4 * hh;
+                const int64_t n = cg * 32 + 8 * r4 + 4 * hh_e;
                 float* dst = a.Y + row * a.ldy + n;
                 const f32x4 v = f32x4{acc[tm][tn][4 * r4], acc[tm][tn][4 * r4 + 1], acc[tm][tn][4 * r4 + 2], acc[tm][tn][4 * r4 + 3]};
                 if (n + 3 < a.N) {
@@ -323,15 +443,82 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
             }
         }
     }
+  }   // pieces
+}
+
+// Time estimates in microseconds for one tile shape, launched as one workgroup per tile or with the
+// work split described at the head of this file.
+struct TileShape { int id, bm, bn, share; double pair, single; };
+// whole-chip TFLOP/s measured on an 8192 x 28672 layer at M = 4096: `pair` with `share` workgroups on
+// every compute unit, `single` with one
+static const TileShape kShapes[] = {
+    {11, 128, 512, 1, 1372.0, 1372.0}, {12, 128, 256, 2, 1280.0, 1000.0}, {4, 128, 128, 2, 1058.0, 900.0},
+};
+constexpr double kPieceUs = 4.0;       // filling the pipeline and storing the tile, per piece
+constexpr double kHandOverUs = 30.0;   // measured cost of handing accumulators over, per workgroup sharing a compute unit
+
+struct Split { int64_t grid, dp_tiles, sk_units, sk_share; };
+
+static Split whole_tiles(int64_t tiles) { return Split{tiles, tiles, 0, 1}; }
+
+// slots = workgroups the chip holds at once
+static Split split_tiles(int64_t tiles, int64_t KT, int64_t slots) {
+    Split sp;
+    sp.grid = slots;
+    sp.dp_tiles = (tiles / slots) * slots;
+    sp.sk_units = (tiles - sp.dp_tiles) * KT;
+    sp.sk_share = (sp.sk_units + slots - 1) / slots;
+    if (sp.sk_share < 2) sp.sk_share = 2;                    // a piece is worth its hand-over
+    if (sp.sk_units == 0) return whole_tiles(tiles);
+    return sp;
+}
+
+// one K tile (256 deep) of one output tile, with `share` workgroups on every compute unit
+static double unit_us(const TileShape& sh, int share, int cus) {
+    const double rate = (share == sh.share) ? sh.pair : sh.single;       // TFLOP/s = flop/us * 1e-6
+    return 2.0 * sh.bm * sh.bn * kTileK * (double)cus * share / (rate * 1e6);
+}
+
+static double time_whole(const TileShape& sh, int64_t tiles, int64_t KT, int cus) {
+    const int64_t n = (tiles + cus - 1) / cus;               // tiles of the busiest compute unit
+    const double full = (double)KT * unit_us(sh, sh.share, cus) + kPieceUs;
+    const double alone = (double)KT * unit_us(sh, 1, cus) + kPieceUs;
+    return (sh.share == 2) ? (double)(n / 2) * full + (double)(n % 2) * alone : (double)n * full;
+}
+
+static double time_split(const TileShape& sh, int64_t tiles, int64_t KT, int cus) {
+    const Split sp = split_tiles(tiles, KT, (int64_t)cus * sh.share);
+    if (sp.sk_units == 0) return time_whole(sh, tiles, KT, cus);
+    const double rounds = (double)(sp.dp_tiles / sp.grid);
+    return (rounds * (double)KT + (double)sp.sk_share) * unit_us(sh, sh.share, cus) + (rounds + 2.0) * kPieceUs +
+           kHandOverUs * sh.share;
+}
+
+// the split has to promise a clear gain: its estimate is the rougher of the two
+static bool split_pays(const TileShape& sh, int64_t tiles, int64_t KT, int cus) {
+    return time_split(sh, tiles, KT, cus) < 0.95 * time_whole(sh, tiles, KT, cus);
 }
 
 template <int TM, int TN, int WR, int WC, int NS, int MINW = 1>
-static hipError_t launch_tiled_t(TiledArgs a, int64_t M, hipStream_t s) {
+static hipError_t launch_tiled_t(TiledArgs a, int64_t M, int mode, int cus, hipStream_t s) {
     constexpr int BM = 32 * TM * WR, BN = 32 * TN * WC;
     constexpr int LDS_BYTES = NS * BM * 128;
     a.grid_m = (int)((M + BM - 1) / BM);
     a.grid_n = (int)((a.N + BN - 1) / BN);
     a.group_m = 8;
+    const int64_t tiles = (int64_t)a.grid_m * a.grid_n;
+    TileShape me = {0, BM, BN, MINW, 1.0, 1.0};
+    for (const TileShape& sh : kShapes)
+        if (sh.bm == BM && sh.bn == BN && sh.share == MINW) me = sh;
+    const int64_t slots = (int64_t)cus * MINW;
+    // mode 0: split when the estimate says so; 1: never; 2: whenever there is a remainder to split
+    bool split = false;
+    if (a.Part != nullptr && (int64_t)BM * BN * 4 * slots <= kTiledPartBytesPerCu * (int64_t)cus && slots <= kTiledFlags) {
+        if (mode == 2) split = true;
+        else if (mode == 0) split = split_pays(me, tiles, a.KT, cus);
+    }
+    const Split sp = split ? split_tiles(tiles, a.KT, slots) : whole_tiles(tiles);
+    a.dp_tiles = sp.dp_tiles; a.sk_units = sp.sk_units; a.sk_share = sp.sk_share;
     auto kern = tiled_kernel<TM, TN, WR, WC, NS, MINW>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -340,9 +527,32 @@ static hipError_t launch_tiled_t(TiledArgs a, int64_t M, hipStream_t s) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((unsigned)(a.grid_m * a.grid_n)), block(64 * WR * WC);
+    dim3 grid((unsigned)sp.grid), block(64 * WR * WC);
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, s, a);
     return hipGetLastError();
+}
+
+__global__ void clear_flags_kernel(uint32_t* flags, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) flags[i] = 0u;
+}
+
+// For a tiled launch that does not follow the projection kernel (which clears the flags itself).
+hipError_t launch_clear_flags(const Workspace& ws, hipStream_t s) {
+    if (ws.flags == nullptr) return hipSuccess;
+    hipLaunchKernelGGL(clear_flags_kernel, dim3((kTiledFlags + 255) / 256), dim3(256), 0, s, ws.flags, kTiledFlags);
+    return hipGetLastError();
+}
+
+int compute_units() {
+    static int cus = 0;                                      // one kind of device per process
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cus = n;
+    }
+    return cus;
 }
 
 hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
@@ -353,34 +563,34 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
     a.Tpart = ws.Tpart; a.S = ws.S; a.tp_stride = ws.tp_rows * L.kp;
     a.M = M; a.N = L.N; a.KT = L.KT; a.N32 = L.N32; a.kp = L.kp; a.kp16 = L.kp16;
     a.grid_m = a.grid_n = 0; a.group_m = 8;
+    a.Part = ws.Part; a.flags = ws.flags;
+    a.spin_limit = 1 << 22;                                  // about a second of polling
+    a.dp_tiles = a.sk_units = 0; a.sk_share = 1;
+    const int cus = compute_units();
+    // variant = 100 * mode + tile shape; mode 0 = split the work when the estimate says so, 1 = never, 2 = always
+    int mode = variant / 100;
+    variant %= 100;
+    if (mode < 0 || mode > 2) return hipErrorInvalidValue;
     if (variant == 0) {
-        // Pick the tile shape with the lowest estimated time.  Tiles spread evenly over the 256
-        // compute units, so the busiest one gets n = ceil(tiles / 256) of them; a shape of which two
-        // workgroups share a compute unit runs them in pairs at rate `pair` and a last odd one at
-        // rate `single` (TFLOP/s of the whole chip, measured on an 8192 x 28672 layer at M = 4096).
-        struct Shape { int id, bm, bn, share; double pair, single; };
-        static const Shape shapes[] = {
-            {11, 128, 512, 1, 0.0, 1372.0}, {12, 128, 256, 2, 1309.0, 1136.0}, {4, 128, 128, 2, 1058.0, 900.0},
-        };
+        // pick the tile shape (and the split) with the lowest estimated time
         double best = 0.0;
-        for (const Shape& sh : shapes) {
+        for (const TileShape& sh : kShapes) {
             const int64_t tiles = ((M + sh.bm - 1) / sh.bm) * ((L.N + sh.bn - 1) / sh.bn);
-            const int64_t n = (tiles + 255) / 256;
-            const double w = (double)sh.bm * sh.bn;
-            const double t = (sh.share == 2) ? (double)(n / 2) * 2.0 * w / sh.pair + (double)(n % 2) * w / sh.single
-                                             : (double)n * w / sh.single;
+            double t = time_whole(sh, tiles, L.KT, cus);
+            if (mode == 2 && ws.Part != nullptr) t = time_split(sh, tiles, L.KT, cus);
+            else if (mode == 0 && ws.Part != nullptr && split_pays(sh, tiles, L.KT, cus)) t = time_split(sh, tiles, L.KT, cus);
             if (variant == 0 || t < best) { best = t; variant = sh.id; }
         }
     }
     switch (variant) {
-        case 1: return launch_tiled_t<4, 4, 2, 2, 4>(a, M, s);      // 256 x 256
-        case 3: return launch_tiled_t<2, 4, 2, 2, 4>(a, M, s);      // 128 x 256
-        case 4: return launch_tiled_t<2, 2, 2, 2, 4>(a, M, s);      // 128 x 128
-        case 7: return launch_tiled_t<2, 4, 2, 4, 4>(a, M, s);      // 128 x 512, eight wavefronts
-        case 8: return launch_tiled_t<2, 4, 2, 2, 4, 2>(a, M, s);   // 128 x 256, two workgroups per compute unit
-        case 11: return launch_tiled_t<4, 2, 1, 8, 4>(a, M, s);     // 128 x 512, eight wavefronts, each 128 x 64
-        case 12: return launch_tiled_t<4, 2, 1, 4, 4, 2>(a, M, s);  // 128 x 256, four wavefronts each 128 x 64, two workgroups per compute unit
-        case 13: return launch_tiled_t<4, 2, 1, 4, 4>(a, M, s);     // 128 x 256, four wavefronts each 128 x 64
+        case 1: return launch_tiled_t<4, 4, 2, 2, 4>(a, M, mode, cus, s);      // 256 x 256
+        case 3: return launch_tiled_t<2, 4, 2, 2, 4>(a, M, mode, cus, s);      // 128 x 256
+        case 4: return launch_tiled_t<2, 2, 2, 2, 4, 2>(a, M, mode, cus, s);   // 128 x 128, two workgroups per compute unit
+        case 7: return launch_tiled_t<2, 4, 2, 4, 4>(a, M, mode, cus, s);      // 128 x 512, eight wavefronts
+        case 8: return launch_tiled_t<2, 4, 2, 2, 4, 2>(a, M, mode, cus, s);   // 128 x 256, two workgroups per compute unit
+        case 11: return launch_tiled_t<4, 2, 1, 8, 4>(a, M, mode, cus, s);     // 128 x 512, eight wavefronts, each 128 x 64
+        case 12: return launch_tiled_t<4, 2, 1, 4, 4, 2>(a, M, mode, cus, s);  // 128 x 256, four wavefronts each 128 x 64, two workgroups per compute unit
+        case 13: return launch_tiled_t<4, 2, 1, 4, 4>(a, M, mode, cus, s);     // 128 x 256, four wavefronts each 128 x 64
         default: return hipErrorInvalidValue;
     }
 }

@@ -255,6 +255,15 @@ static Workspace plan_workspace(const Layer& L, int64_t M, int path, void* base)
     ws.Xh = (uint16_t*)base;
     ws.Tpart = partial ? (float*)((uint8_t*)base + xh_bytes) : nullptr;
     ws.bytes = xh_bytes + tp_bytes;
+    // tiled path: slots for accumulators handed between workgroups, and their flags
+    ws.Part = nullptr;
+    ws.flags = nullptr;
+    if (path == 2) {
+        ws.flags = (uint32_t*)((uint8_t*)base + ws.bytes);
+        ws.bytes += (size_t)kTiledFlags * 4;
+        ws.Part = (float*)((uint8_t*)base + ws.bytes);
+        ws.bytes += (size_t)(kTiledPartBytesPerCu * compute_units());
+    }
     return ws;
 }
 
@@ -298,6 +307,7 @@ static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, co
         if (launch_prep(L, X, ldx, Xc, Xe, M, ws, zero_y ? Y : nullptr, ldy, s) != hipSuccess) return LQER_ERR_HIP;
     }
     if (stages & 2) {
+        if (!(stages & 1) && path == 2 && launch_clear_flags(ws, s) != hipSuccess) return LQER_ERR_HIP;
         const hipError_t e = (path == 1) ? launch_stream(L, M, ws, Y, ldy, variant, s)
                                          : launch_tiled(L, M, ws, Y, ldy, variant, s);
         if (e == hipErrorInvalidValue) return LQER_ERR_SHAPE;

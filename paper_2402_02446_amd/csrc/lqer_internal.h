@@ -69,8 +69,16 @@ struct Workspace {
     int64_t tp_rows;     // rows per slice of Tpart (M, or M padded to the tile height for the tiled kernel)
     bool cells;          // streaming kernel: Xh holds 16-byte cells [KT*32][1 << lr token rows]
     int lr;
+    float* Part;         // tiled kernel: accumulators handed from one workgroup to another, or null
+    uint32_t* flags;     // tiled kernel: kTiledFlags words, cleared by the projection kernel
     size_t bytes;
 };
+
+// The tiled kernel may cut output tiles along K between workgroups; each workgroup resident on the
+// chip then has one slot of tile size in the workspace: 256 KiB per compute unit covers every tile
+// shape (128 x 512 with one workgroup per compute unit, 128 x 256 with two).
+constexpr int64_t kTiledPartBytesPerCu = 256 * 1024;
+constexpr int kTiledFlags = 1024;
 
 // ---- kernel launchers (each returns the hipError_t of its launch) ------------------------
 hipError_t launch_quantize_mx(const float* x, int64_t rows, int64_t cols, int64_t ld, int bits,
@@ -79,6 +87,7 @@ hipError_t launch_quantize_mx(const float* x, int64_t rows, int64_t cols, int64_
 // Quantize X (or take codes) -> Xh bf16, and T = X_q A_k.  S == 1 writes T_hi/T_lo into Xh,
 // S > 1 writes fp32 partial sums per K slice.
 // y_zero != null: also clears Y[M][N] (row stride ldy) for a main kernel that adds into it.
+// Clears ws.flags when the workspace has them.
 hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t* Xc, const uint8_t* Xe,
                        int64_t M, const Workspace& ws, float* y_zero, int64_t ldy, hipStream_t s);
 
@@ -93,6 +102,9 @@ int stream_cell_rows_log2(int64_t M);
 hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
                         int variant, hipStream_t s);
 
+hipError_t launch_clear_flags(const Workspace& ws, hipStream_t s);
+
 int prep_slices(const Layer& L, int64_t M, int path);
+int compute_units();               // of the current device
 
 }  // namespace lqer

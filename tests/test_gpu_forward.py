@@ -81,8 +81,11 @@ def test_streaming_kernel_shapes(K, N, k, M, variant):
     h.free()
 
 
-@pytest.mark.parametrize("variant", [1, 3, 4, 7, 8, 11, 12, 13])
-@pytest.mark.parametrize("M,K,N,k", [(16, 512, 512, 8), (300, 272, 200, 0), (513, 1024, 528, 64), (100, 2304, 40, 33)])
+# variant = 100 * mode + tile shape; mode 2 cuts output tiles along K between workgroups wherever the
+# tiles do not fill whole rounds of the chip, mode 1 never does, mode 0 decides by estimate
+@pytest.mark.parametrize("variant", [1, 3, 4, 7, 8, 11, 12, 13, 101, 111, 112, 201, 204, 208, 211, 212, 213])
+@pytest.mark.parametrize("M,K,N,k", [(16, 512, 512, 8), (300, 272, 200, 0), (513, 1024, 528, 64), (100, 2304, 40, 33),
+                                     (700, 4352, 1100, 16)])
 def test_tiled_kernel_shapes(variant, M, K, N, k):
     layer, ch = oracle_layer_small(K, N, k, seed=M + variant)
     h = upload(layer)
@@ -203,6 +206,27 @@ def test_cfg3_prefill_sampled_rows(name):
     rows = np.r_[0, 1, 255, 256, 1023, M - 1, np.random.default_rng(0).integers(0, M, 26)]
     _assert_close(Y[rows], oracle_rows(X[rows], layer))
     assert np.all(np.isfinite(Y))
+    h.free()
+
+
+@pytest.mark.parametrize("variant", [211, 212, 204])
+def test_split_tiles_give_the_same_bits_every_run(variant):
+    # Output tiles cut along K: the pieces are added in K order by one workgroup, whatever the order
+    # in which the others finish, so repeated runs agree bit for bit (and with the oracle within tolerance)
+    import torch
+    from paper_2402_02446_amd import binding
+    layer, ch = oracle_layer_big(4096, 4096, 32, seed=5)
+    h = upload(layer)
+    M = 300
+    Xn = synth.gen_activations(np.random.default_rng(M), M, 4096, ch, 50.0)
+    X = torch.from_numpy(Xn).cuda()
+    first = binding.lqer_linear_forward_ex(h, X, path=2, variant=variant).clone()
+    rows = np.r_[0, 127, 128, M - 1, np.random.default_rng(0).integers(0, M, 12)]
+    _assert_close(first.cpu().numpy()[rows], oracle_rows(Xn[rows], layer))
+    for _ in range(10):
+        Y = torch.full_like(first, 3.0)
+        binding.lqer_linear_forward_ex(h, X, Y=Y, path=2, variant=variant)
+        assert torch.equal(Y, first)
     h.free()
 
 
