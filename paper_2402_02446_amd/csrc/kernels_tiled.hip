@@ -51,7 +51,9 @@ struct TiledArgs {
 };
 
 // MINW = wavefronts per SIMD the register allocation must allow (2 lets two four-wavefront workgroups share a compute unit)
-template <int TM, int TN, int WR, int WC, int NS, int MINW>
+// SPLIT = the workgroup walks a list of pieces (work split); otherwise it computes output tile blockIdx.x
+// whole, as straight-line code (the loop over pieces costs the main product a few percent)
+template <int TM, int TN, int WR, int WC, int NS, int MINW, bool SPLIT>
 __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) {
     constexpr int BM = 32 * TM * WR;
     constexpr int NW = WR * WC;
@@ -77,7 +79,8 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         lin = (xcd < rem) ? xcd * (per + 1) + local : rem * (per + 1) + (xcd - rem) * per + local;
     }
     __shared__ int wait_ok;
-    const int64_t main_chunks = a.KT * 4;
+    const int KT = (int)a.KT;                                  // K tiles and chunks fit 32 bits: scalar compares
+    const int main_chunks = KT * 4;
     const int nb2 = 2 * a.kp16;
     const int tail_chunks = (nb2 + 3) / 4;
     static_assert(NS == 4, "stage and register-set indices below assume rings of four");
@@ -102,25 +105,29 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
   for (;;) {
     // ---- next piece: output tile and K tiles [kt0, kt1) -------------------------------------------
     int64_t tile_lin;
-    int64_t kt0, kt1;
+    int kt0, kt1;
     // The shared K tiles come first: the hand-over between workgroups then overlaps with the whole
     // tiles of other workgroups instead of ending the kernel.
-    if (u < u_end) {
-        const int64_t rt = u / a.KT;
+    if constexpr (!SPLIT) {
+        tile_lin = lin; kt0 = 0; kt1 = KT;
+    } else if (u < u_end) {
+        const int64_t rt = u / KT;
         tile_lin = a.dp_tiles + rt;
-        kt0 = u - rt * a.KT;
-        kt1 = kt0 + (u_end - u);
-        if (kt1 > a.KT) kt1 = a.KT;
+        kt0 = (int)(u - rt * KT);
+        const int64_t left = u_end - u;
+        kt1 = (left < (int64_t)(KT - kt0)) ? kt0 + (int)left : KT;
         u += kt1 - kt0;
     } else if (dp_next < a.dp_tiles) {
-        tile_lin = dp_next; kt0 = 0; kt1 = a.KT;
+        tile_lin = dp_next; kt0 = 0; kt1 = KT;
         dp_next += gridDim.x;
     } else {
         break;
     }
-    const bool owner = (kt0 == 0);                             // this piece stores the tile
-    if (!first_piece) __syncthreads();                         // every wavefront is done with the LDS stages
-    first_piece = false;
+    const bool owner = !SPLIT || (kt0 == 0);                   // this piece stores the tile
+    if constexpr (SPLIT) {
+        if (!first_piece) __syncthreads();                     // every wavefront is done with the LDS stages
+        first_piece = false;
+    }
     // output tiles are walked in bands of group_m tile rows
     int tile_m, tile_n;
     {
@@ -158,30 +165,31 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     struct ESet {                // exponent bytes of one K tile (four chunks) for the same groups
         u32x2 e[TN];
     };
-    auto load_wset = [&](WSet& w, int64_t ch) {
+    auto load_wset = [&](WSet& w, int ch) {
         const int64_t tile = ch >> 2;
-        const int cc = (int)(ch & 3);
+        const int cc = ch & 3;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
             const uint8_t* rec = a.Wt + (tile * a.N32 + group_of(tn)) * kWRecordBytes;   // wave-uniform
             w.c[tn] = *reinterpret_cast<const u32x4*>(rec + cc * 1024 + lane16);
         }
     };
-    auto load_eset = [&](ESet& x, int64_t tile) {
+    auto load_eset = [&](ESet& x, int tile_i) {
+        const int64_t tile = tile_i;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
             const uint8_t* rec = a.Wt + (tile * a.N32 + group_of(tn)) * kWRecordBytes;
             x.e[tn] = *reinterpret_cast<const u32x2*>(rec + kWExpOffset + (lane16 >> 1));
         }
     };
-    auto fetch_x = [&](u32x4 (&st)[LPT], int64_t ch) {
+    auto fetch_x = [&](u32x4 (&st)[LPT], int ch) {
 #pragma unroll
-        for (int j = 0; j < LPT; ++j) st[j] = *reinterpret_cast<const u32x4*>(ld_base + j * ld_stride + ch * 64);
+        for (int j = 0; j < LPT; ++j) st[j] = *reinterpret_cast<const u32x4*>(ld_base + j * ld_stride + (int64_t)ch * 64);
     };
     // Correction chunk tc when the projection kernel left T as S partial sums (it split K over
     // workgroups): add them in slice order and form the bf16 term this cell holds - T_hi for tail
     // columns below kp, T_lo for the next kp, zero behind.
-    auto fetch_t = [&](u32x4 (&st)[LPT], int64_t tc) {
+    auto fetch_t = [&](u32x4 (&st)[LPT], int tc) {
         const int col = (int)tc * 64 + 8 * (tid & 7);
         const bool lo = col >= a.kp;
         const int r0 = lo ? col - a.kp : col;
@@ -209,9 +217,9 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         }
     };
     // any chunk of the activation row: a main one or a correction chunk in either form
-    auto fetch_any = [&](u32x4 (&st)[LPT], int64_t ch) {
-        if (ch < a.KT * 4 || a.S <= 1) fetch_x(st, ch);
-        else fetch_t(st, ch - a.KT * 4);
+    auto fetch_any = [&](u32x4 (&st)[LPT], int ch) {
+        if (ch < main_chunks || a.S <= 1) fetch_x(st, ch);
+        else fetch_t(st, ch - main_chunks);
     };
     auto store_x = [&](const u32x4 (&st)[LPT], int stage) {
 #pragma unroll
@@ -254,7 +262,7 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
 
     // prologue: activations of the piece's first two chunks into stages 0 and 1, and their weights
     // (a K tile is four chunks, so a piece has at least four)
-    const int64_t first_ch = kt0 * 4;
+    const int first_ch = kt0 * 4;
     WSet w0, w1, w2, w3;
     ESet ea, eb;
     {
@@ -275,8 +283,8 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     // Every load below is issued unconditionally, with its index clamped at the end of the range:
     // a load inside a branch would make the compiler's wait counts assume the worst case and the
     // LDS write at the end of the chunk would wait for the newest weights as well.
-    const int64_t last_main = kt1 * 4 - 1, last_tile = kt1 - 1;
-    auto step = [&](const WSet& cur, const ESet& ecur, WSet& fill, ESet& enext, int64_t ch, int c) {
+    const int last_main = kt1 * 4 - 1, last_tile = kt1 - 1;
+    auto step = [&](const WSet& cur, const ESet& ecur, WSet& fill, ESet& enext, int ch, int c) {
         __syncthreads();
         if (ch == first_ch) read_xa(xa, 0, 0);   // later chunks find step 0 already read by the previous one
         u32x4 st[LPT];
@@ -289,7 +297,7 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         mma_chunk(cur, ecur, c);
         store_x(st, (c + 2) & 3);      // stage (ch+2)%4: free since two barriers ago, also for a clamped re-write
     };
-    for (int64_t tile = kt0; tile < kt1; tile += 2) {
+    for (int tile = kt0; tile < kt1; tile += 2) {
         step(w0, ea, w2, eb, tile * 4 + 0, 0);
         step(w1, ea, w3, eb, tile * 4 + 1, 1);
         step(w2, ea, w0, eb, tile * 4 + 2, 2);
@@ -311,7 +319,7 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     // built from them would otherwise be computed once in front of the loop over pieces and
     // occupy registers all through the main product.
     int t_e = t, hh_e = hh, lane_e = lane;
-    asm volatile("" : "+v"(t_e), "+v"(hh_e), "+v"(lane_e));
+    if constexpr (SPLIT) asm volatile("" : "+v"(t_e), "+v"(hh_e), "+v"(lane_e));
     const int my_tail = owner ? tail_chunks : 0;              // the piece that stores the tile adds the correction
     if (my_tail > 0) {
         u32x4 tst[2][LPT];
@@ -361,7 +369,7 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     constexpr int64_t PART_FLOATS = (int64_t)NW * TM * TN * 1024;          // = BM x BN
     typedef unsigned long long u64;
     union Pair { u64 q; float f[2]; };
-    if (!owner) {
+    if (SPLIT && !owner) {
         u64* slot = reinterpret_cast<u64*>(a.Part + (int64_t)lin * PART_FLOATS) + (int64_t)wave * TM * TN * 8 * 64 + lane_e;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
@@ -379,7 +387,7 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         continue;
     }
     // ---- the piece with the start of the tile adds the later pieces, in K order --------------------
-    if (kt1 < a.KT) {
+    if (SPLIT && kt1 < KT) {
         const int64_t rt = tile_lin - a.dp_tiles;
         const int64_t last_wg = ((rt + 1) * a.KT - 1) / a.sk_share;        // workgroup with the tile's last K tile
         for (int64_t w = lin + 1; w <= last_wg; ++w) {
@@ -443,6 +451,7 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
             }
         }
     }
+    if constexpr (!SPLIT) break;
   }   // pieces
 }
 
@@ -452,7 +461,7 @@ struct TileShape { int id, bm, bn, share; double pair, single; };
 // whole-chip TFLOP/s measured on an 8192 x 28672 layer at M = 4096: `pair` with `share` workgroups on
 // every compute unit, `single` with one
 static const TileShape kShapes[] = {
-    {11, 128, 512, 1, 1372.0, 1372.0}, {12, 128, 256, 2, 1280.0, 1000.0}, {4, 128, 128, 2, 1058.0, 900.0},
+    {11, 128, 512, 1, 1372.0, 1372.0}, {12, 128, 256, 2, 1300.0, 1000.0}, {4, 128, 128, 2, 1058.0, 900.0},
 };
 constexpr double kPieceUs = 4.0;       // filling the pipeline and storing the tile, per piece
 constexpr double kHandOverUs = 30.0;   // measured cost of handing accumulators over, per workgroup sharing a compute unit
@@ -499,7 +508,20 @@ static bool split_pays(const TileShape& sh, int64_t tiles, int64_t KT, int cus) 
     return time_split(sh, tiles, KT, cus) < 0.95 * time_whole(sh, tiles, KT, cus);
 }
 
-template <int TM, int TN, int WR, int WC, int NS, int MINW = 1>
+template <typename Kern>
+static hipError_t launch_kernel(Kern kern, bool& attr_set, int lds_bytes, int64_t grid_x, int threads, const TiledArgs& a, hipStream_t s) {
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid_x), dim3(threads), lds_bytes, s, a);
+    return hipGetLastError();
+}
+
+// CAN_SPLIT: the shape also exists in the form that walks a list of pieces
+template <int TM, int TN, int WR, int WC, int NS, int MINW = 1, bool CAN_SPLIT = false>
 static hipError_t launch_tiled_t(TiledArgs a, int64_t M, int mode, int cus, hipStream_t s) {
     constexpr int BM = 32 * TM * WR, BN = 32 * TN * WC;
     constexpr int LDS_BYTES = NS * BM * 128;
@@ -513,23 +535,21 @@ static hipError_t launch_tiled_t(TiledArgs a, int64_t M, int mode, int cus, hipS
     const int64_t slots = (int64_t)cus * MINW;
     // mode 0: split when the estimate says so; 1: never; 2: whenever there is a remainder to split
     bool split = false;
-    if (a.Part != nullptr && (int64_t)BM * BN * 4 * slots <= kTiledPartBytesPerCu * (int64_t)cus && slots <= kTiledFlags) {
+    if (CAN_SPLIT && a.Part != nullptr && (int64_t)BM * BN * 4 * slots <= kTiledPartBytesPerCu * (int64_t)cus && slots <= kTiledFlags) {
         if (mode == 2) split = true;
         else if (mode == 0) split = split_pays(me, tiles, a.KT, cus);
     }
+    if (mode == 2 && !split) return hipErrorInvalidValue;      // asked for, not available
     const Split sp = split ? split_tiles(tiles, a.KT, slots) : whole_tiles(tiles);
     a.dp_tiles = sp.dp_tiles; a.sk_units = sp.sk_units; a.sk_share = sp.sk_share;
-    auto kern = tiled_kernel<TM, TN, WR, WC, NS, MINW>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
+    if constexpr (CAN_SPLIT) {
+        if (sp.sk_units > 0) {
+            static bool attr_split = false;
+            return launch_kernel(tiled_kernel<TM, TN, WR, WC, NS, MINW, true>, attr_split, LDS_BYTES, sp.grid, 64 * WR * WC, a, s);
+        }
     }
-    dim3 grid((unsigned)sp.grid), block(64 * WR * WC);
-    hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, s, a);
-    return hipGetLastError();
+    static bool attr_whole = false;
+    return launch_kernel(tiled_kernel<TM, TN, WR, WC, NS, MINW, false>, attr_whole, LDS_BYTES, tiles, 64 * WR * WC, a, s);
 }
 
 __global__ void clear_flags_kernel(uint32_t* flags, int n) {
@@ -585,11 +605,11 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
     switch (variant) {
         case 1: return launch_tiled_t<4, 4, 2, 2, 4>(a, M, mode, cus, s);      // 256 x 256
         case 3: return launch_tiled_t<2, 4, 2, 2, 4>(a, M, mode, cus, s);      // 128 x 256
-        case 4: return launch_tiled_t<2, 2, 2, 2, 4, 2>(a, M, mode, cus, s);   // 128 x 128, two workgroups per compute unit
+        case 4: return launch_tiled_t<2, 2, 2, 2, 4, 2, true>(a, M, mode, cus, s);   // 128 x 128, two workgroups per compute unit
         case 7: return launch_tiled_t<2, 4, 2, 4, 4>(a, M, mode, cus, s);      // 128 x 512, eight wavefronts
         case 8: return launch_tiled_t<2, 4, 2, 2, 4, 2>(a, M, mode, cus, s);   // 128 x 256, two workgroups per compute unit
-        case 11: return launch_tiled_t<4, 2, 1, 8, 4>(a, M, mode, cus, s);     // 128 x 512, eight wavefronts, each 128 x 64
-        case 12: return launch_tiled_t<4, 2, 1, 4, 4, 2>(a, M, mode, cus, s);  // 128 x 256, four wavefronts each 128 x 64, two workgroups per compute unit
+        case 11: return launch_tiled_t<4, 2, 1, 8, 4, 1, true>(a, M, mode, cus, s);     // 128 x 512, eight wavefronts, each 128 x 64
+        case 12: return launch_tiled_t<4, 2, 1, 4, 4, 2, true>(a, M, mode, cus, s);  // 128 x 256, four wavefronts each 128 x 64, two workgroups per compute unit
         case 13: return launch_tiled_t<4, 2, 1, 4, 4>(a, M, mode, cus, s);     // 128 x 256, four wavefronts each 128 x 64
         default: return hipErrorInvalidValue;
     }
