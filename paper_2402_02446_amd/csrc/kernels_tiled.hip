@@ -7,11 +7,11 @@
 // MFMA (the shape one wavefront per SIMD can keep close to the matrix pipe's peak).  The
 // contraction axis is walked in chunks of 64 = four MFMA steps; lane half hh owns blocks 2hh and
 // 2hh+1 of a chunk for every operand, so block scales never cross lanes.
-//   activations (bf16, exact dequantized X_q, then T_hi | T_lo): global -> registers two chunks
-//       ahead -> a ring of four LDS stages of XOR-swizzled 16-byte cells -> ds_read_b128 operands
-//       shared by the wavefronts of a row;
+//   activations (bf16, exact dequantized X_q, then T_hi | T_lo): global -> registers two or three
+//       chunks ahead -> a ring of four LDS stages of XOR-swizzled 16-byte cells -> ds_read_b128
+//       operands shared by the wavefronts of a row;
 //   weights: each wavefront loads the packed MXINT4 records of its own columns straight into
-//       registers (fully coalesced 16-byte loads), two chunks ahead, into four register sets used
+//       registers (fully coalesced 16-byte loads), three chunks ahead, into four register sets used
 //       by name in turn (a copy between sets would force a wait on the newest load), and expands
 //       them there;
 //   the rank-kp correction is ceil(2 kp / 64) more chunks whose weight operand comes from B_k.
@@ -60,6 +60,8 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     constexpr int STAGE = BM * 128;                // bytes: BM rows x 64 bf16
     constexpr int NT = 64 * NW;
     constexpr int LPT = BM * 8 / NT;               // 16-byte cells each thread moves per chunk
+    // chunks between fetching activations and using them: 3 where the registers allow a second set in flight
+    constexpr int XD = (TM * TN * 16 + LPT * 8 <= 144) ? 3 : 2;
     static_assert((BM * 8) % NT == 0, "loader must divide evenly");
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
@@ -260,53 +262,65 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         }
     };
 
-    // prologue: activations of the piece's first two chunks into stages 0 and 1, and their weights
+    // prologue: activations of the piece's first two chunks into stages 0 and 1, the weights of its
+    // first three, and (XD == 3) the activations of the third in registers
     // (a K tile is four chunks, so a piece has at least four)
     const int first_ch = kt0 * 4;
     WSet w0, w1, w2, w3;
     ESet ea, eb;
+    u32x4 sta[LPT], stb[LPT];                      // activations on their way to LDS (stb: XD == 3 only)
     {
-        u32x4 st[LPT];
-        fetch_x(st, first_ch);
+        fetch_x(sta, first_ch);
         load_eset(ea, kt0);
         load_wset(w0, first_ch);
-        store_x(st, 0);
-        fetch_x(st, first_ch + 1);
+        store_x(sta, 0);
+        fetch_x(sta, first_ch + 1);
         load_wset(w1, first_ch + 1);
-        store_x(st, 1);
+        store_x(sta, 1);
+        if constexpr (XD == 3) fetch_x(sta, first_ch + 2);
+        load_wset(w2, first_ch + 2);
     }
 
     // ---- main product -----------------------------------------------------------------------------
-    // chunk ch: barrier; fetch activations and weights of chunk ch+2; arithmetic of chunk ch;
-    // write the fetched activations into stage (ch+2)%4, which was last read two barriers ago.
+    // chunk ch: barrier; fetch the weights of chunk ch+3 into the register set chunk ch-1 has left,
+    // and the activations of chunk ch+XD; arithmetic of chunk ch; write the activations of chunk ch+2
+    // into stage (ch+2)%4, which was last read two barriers ago.  With XD == 3 those were fetched
+    // during the previous chunk and waited in registers (two sets, used in turn), so both kinds of
+    // load have more than two chunks' time to arrive: measured with the loads taken out, a
+    // distance of two left a fifth of the kernel's time waiting for them.
     // Exponent bytes of the next tile are fetched during the second chunk of a tile.
     // Every load below is issued unconditionally, with its index clamped at the end of the range:
     // a load inside a branch would make the compiler's wait counts assume the worst case and the
     // LDS write at the end of the chunk would wait for the newest weights as well.
     const int last_main = kt1 * 4 - 1, last_tile = kt1 - 1;
-    auto step = [&](const WSet& cur, const ESet& ecur, WSet& fill, ESet& enext, int ch, int c) {
+    auto step = [&](const WSet& cur, const ESet& ecur, WSet& fill, ESet& enext, u32x4 (&st_old)[LPT],
+                    u32x4 (&st_new)[LPT], int ch, int c) {
         __syncthreads();
         if (ch == first_ch) read_xa(xa, 0, 0);   // later chunks find step 0 already read by the previous one
-        u32x4 st[LPT];
-        fetch_x(st, ch + 2 < last_main ? ch + 2 : last_main);
+        fetch_x(st_new, ch + XD < last_main ? ch + XD : last_main);
         // loads retire in order: keep the activation loads ahead of the weight loads, so that the
-        // LDS write at the end of this chunk does not have to wait for the weights of chunk ch+2
+        // LDS write at the end of this chunk does not have to wait for the weights fetched here
         __builtin_amdgcn_sched_barrier(0);
-        load_wset(fill, ch + 2 < last_main ? ch + 2 : last_main);
+        load_wset(fill, ch + 3 < last_main ? ch + 3 : last_main);
         if (c == 1) load_eset(enext, (ch >> 2) + 1 < last_tile ? (ch >> 2) + 1 : last_tile);
         mma_chunk(cur, ecur, c);
-        store_x(st, (c + 2) & 3);      // stage (ch+2)%4: free since two barriers ago, also for a clamped re-write
+        store_x(st_old, (c + 2) & 3);  // stage (ch+2)%4: free since two barriers ago, also for a clamped re-write
     };
+    // XD == 2: one set, fetched and written in the same chunk
+    u32x4 (&st_even_old)[LPT] = sta;
+    u32x4 (&st_even_new)[LPT] = (XD == 3) ? stb : sta;
+    u32x4 (&st_odd_old)[LPT] = (XD == 3) ? stb : sta;
+    u32x4 (&st_odd_new)[LPT] = sta;
     for (int tile = kt0; tile < kt1; tile += 2) {
-        step(w0, ea, w2, eb, tile * 4 + 0, 0);
-        step(w1, ea, w3, eb, tile * 4 + 1, 1);
-        step(w2, ea, w0, eb, tile * 4 + 2, 2);
-        step(w3, ea, w1, eb, tile * 4 + 3, 3);
+        step(w0, ea, w3, eb, st_even_old, st_even_new, tile * 4 + 0, 0);
+        step(w1, ea, w0, eb, st_odd_old, st_odd_new, tile * 4 + 1, 1);
+        step(w2, ea, w1, eb, st_even_old, st_even_new, tile * 4 + 2, 2);
+        step(w3, ea, w2, eb, st_odd_old, st_odd_new, tile * 4 + 3, 3);
         if (tile + 1 < kt1) {
-            step(w0, eb, w2, ea, tile * 4 + 4, 0);
-            step(w1, eb, w3, ea, tile * 4 + 5, 1);
-            step(w2, eb, w0, ea, tile * 4 + 6, 2);
-            step(w3, eb, w1, ea, tile * 4 + 7, 3);
+            step(w0, eb, w3, ea, st_even_old, st_even_new, tile * 4 + 4, 0);
+            step(w1, eb, w0, ea, st_odd_old, st_odd_new, tile * 4 + 5, 1);
+            step(w2, eb, w1, ea, st_even_old, st_even_new, tile * 4 + 6, 2);
+            step(w3, eb, w2, ea, st_odd_old, st_odd_new, tile * 4 + 7, 3);
         }
     }
 
