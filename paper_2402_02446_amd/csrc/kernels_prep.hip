@@ -114,9 +114,9 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
             const bool ok = row_ok && kb < nblk;
             float scale = 0.f;
             float r[16];
+            u32x4 cw = u32x4{0, 0, 0, 0};                     // the block's 16 codes as bytes (FROM_CODES, or CELLS of 16+ rows)
+            uint32_t eb = 0;
             if (FROM_CODES) {
-                u32x4 cw = u32x4{0, 0, 0, 0};
-                uint32_t eb = 0;
                 if (ok) {
                     cw = *reinterpret_cast<const u32x4*>(a.Xc + row * a.K + kb * 16);
                     eb = a.Xe[row * nblk + kb];
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
                     m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(v[i].x), __builtin_fabsf(v[i].y)),
                                                            __builtin_fmaxf(__builtin_fabsf(v[i].z), __builtin_fabsf(v[i].w))));
                 }
-                const uint32_t eb = (f32_bits(m) >> 23) & 0xFFu;
+                eb = (f32_bits(m) >> 23) & 0xFFu;
                 const int sh = 6 - ((int)eb - 127);
                 scale = h_scale(eb);
 #pragma unroll
@@ -153,6 +153,9 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
                         float c = __builtin_rintf(__builtin_amdgcn_ldexpf(in[j], sh));
                         r[4 * i + j] = __builtin_fminf(__builtin_fmaxf(c, -127.0f), 127.0f);
                     }
+                    if constexpr (CELLS)
+                        cw[i] = ((uint32_t)(int)r[4 * i] & 0xFFu) | (((uint32_t)(int)r[4 * i + 1] & 0xFFu) << 8) |
+                                (((uint32_t)(int)r[4 * i + 2] & 0xFFu) << 16) | ((uint32_t)(int)r[4 * i + 3] << 24);
                 }
             }
 #pragma unroll
@@ -162,10 +165,19 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
                     xf[p][h].u[i] = pack_bf16_exact(r[8 * h + 2 * i] * scale, r[8 * h + 2 * i + 1] * scale);
             if (store_x && row_ok) {
                 if (CELLS) {
-                    const int64_t cell = (tile * 16 + q + 4 * p) * 2;
-                    uint16_t* dst = a.Xh + (((cell << a.lr) + row) << 3);
-                    *reinterpret_cast<u32x4*>(dst) = xf[p][0].u;
-                    *reinterpret_cast<u32x4*>(dst + (8 << a.lr)) = xf[p][1].u;
+                    const int64_t blk = tile * 16 + q + 4 * p;
+                    if (a.lr >= 4) {
+                        // 16 token rows and more: MXINT8 as it is, 16 code bytes per (block, row), and the
+                        // exponent bytes [block][row] behind all codes; the main kernel converts
+                        uint8_t* base = reinterpret_cast<uint8_t*>(a.Xh);
+                        const int64_t entry = (blk << a.lr) + row;
+                        *reinterpret_cast<u32x4*>(base + entry * 16) = cw;
+                        base[((a.KT * 16) << (a.lr + 4)) + entry] = (uint8_t)eb;
+                    } else {
+                        uint16_t* dst = a.Xh + ((((blk * 2) << a.lr) + row) << 3);
+                        *reinterpret_cast<u32x4*>(dst) = xf[p][0].u;
+                        *reinterpret_cast<u32x4*>(dst + (8 << a.lr)) = xf[p][1].u;
+                    }
                 } else {
                     uint16_t* dst = a.Xh + row * a.ldxh + (tile * 16 + q + 4 * p) * 16;
                     *reinterpret_cast<u32x4*>(dst) = xf[p][0].u;

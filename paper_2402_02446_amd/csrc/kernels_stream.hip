@@ -36,7 +36,7 @@ constexpr int kStreamTBytes = 9 * 1024;          // 32 rows x (128 + 8) bf16, ro
 
 struct StreamArgs {
     const uint8_t* Wt; const uint8_t* Bt;
-    const uint8_t* Xcell;          // bf16 activations as 16-byte cells [KT*32][R rows]
+    const uint8_t* Xcell;          // activations: bf16 as 16-byte cells [KT*32][R rows] (R = 4), or MXINT8 codes [KT*16][R][16] + exponent bytes [KT*16][R]
     const float* Tpart; int S;
     float* Y; int64_t ldy;
     int64_t M, N, KT, N32;
@@ -60,13 +60,18 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     constexpr int NW = NWC * NWK;
     constexpr int NG = NWC * G;                      // column groups of the workgroup
     constexpr int R = 1 << LR;
-    constexpr int XT = NWK * R * 512;                // bytes of one stage: NWK tiles x R rows of bf16
-    constexpr int NL = XT / 1024;                    // 1 KiB loads per stage
+    constexpr int XT = NWK * R * 512;                // bytes of one stage in LDS: NWK tiles x R rows of bf16
+    // With 16 token rows and more the activations travel as MXINT8 (16 code bytes per block and row,
+    // exponent bytes behind all codes) and become bf16 on the way into LDS: the fill loads are what
+    // this kernel pays for beside the weight stream, and this halves their bytes.
+    constexpr bool X8 = LR >= 4;
+    constexpr int XG = X8 ? XT / 2 : XT;             // bytes of one stage in global memory (codes only)
+    constexpr int NL = XG / 1024;                    // 1 KiB loads per stage
     constexpr int XL = (NL + NW - 1) / NW;           // ... per wavefront
     // array length for the staging registers: an aggregate of exactly 32 dwords is turned into one
     // 1024-bit register tuple by the compiler, which costs over a hundred registers here
     constexpr int XLA = (XL == 8) ? 9 : XL;
-    static_assert(XT % 1024 == 0, "a stage is a whole number of wavefront loads");
+    static_assert(XG % 1024 == 0, "a stage is a whole number of wavefront loads");
     // T_hi | T_lo of up to 32 tokens x 64 ranks, bf16; a row is padded by 16 bytes so that the token rows
     // of one operand read fall into different banks
     constexpr int kTBytes = kStreamTBytes * MB;
@@ -108,34 +113,61 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
         const int64_t tl = tile_raw(it);
         return tl < a.KT ? tl : a.KT - 1;
     };
-    // activation stage of step it: XT bytes of the cell array from (it KSP + kh) XT on, clamped at its end
-    const int64_t x_last = (a.KT * 32 * R * 16) - 1024;            // last whole 1 KiB of the array
+    // activation stage of step it: XG bytes of the cell (or code) array from (it KSP + kh) XG on, clamped at its end
+    const int64_t x_bytes = X8 ? (a.KT * 16 * R * 16) : (a.KT * 32 * R * 16);    // cells, or codes
+    const int64_t x_last = x_bytes - 1024;                         // last whole 1 KiB of the array
+    const int64_t e_last = a.KT * 16 * R - 64;                     // X8: last 64 exponent bytes
     // load x of this wavefront is 1 KiB number j = wave + NW x of the stage (wave-uniform, so the
-    // address arithmetic stays in scalar registers); its lane writes 16 bytes at swz(1024 j + 16 lane)
+    // address arithmetic stays in scalar registers).  As cells its lane writes 16 bytes at
+    // swz(1024 j + 16 lane); as codes its lane holds block (64 j + lane) >> LR of token row
+    // (64 j + lane) % R, which becomes the two cells 2 block and 2 block + 1 of that row.
     auto swz = [](int off) { return off ^ (((off >> (6 + LR)) & 1) << 7); };
     // LDS placement of a cell: the two lane halves of an operand read are 4 cells apart, which is a
     // multiple of the 256-byte bank period; flipping address bit 7 for the upper half's cells moves
     // them to the other half of the banks.
     int st_dst[XL];
 #pragma unroll
-    for (int x = 0; x < XL; ++x) st_dst[x] = swz((wave + NW * x) * 1024 + lane * 16);
+    for (int x = 0; x < XL; ++x) {
+        const int idx = (wave + NW * x) * 64 + lane;
+        st_dst[x] = X8 ? swz(((((idx >> LR) * 2) << LR) + (idx & (R - 1))) << 4) : swz(idx * 16);
+    }
+    struct XStage {
+        u32x4 c[XLA];                                // 16 bytes per load: a cell, or the 16 codes of a block
+        uint32_t e[X8 ? XL : 1];                     // X8: the block's exponent byte
+    };
     const uint8_t* xlane = a.Xcell + lane * 16;
-    auto fetch_x = [&](u32x4 (&st)[XLA], int64_t it) {
-        const int64_t base = (it * KSP + kh) * XT;
+    const uint8_t* elane = a.Xcell + x_bytes + lane;
+    auto fetch_x = [&](XStage& st, int64_t it) {
+        const int64_t base = (it * KSP + kh) * XG;
 #pragma unroll
         for (int x = 0; x < XL; ++x) {
             const int j = wave + NW * x;
             if (j < NL) {
                 int64_t off = base + j * 1024;
                 if (off > x_last) off = x_last;
-                st[x] = *reinterpret_cast<const u32x4*>(xlane + off);
+                st.c[x] = *reinterpret_cast<const u32x4*>(xlane + off);
+                if constexpr (X8) {
+                    int64_t eoff = (base >> 4) + j * 64;
+                    if (eoff > e_last) eoff = e_last;
+                    st.e[x] = elane[eoff];
+                }
             }
         }
     };
-    auto store_x = [&](const u32x4 (&st)[XLA], int buf) {
+    auto store_x = [&](const XStage& st, int buf) {
 #pragma unroll
-        for (int x = 0; x < XL; ++x)
-            if (wave + NW * x < NL) *reinterpret_cast<u32x4*>(xlds + buf * XT + st_dst[x]) = st[x];
+        for (int x = 0; x < XL; ++x) {
+            if (wave + NW * x < NL) {
+                if constexpr (X8) {
+                    Frag f0, f1;
+                    int8x16_to_frags(st.c[x], h_scale(st.e[x]), f0, f1);
+                    *reinterpret_cast<u32x4*>(xlds + buf * XT + st_dst[x]) = f0.u;
+                    *reinterpret_cast<u32x4*>(xlds + buf * XT + st_dst[x] + (16 << LR)) = f1.u;
+                } else {
+                    *reinterpret_cast<u32x4*>(xlds + buf * XT + st_dst[x]) = st.c[x];
+                }
+            }
+        }
     };
     // operand read: cell 32 wk + 8 c + 4 hh + s of the stage, token row trow
     int rd_base[MB];
@@ -240,7 +272,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
         u32x4 wcd[DT][G][4];         // packed codes, chunk by chunk
         u32x2 wex[DT][G];            // exponent bytes
         {
-            u32x4 st[XLA];
+            XStage st;
             fetch_x(st, 0);
 #pragma unroll
             for (int g = 0; g < G; ++g) wex[0][g] = load_we(g, tile_at(0));
@@ -265,7 +297,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
         auto step = [&](u32x4 (&wc_)[G][4], u32x2 (&we_)[G], int64_t it, auto pfx, auto pfw) {
             constexpr bool PFX = decltype(pfx)::value, PFW = decltype(pfw)::value;
             __syncthreads();         // stage it % 2 is complete; the other one is free again
-            u32x4 st[XLA];
+            XStage st;
             u32x2 wen[G];
             const int64_t nt = tile_at(it + DT);
             if constexpr (PFX) fetch_x(st, it + 1);
