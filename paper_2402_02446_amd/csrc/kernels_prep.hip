@@ -30,6 +30,7 @@ struct PrepArgs {
     float* Tpart;
     int64_t tp_rows;       // rows per slice of Tpart
     int lr;                // CELLS: log2 of the token rows per 16-byte cell column
+    bool x8;               // CELLS: store MXINT8 codes [block][row][16] and exponent bytes [block][row] instead of bf16 cells
     float* Yz; int64_t ldy, N;   // Yz != null: extra workgroups clear Y[M][N] for a main kernel that adds into it
     int nslices;                 // K slices = the part of grid.y that does the projection
     uint32_t* flags; int nflags; // flags != null: words the first workgroup clears for the main kernel
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
             if (store_x && row_ok) {
                 if (CELLS) {
                     const int64_t blk = tile * 16 + q + 4 * p;
-                    if (a.lr >= 4) {
+                    if (a.x8) {
                         // 16 token rows and more: MXINT8 as it is, 16 code bytes per (block, row), and the
                         // exponent bytes [block][row] behind all codes; the main kernel converts
                         uint8_t* base = reinterpret_cast<uint8_t*>(a.Xh);
@@ -281,6 +282,7 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     a.Tpart = ws.Tpart;
     a.tp_rows = ws.tp_rows;
     a.lr = ws.lr;
+    a.x8 = ws.x8;
     a.Yz = y_zero; a.ldy = ldy; a.N = L.N;
     a.nslices = ws.S;
     a.flags = ws.flags; a.nflags = ws.flags ? kTiledFlags : 0;

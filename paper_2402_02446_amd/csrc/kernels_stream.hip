@@ -63,8 +63,8 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     constexpr int XT = NWK * R * 512;                // bytes of one stage in LDS: NWK tiles x R rows of bf16
     // With 16 token rows and more the activations travel as MXINT8 (16 code bytes per block and row,
     // exponent bytes behind all codes) and become bf16 on the way into LDS: the fill loads are what
-    // this kernel pays for beside the weight stream, and this halves their bytes.
-    constexpr bool X8 = LR >= 4;
+    // this kernel pays for beside the weight stream, and this halves their bytes (stream_takes_codes()).
+    constexpr bool X8 = LR >= 4 && KSP == 1;         // pairs of workgroups serve layers too small for the halved loads to show
     constexpr int XG = X8 ? XT / 2 : XT;             // bytes of one stage in global memory (codes only)
     constexpr int NL = XG / 1024;                    // 1 KiB loads per stage
     constexpr int XL = (NL + NW - 1) / NW;           // ... per wavefront
@@ -525,6 +525,7 @@ int stream_variant(const Layer& L, int64_t M, int variant) {
     return (M <= 16) ? 11181 : 11241;
 }
 bool stream_variant_adds_into_y(int variant) { return variant / 10000 == 2; }
+bool stream_takes_codes(int variant, int lr) { return lr >= 4 && !stream_variant_adds_into_y(variant); }
 
 hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
                          int variant, hipStream_t s) {

@@ -245,6 +245,7 @@ static Workspace plan_workspace(const Layer& L, int64_t M, int path, void* base)
     ws.S = prep_slices(L, M, path);
     ws.cells = (path == 1);
     ws.lr = stream_cell_rows_log2(M);
+    ws.x8 = false;
     // the tiled kernel reads whole tiles of Xh, 96 to 256 rows high (rows past M hold whatever was there)
     const int64_t xh_rows = (path == 2) ? round_up(M + 95, 256) : (ws.cells ? (int64_t)1 << ws.lr : M);
     const size_t xh_bytes = (size_t)round_up(xh_rows * ws.ldxh * 2, 256);
@@ -299,8 +300,9 @@ static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, co
     if (path == 1 && M > stream_max_rows()) return LQER_ERR_SHAPE;
     if (stages == 0) stages = 3;
     if (!wsp || ((uintptr_t)wsp & 255) != 0) return LQER_ERR_WORKSPACE;
-    const Workspace ws = plan_workspace(L, M, path, wsp);
+    Workspace ws = plan_workspace(L, M, path, wsp);
     if (ws.bytes > ws_bytes) return LQER_ERR_WORKSPACE;
+    if (path == 1) ws.x8 = stream_takes_codes(stream_variant(L, M, variant), ws.lr);
     hipStream_t s = (hipStream_t)stream;
     if (stages & 1) {
         const bool zero_y = (path == 1) && stream_variant_adds_into_y(stream_variant(L, M, variant));

@@ -69,6 +69,7 @@ struct Workspace {
     int64_t tp_rows;     // rows per slice of Tpart (M, or M padded to the tile height for the tiled kernel)
     bool cells;          // streaming kernel: Xh holds 16-byte cells [KT*32][1 << lr token rows]
     int lr;
+    bool x8;             // streaming kernel: the cells hold MXINT8 codes and exponent bytes (set per launch)
     float* Part;         // tiled kernel: accumulators handed from one workgroup to another, or null
     uint32_t* flags;     // tiled kernel: kTiledFlags words, cleared by the projection kernel
     size_t bytes;
@@ -97,6 +98,7 @@ hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* 
 int stream_max_rows();
 int stream_variant(const Layer& L, int64_t M, int variant);      // resolves 0 = automatic
 bool stream_variant_adds_into_y(int variant);                    // Y must be zero before the launch
+bool stream_takes_codes(int variant, int lr);                    // activations as MXINT8 codes + exponent bytes instead of bf16 cells
 int stream_cell_rows_log2(int64_t M);
 // Tiled MFMA (large M) main kernel.
 hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
