@@ -379,8 +379,8 @@ def main():
                          "plain 1 GiB copy that calibrates the byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus must be 1 (the layer's sharding "
-              "over several GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (sharding the layer over "
+              "several GPUs is a design note, not built)", file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():
