@@ -209,6 +209,42 @@ def test_cfg3_prefill_sampled_rows(name):
     h.free()
 
 
+@pytest.mark.parametrize("K,N,k", [(4096, 4096, 32), (4096, 11008, 64), (11008, 4096, 16)])
+def test_cfg5_block_shapes_at_65536_tokens_sampled(K, N, k):
+    # the decoder-block workload (batch 32 x sequence 2048 = 65536 tokens) at its full size, in the launch
+    # configuration the benchmark times: sampled token rows (every tile edge region included) against the
+    # oracle, and the stand-alone quantizer's codes and exponent bytes on the same rows, bit for bit
+    import torch
+    from paper_2402_02446_amd import binding
+    M = 65536
+    d = synth.random_packed_layer(np.random.default_rng(K + k), K, N, k)
+    layer = factors.PackedLayer(**d)
+    h = upload(layer)
+    rng = np.random.default_rng(7)
+    ch = synth.gen_outlier_channels(rng, K, round(0.01 * K))
+    X = torch.empty((M, K), dtype=torch.float32, device="cuda")
+    rows = np.unique(np.r_[0, 127, 128, 255, 256, 32767, 32768, M - 129, M - 128, M - 1, rng.integers(0, M, 12)])
+    keep = {}
+    for r0 in range(0, M, 8192):                             # generated in slabs: the host never holds all of X
+        slab = synth.gen_activations(np.random.default_rng(r0 + 1), 8192, K, ch, 50.0)
+        X[r0:r0 + 8192] = torch.from_numpy(slab).cuda()
+        for r in rows[(rows >= r0) & (rows < r0 + 8192)]:
+            keep[int(r)] = slab[r - r0].copy()
+    Xs = np.stack([keep[int(r)] for r in rows])
+    Y = binding.lqer_linear_forward(h, X)
+    torch.cuda.synchronize()
+    idx = torch.from_numpy(rows).cuda()
+    Ys = Y[idx].cpu().numpy()
+    assert bool(torch.isfinite(Y).all())
+    _assert_close(Ys, oracle_rows(Xs, layer))
+    del Y
+    codes, exps = binding.lqer_quantize_mx(X, 8)
+    torch.cuda.synchronize()
+    oc, oe = mxint.mx_quantize(Xs, 8, axis=-1)
+    assert np.array_equal(codes[idx].cpu().numpy(), oc) and np.array_equal(exps[idx].cpu().numpy(), oe)
+    h.free()
+
+
 def test_split_is_refused_for_shapes_without_it():
     from paper_2402_02446_amd import binding
     layer, ch = oracle_layer_small(1024, 272, 8, seed=2)
