@@ -269,7 +269,10 @@ def run_crossover(rng, steps=10):
 
 
 def time_build_factors(rng):
-    """Wall time of the offline step (lqer_build_factors, host fp64 + upload) per layer shape of cfg5."""
+    """Wall time of the offline step per layer shape of cfg5: lqer_build_factors (host fp64 + upload, from host
+    arrays) and lqer_build_factors_device (device kernels + small host steps, from device tensors; second call,
+    so that one-time module loading is not counted)."""
+    import torch
     from paper_2402_02446_amd import binding, synth
     res = []
     for (K, N) in ((4096, 4096), (4096, 11008), (11008, 4096)):
@@ -278,8 +281,17 @@ def time_build_factors(rng):
         calib = np.stack([synth.gen_activations(rng, 128, K, ch, 50.0)])
         t0 = time.perf_counter()
         layer = binding.lqer_build_factors(W, calib, 32, 1)
-        res.append({"K": K, "N": N, "k": 32, "mode": "L2QER", "seconds": time.perf_counter() - t0})
+        host_s = time.perf_counter() - t0
         layer.free()
+        Wd, cd = torch.from_numpy(W).cuda(), torch.from_numpy(calib).cuda()
+        dev_s = None
+        for _ in range(2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            layer = binding.lqer_build_factors_device(Wd, cd, 32, 1)
+            dev_s = time.perf_counter() - t0
+            layer.free()
+        res.append({"K": K, "N": N, "k": 32, "mode": "L2QER", "seconds": host_s, "seconds_device_path": dev_s})
     return res
 
 
@@ -330,6 +342,9 @@ def pmc_probe(rng, which):
     that show what the streaming and the tiled kernel wait for."""
     import torch
     from paper_2402_02446_amd import binding, synth
+    if which == "build":
+        print(json.dumps({"build_factors_seconds_per_layer": time_build_factors(rng)}))
+        return
     if which == "headline":
         src = torch.ones(PMC_COPY_BYTES // 4, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -374,9 +389,10 @@ def main():
     ap.add_argument("--cases", default="all", choices=["headline", "all", "full"],
                     help="headline: cfg2 only; all: + cfg3, cfg4 and the quantizer; full: + cfg5 and build_factors timing")
     ap.add_argument("--pmc-probe", nargs="?", const="headline", default=None,
-                    choices=["headline", "cfg4_decode", "cfg4_prefill"],
-                    help="run one workload a few times and exit, for rocprofv3 --pmc runs (headline: after a "
-                         "plain 1 GiB copy that calibrates the byte counters)")
+                    choices=["headline", "cfg4_decode", "cfg4_prefill", "build"],
+                    help="run one workload a few times and exit, for rocprofv3 runs (headline: after a "
+                         "plain 1 GiB copy that calibrates the byte counters; build: the offline step per "
+                         "layer shape of cfg5, host and device path, timings printed as JSON)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (sharding the layer over "

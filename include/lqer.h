@@ -97,6 +97,23 @@ int lqer_build_factors(const float* W_host, int64_t K, int64_t N,
                        int k, int mode, const lqer_config* cfg, lqer_layer** out);
 
 /*
+ * The same construction (Sec. 3.1 Eq. 1-2; Sec. 3.2 Eq. 4-5; App. A Eq. 7-8) with W and the
+ * calibration samples already on the device:
+ *   W_dev       [K][N] fp32 row-major, device
+ *   calib_dev   [n_samples][rows_per_sample][K] fp32, device (ignored when mode == 0; may be NULL then)
+ *   hip_stream  the stream the kernels run on
+ * The calibration magnitudes, W_q, S (W - W_q) and the two products of every subspace iteration
+ * are computed by device kernels in fp32 (the magnitudes in fp64, with the bits of the host
+ * path); the l x l steps and the MXINT8 packing of A_k and B_k run on the host.  W_q has the
+ * bits lqer_build_factors gives; A_k and B_k agree with it up to the rotation freedom of the
+ * truncated SVD and fp32 rounding.  Allocates and frees its own device scratch (K N fp32 plus
+ * small buffers).  Synchronous; same status codes.
+ */
+int lqer_build_factors_device(const float* W_dev, int64_t K, int64_t N,
+                              const float* calib_dev, int64_t n_samples, int64_t rows_per_sample,
+                              int k, int mode, const lqer_config* cfg, void* hip_stream, lqer_layer** out);
+
+/*
  * Layer from / to canonical packed bytes (host pointers, layouts above).
  * Import copies; the caller keeps its buffers.  Ac/Ae/Bc/Be may be NULL when k == 0.
  * Wc nibbles must not be -8; We bytes must be <= 247; Ae, Be bytes must be <= 254

@@ -20,7 +20,8 @@ STATUS_NAMES = {0: "LQER_OK", 1: "LQER_ERR_NULL", 2: "LQER_ERR_SHAPE", 3: "LQER_
                 7: "LQER_ERR_NO_CONVERGENCE", 8: "LQER_ERR_VALUE"}
 
 # every symbol include/lqer.h declares
-EXPORTS = ("lqer_status_string", "lqer_quantize_mx", "lqer_build_factors", "lqer_layer_import",
+EXPORTS = ("lqer_status_string", "lqer_quantize_mx", "lqer_build_factors", "lqer_build_factors_device",
+           "lqer_layer_import",
            "lqer_layer_export", "lqer_layer_dims", "lqer_layer_free", "lqer_linear_workspace_bytes",
            "lqer_linear_forward", "lqer_linear_forward_q", "lqer_linear_forward_ex", "lqer_linear_path")
 
@@ -61,6 +62,8 @@ def lib() -> C.CDLL:
     L.lqer_quantize_mx.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp]
     L.lqer_build_factors.restype = i32
     L.lqer_build_factors.argtypes = [vp, i64, i64, vp, i64, i64, i32, i32, vp, C.POINTER(vp)]
+    L.lqer_build_factors_device.restype = i32
+    L.lqer_build_factors_device.argtypes = [vp, i64, i64, vp, i64, i64, i32, i32, vp, vp, C.POINTER(vp)]
     L.lqer_layer_import.restype = i32
     L.lqer_layer_import.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, C.POINTER(vp)]
     L.lqer_layer_export.restype = i32
@@ -181,6 +184,28 @@ def lqer_build_factors(W, calib, k: int, mode: int = 1, cfg=None) -> Layer:
     out = C.c_void_p()
     _check(lib().lqer_build_factors(_np_ptr(W), K, N, _np_ptr(calib), ns, rows, k, mode, c, C.byref(out)),
            "lqer_build_factors")
+    return Layer(out.value)
+
+
+def lqer_build_factors_device(W, calib, k: int, mode: int = 1, cfg=None) -> Layer:
+    """W [K][N] and calib [n_samples][rows][K] are fp32 CUDA tensors; runs on torch's current stream."""
+    import torch
+    if not (W.is_cuda and W.dtype == torch.float32 and (calib is None or (calib.is_cuda and calib.dtype == torch.float32))):
+        raise ValueError("W and calib must be fp32 CUDA tensors")
+    W = W.contiguous()
+    K, N = W.shape
+    if calib is not None:
+        calib = calib.contiguous()
+        ns, rows, kc = calib.shape
+        if kc != K:
+            raise ValueError("calib's last axis must be K")
+        cptr = C.c_void_p(calib.data_ptr())
+    else:
+        ns, rows, cptr = 0, 0, None
+    c = None if cfg is None else C.byref(Config(*cfg))
+    out = C.c_void_p()
+    _check(lib().lqer_build_factors_device(C.c_void_p(W.data_ptr()), K, N, cptr, ns, rows, k, mode, c, _stream(), C.byref(out)),
+           "lqer_build_factors_device")
     return Layer(out.value)
 
 

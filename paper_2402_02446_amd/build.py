@@ -20,7 +20,7 @@ BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "liblqer.so")
 
 SOURCES = ["lqer_host.cpp", "build_factors.cpp", "kernels_quant.hip", "kernels_prep.hip",
-           "kernels_stream.hip", "kernels_tiled.hip"]
+           "kernels_stream.hip", "kernels_tiled.hip", "kernels_build.hip"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

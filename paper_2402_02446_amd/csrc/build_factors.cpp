@@ -12,30 +12,9 @@
 
 #include "lqer_internal.h"
 #include "host_parallel.h"
+#include "build_common.h"
 
 namespace lqer {
-
-// ---- MXINT quantization of one block of 16 doubles (Sec. 2.2 / 4.1 reading, see lqer.h) ---------
-static void mx_block(const double* v, int stride, int bits, int8_t* codes, uint8_t* ebyte) {
-    double amax = 0.0;
-    for (int i = 0; i < 16; ++i) amax = std::max(amax, std::fabs(v[i * stride]));
-    int e = -127;
-    if (amax > 0.0) {
-        int ex;
-        (void)std::frexp(amax, &ex);          // amax = m * 2^ex, m in [0.5, 1)
-        e = ex - 1;
-        if (e < -127) e = -127;
-        if (e > 127) e = 127;
-    }
-    const int lim = (1 << (bits - 1)) - 1;
-    for (int i = 0; i < 16; ++i) {
-        double r = std::nearbyint(std::ldexp(v[i * stride], (bits - 2) - e));   // ties to even
-        if (r > lim) r = lim;
-        if (r < -lim) r = -lim;
-        codes[i] = (int8_t)r;
-    }
-    *ebyte = (uint8_t)(e + 127);
-}
 
 // ---- small dense helpers ------------------------------------------------------------------------
 // Orthonormalize the l columns of Y (rows x l, row-major) with two passes of modified Gram-Schmidt.
@@ -91,62 +70,6 @@ static void gemm_tn(const std::vector<double>& G, int64_t K, int64_t N, const st
         }
     });
 }
-
-// Symmetric eigen-decomposition by cyclic Jacobi: A (l x l, destroyed) -> eigenvalues d, vectors V (columns).
-static bool jacobi_eig(std::vector<double>& A, int l, std::vector<double>& d, std::vector<double>& V) {
-    V.assign((size_t)l * l, 0.0);
-    for (int i = 0; i < l; ++i) V[i * l + i] = 1.0;
-    for (int sweep = 0; sweep < 100; ++sweep) {
-        double off = 0.0, diag = 0.0;
-        for (int i = 0; i < l; ++i)
-            for (int j = 0; j < l; ++j) (i == j ? diag : off) += A[i * l + j] * A[i * l + j];
-        if (off <= 1e-30 * diag || off == 0.0) {
-            d.resize(l);
-            for (int i = 0; i < l; ++i) d[i] = A[i * l + i];
-            return true;
-        }
-        for (int p = 0; p < l - 1; ++p)
-            for (int q = p + 1; q < l; ++q) {
-                const double apq = A[p * l + q];
-                if (apq == 0.0) continue;
-                const double theta = (A[q * l + q] - A[p * l + p]) / (2.0 * apq);
-                const double t = (theta >= 0 ? 1.0 : -1.0) / (std::fabs(theta) + std::sqrt(theta * theta + 1.0));
-                const double c = 1.0 / std::sqrt(t * t + 1.0), s = t * c;
-                for (int i = 0; i < l; ++i) {
-                    const double aip = A[i * l + p], aiq = A[i * l + q];
-                    A[i * l + p] = c * aip - s * aiq;
-                    A[i * l + q] = s * aip + c * aiq;
-                }
-                for (int i = 0; i < l; ++i) {
-                    const double api = A[p * l + i], aqi = A[q * l + i];
-                    A[p * l + i] = c * api - s * aqi;
-                    A[q * l + i] = s * api + c * aqi;
-                }
-                for (int i = 0; i < l; ++i) {
-                    const double vip = V[i * l + p], viq = V[i * l + q];
-                    V[i * l + p] = c * vip - s * viq;
-                    V[i * l + q] = s * vip + c * viq;
-                }
-            }
-    }
-    return false;
-}
-
-// splitmix64 -> standard normal (Box-Muller); a fixed stream so the build is reproducible.
-struct Rng {
-    uint64_t s;
-    uint64_t next() {
-        uint64_t z = (s += 0x9E3779B97F4A7C15ull);
-        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-        return z ^ (z >> 31);
-    }
-    double uniform() { return ((next() >> 11) + 0.5) * (1.0 / 9007199254740992.0); }
-    double normal() {
-        const double u = uniform(), v = uniform();
-        return std::sqrt(-2.0 * std::log(u)) * std::cos(6.283185307179586 * v);
-    }
-};
 
 // Leading-k split of G = S E (K x N): A = S^-1 U_k (K x k), B = Sigma_k V_k^T (k x N).
 static int truncated_split(const std::vector<double>& G, int64_t K, int64_t N, const std::vector<double>& s,
@@ -210,6 +133,54 @@ static int truncated_split(const std::vector<double>& G, int64_t K, int64_t N, c
     return LQER_OK;
 }
 
+// A (K x k) and B (k x N) -> MXINT8 bytes in the canonical layouts, then the layer handle.
+int pack_factors_and_import(int64_t K, int64_t N, int k, const std::vector<uint8_t>& Wc, const std::vector<uint8_t>& We,
+                            const std::vector<double>& A, const std::vector<double>& B, lqer_layer** out) {
+    const int kp = (k + 15) / 16 * 16;
+    const int64_t nblk = K / 16;
+    std::vector<int8_t> Ac, Bc;
+    std::vector<uint8_t> Ae, Be;
+    if (k > 0) {
+        // A_k: K x k -> MXINT8 blocks down K, stored [kp][K]
+        Ac.assign((size_t)kp * K, 0);
+        Ae.assign((size_t)kp * nblk, 0);
+        for (int r = 0; r < k; ++r)
+            for (int64_t kb = 0; kb < nblk; ++kb)
+                mx_block(&A[(size_t)kb * 16 * k + r], k, 8, &Ac[(size_t)r * K + kb * 16], &Ae[(size_t)r * nblk + kb]);
+        // B_k: k x N (zero padded to kp) -> MXINT8 blocks down k, stored [N][kp]
+        Bc.assign((size_t)N * kp, 0);
+        Be.assign((size_t)N * (kp / 16), 0);
+        std::vector<double> colb(16);
+        for (int64_t n = 0; n < N; ++n)
+            for (int rb = 0; rb < kp / 16; ++rb) {
+                for (int i = 0; i < 16; ++i) {
+                    const int r = rb * 16 + i;
+                    colb[i] = (r < k) ? B[(size_t)r * N + n] : 0.0;
+                }
+                mx_block(colb.data(), 1, 8, &Bc[(size_t)n * kp + rb * 16], &Be[(size_t)n * (kp / 16) + rb]);
+            }
+    }
+    return lqer_layer_import(K, N, k, Wc.data(), We.data(), k > 0 ? Ac.data() : nullptr,
+                             k > 0 ? Ae.data() : nullptr, k > 0 ? Bc.data() : nullptr,
+                             k > 0 ? Be.data() : nullptr, out);
+}
+
+// S of App. A from the per-channel magnitudes abar (maximum over samples of the mean |x|): geometric-mean normalisation.
+int scale_from_magnitudes(const std::vector<double>& abar, std::vector<double>& s) {
+    const int64_t K = (int64_t)abar.size();
+    double lo = abar[0], hi = abar[0];
+    for (int64_t c = 0; c < K; ++c) {
+        if (!(abar[c] > 0.0) || !std::isfinite(abar[c])) return LQER_ERR_SINGULAR_SCALE;
+        lo = std::min(lo, abar[c]);
+        hi = std::max(hi, abar[c]);
+    }
+    const double norm = std::sqrt(lo * hi);
+    if (!(norm > 0.0) || !std::isfinite(norm)) return LQER_ERR_SINGULAR_SCALE;
+    s.resize((size_t)K);
+    for (int64_t c = 0; c < K; ++c) s[c] = abar[c] / norm;
+    return LQER_OK;
+}
+
 }  // namespace lqer
 
 using namespace lqer;
@@ -242,15 +213,8 @@ extern "C" int lqer_build_factors(const float* W_host, int64_t K, int64_t N, con
             }
             for (int64_t c = 0; c < K; ++c) abar[c] = std::max(abar[c], a[c] / (double)rows_per_sample);
         }
-        double lo = abar[0], hi = abar[0];
-        for (int64_t c = 0; c < K; ++c) {
-            if (!(abar[c] > 0.0) || !std::isfinite(abar[c])) return LQER_ERR_SINGULAR_SCALE;
-            lo = std::min(lo, abar[c]);
-            hi = std::max(hi, abar[c]);
-        }
-        const double norm = std::sqrt(lo * hi);
-        if (!(norm > 0.0) || !std::isfinite(norm)) return LQER_ERR_SINGULAR_SCALE;
-        for (int64_t c = 0; c < K; ++c) s[c] = abar[c] / norm;
+        const int st = scale_from_magnitudes(abar, s);
+        if (st != LQER_OK) return st;
     }
 
     // W_q and G = S (W - W_q)
@@ -279,34 +243,12 @@ extern "C" int lqer_build_factors(const float* W_host, int64_t K, int64_t N, con
         }
     }, 8);
 
-    std::vector<int8_t> Ac, Bc;
-    std::vector<uint8_t> Ae, Be;
+    std::vector<double> A, B;
     if (k > 0) {
-        std::vector<double> A, B;
         const int st = truncated_split(G, K, N, s, k, A, B);
         if (st != LQER_OK) return st;
         G.clear();
         G.shrink_to_fit();
-        // A_k: K x k -> MXINT8 blocks down K, stored [kp][K]
-        Ac.assign((size_t)kp * K, 0);
-        Ae.assign((size_t)kp * nblk, 0);
-        for (int r = 0; r < k; ++r)
-            for (int64_t kb = 0; kb < nblk; ++kb)
-                mx_block(&A[(size_t)kb * 16 * k + r], k, 8, &Ac[(size_t)r * K + kb * 16], &Ae[(size_t)r * nblk + kb]);
-        // B_k: k x N (zero padded to kp) -> MXINT8 blocks down k, stored [N][kp]
-        Bc.assign((size_t)N * kp, 0);
-        Be.assign((size_t)N * (kp / 16), 0);
-        std::vector<double> colb(16);
-        for (int64_t n = 0; n < N; ++n)
-            for (int rb = 0; rb < kp / 16; ++rb) {
-                for (int i = 0; i < 16; ++i) {
-                    const int r = rb * 16 + i;
-                    colb[i] = (r < k) ? B[(size_t)r * N + n] : 0.0;
-                }
-                mx_block(colb.data(), 1, 8, &Bc[(size_t)n * kp + rb * 16], &Be[(size_t)n * (kp / 16) + rb]);
-            }
     }
-    return lqer_layer_import(K, N, k, Wc.data(), We.data(), k > 0 ? Ac.data() : nullptr,
-                             k > 0 ? Ae.data() : nullptr, k > 0 ? Bc.data() : nullptr,
-                             k > 0 ? Be.data() : nullptr, out);
+    return pack_factors_and_import(K, N, k, Wc, We, A, B, out);
 }

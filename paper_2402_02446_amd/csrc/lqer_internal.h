@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <vector>
 #include "lqer.h"
 
 namespace lqer {
@@ -105,6 +106,11 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
                         int variant, hipStream_t s);
 
 hipError_t launch_clear_flags(const Workspace& ws, hipStream_t s);
+
+// ---- offline construction, shared host steps (build_factors.cpp) ---------------------------
+int pack_factors_and_import(int64_t K, int64_t N, int k, const std::vector<uint8_t>& Wc, const std::vector<uint8_t>& We,
+                            const std::vector<double>& A, const std::vector<double>& B, lqer_layer** out);
+int scale_from_magnitudes(const std::vector<double>& abar, std::vector<double>& s);
 
 int prep_slices(const Layer& L, int64_t M, int path);
 int compute_units();               // of the current device

@@ -80,3 +80,88 @@ def test_build_factors_full_rank_and_zero_rank():
     h0 = binding.lqer_build_factors(W, None, 0, mode=0)
     assert h0.kp == 0
     h0.free()
+
+
+def _residuals(W, calib, k, mode, ref, out, kp):
+    """Weighted residual norms of a built layer, of the oracle's layer, and of the unquantized optimum."""
+    K, N = W.shape
+    W_hat, A_ref, B_ref = factors.dequantize_layer(ref)
+    got = factors.PackedLayer(K=K, N=N, k=k, kp=kp, **out)
+    _, A_got, B_got = factors.dequantize_layer(got)
+    s = factors.calibrate_scale(calib) if mode == 1 else np.ones(K)
+    E = W.astype(np.float64) - W_hat
+    r_ref = np.linalg.norm(s[:, None] * (E - A_ref @ B_ref))
+    r_got = np.linalg.norm(s[:, None] * (E - A_got @ B_got))
+    sig = np.linalg.svd(s[:, None] * E, compute_uv=False)
+    return r_got, r_ref, np.sqrt((sig[k:] ** 2).sum())
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_build_factors_device_against_oracle(mode):
+    # the construction with its heavy steps on the device (Sec. 3.1 Eq. 1-2, Sec. 3.2 Eq. 4-5, App. A):
+    # W_q bit for bit; for the factors what is unique - the weighted residual against the Eckart-Young optimum
+    import torch
+    from paper_2402_02446_amd import binding
+    wl = synth.WORKLOADS["cfg1"]
+    d = synth.draw(wl)
+    ref = factors.build_factors(d.W, d.calib, wl.k, mode)
+    h = binding.lqer_build_factors_device(torch.from_numpy(d.W).cuda(), torch.from_numpy(d.calib).cuda(), wl.k, mode)
+    out = binding.lqer_layer_export(h)
+    assert np.array_equal(out["Wc"], ref.Wc) and np.array_equal(out["We"], ref.We)
+    r_got, r_ref, opt = _residuals(d.W, d.calib, wl.k, mode, ref, out, h.kp)
+    assert r_got <= opt * 1.01 and abs(r_got - r_ref) <= 0.01 * r_ref
+    h.free()
+
+
+@pytest.mark.parametrize("K,N,k", [(1024, 272, 32), (272, 1040, 33), (2048, 2048, 64)])
+def test_build_factors_device_shapes(K, N, k):
+    # ragged sizes and the largest rank; outlier channels as in the LLaMA-shaped workloads
+    import torch
+    from paper_2402_02446_amd import binding
+    rng = np.random.default_rng(K + k)
+    W = synth.gen_weight(rng, K, N)
+    ch = synth.gen_outlier_channels(rng, K, max(1, round(0.01 * K)))
+    calib = np.stack([synth.gen_activations(rng, 64, K, ch, 50.0) for _ in range(2)])
+    ref = factors.build_factors(W, calib, k, 1)
+    h = binding.lqer_build_factors_device(torch.from_numpy(W).cuda(), torch.from_numpy(calib).cuda(), k, 1)
+    out = binding.lqer_layer_export(h)
+    assert np.array_equal(out["Wc"], ref.Wc) and np.array_equal(out["We"], ref.We)
+    r_got, r_ref, opt = _residuals(W, calib, k, 1, ref, out, h.kp)
+    assert r_got <= opt * 1.01 and abs(r_got - r_ref) <= 0.01 * r_ref
+    # and the host construction of the library lands in the same place
+    h2 = binding.lqer_build_factors(W, calib, k, 1)
+    r_host, _, _ = _residuals(W, calib, k, 1, ref, binding.lqer_layer_export(h2), h2.kp)
+    assert abs(r_got - r_host) <= 0.005 * r_host
+    h.free()
+    h2.free()
+
+
+def test_build_factors_device_full_rank_zero_rank_and_errors():
+    import torch
+    from paper_2402_02446_amd import binding
+    rng = np.random.default_rng(3)
+    W = synth.gen_weight(rng, 64, 48)
+    Wd = torch.from_numpy(W).cuda()
+    h = binding.lqer_build_factors_device(Wd, None, 48, mode=0)
+    out = binding.lqer_layer_export(h)
+    got = factors.PackedLayer(K=64, N=48, k=48, kp=48, **out)
+    W_hat, A, B = factors.dequantize_layer(got)
+    base = np.linalg.norm(W - W_hat)
+    assert np.linalg.norm(W - W_hat - A @ B) < 0.05 * base      # k = min(K, N) recovers W up to the factors' 8 bits
+    h.free()
+    h0 = binding.lqer_build_factors_device(Wd, None, 0, mode=0)
+    assert h0.kp == 0
+    h0.free()
+    bad = Wd.clone()
+    bad[5, 7] = float("inf")
+    with pytest.raises(binding.LqerError) as e:
+        binding.lqer_build_factors_device(bad, None, 8, mode=0)
+    assert e.value.status == 8
+    calib = torch.ones((1, 8, 64), device="cuda")
+    calib[:, :, 3] = 0.0                                          # a channel that never fires: S is singular
+    with pytest.raises(binding.LqerError) as e:
+        binding.lqer_build_factors_device(Wd, calib, 8, mode=1)
+    assert e.value.status == 4
+    with pytest.raises(binding.LqerError) as e:
+        binding.lqer_build_factors_device(Wd, None, 49, mode=0)  # k > min(K, N)
+    assert e.value.status == 2
