@@ -139,6 +139,11 @@ int lqer_layer_free(lqer_layer* layer);
  * Calls on different streams need distinct workspaces.  The library allocates nothing here,
  * uses only the given stream and no host synchronisation, so the call can be captured in a HIP
  * graph.  Results are the same bits on every run.
+ * For large M the workspace also holds one slot of 256 KiB per compute unit: when the output
+ * tiles do not fill whole rounds of the chip, workgroups cut the remaining tiles along K, hand
+ * their partial sums over through these slots and the receiving workgroup polls a flag.  The
+ * poll is bounded (about a second): the kernel always ends, and a tile whose partner never
+ * arrived is stored as NaN, never as a wrong number.
  * lqer_linear_forward_q takes activations that are already quantized
  * (Xc int8 [M][K], Xe uint8 [M][K/16], canonical, device).
  */
