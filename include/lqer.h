@@ -71,7 +71,7 @@ const char* lqer_status_string(int status);
  * the contiguous axis of a row-major fp32 matrix.
  *   x_dev      [rows][ld] fp32, device; only the first `cols` of each row are read
  *   cols       multiple of 16;  ld >= cols
- *   elem_bits  8 (codes_dev = int8 [rows][cols]) or 4 (codes_dev = uint8 [rows][cols/2], canonical nibbles)
+ *   elem_bits  8 or 6 (codes_dev = int8 [rows][cols]) or 4 (codes_dev = uint8 [rows][cols/2], canonical nibbles)
  *   exp_bits   8
  *   exps_dev   uint8 [rows][cols/16]
  * rows == 0 is a no-op.  Caller owns all buffers.
@@ -127,6 +127,13 @@ int lqer_layer_import(int64_t K, int64_t N, int k,
 int lqer_layer_export(const lqer_layer* layer, uint8_t* Wc, uint8_t* We,
                       int8_t* Ac, uint8_t* Ae, int8_t* Bc, uint8_t* Be);
 int lqer_layer_dims(const lqer_layer* layer, int64_t* K, int64_t* N, int* k, int* kp);
+/*
+ * Width of the activation codes the forward pass quantizes X to: 8 (W4A8, the default) or 6
+ * (the W4A6 setup of Table 2; Sec. 4.1 keeps the 8-bit shared exponent for activations).
+ * lqer_linear_forward_q then expects codes of that width (int8 storage either way).
+ * With 6 bits, block maxima of 2^125 and above are outside the supported range.
+ */
+int lqer_layer_set_activation_bits(lqer_layer* layer, int bits);
 int lqer_layer_free(lqer_layer* layer);
 
 /*

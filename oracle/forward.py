@@ -18,23 +18,24 @@ from . import mxint
 from .factors import PackedLayer, dequantize_layer, W_BITS, H_BITS
 
 
-def quantize_activations(X):
-    """(codes[M][K] int8, exps[M][K/16] uint8) for activations X[M][K]."""
-    return mxint.mx_quantize(X, H_BITS, axis=-1)
+def quantize_activations(X, act_bits: int = H_BITS):
+    """(codes[M][K] int8, exps[M][K/16] uint8) for activations X[M][K]; act_bits = 6 is the
+    W4A6 setup of Table 2 (8-bit shared exponents for activations either way, Sec. 4.1)."""
+    return mxint.mx_quantize(X, act_bits, axis=-1)
 
 
-def forward_q(Xc, Xe, layer: PackedLayer) -> np.ndarray:
+def forward_q(Xc, Xe, layer: PackedLayer, act_bits: int = H_BITS) -> np.ndarray:
     """Y from already-quantized activations, fp64."""
-    X_hat = mxint.mx_dequantize(Xc, Xe, H_BITS, axis=-1)
+    X_hat = mxint.mx_dequantize(Xc, Xe, act_bits, axis=-1)
     W_hat, A_hat, B_hat = dequantize_layer(layer)
     T = X_hat @ A_hat
     return X_hat @ W_hat + T @ B_hat
 
 
-def forward(X, layer: PackedLayer) -> np.ndarray:
+def forward(X, layer: PackedLayer, act_bits: int = H_BITS) -> np.ndarray:
     """Y = X_q W_q + (X_q A_k) B_k for fp32 activations X[M][K], fp64 result."""
-    Xc, Xe = quantize_activations(X)
-    return forward_q(Xc, Xe, layer)
+    Xc, Xe = quantize_activations(X, act_bits)
+    return forward_q(Xc, Xe, layer, act_bits)
 
 
 def forward_int_exact(Xc, Xe, layer: PackedLayer) -> np.ndarray:

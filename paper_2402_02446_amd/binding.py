@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "LQER_OK", 1: "LQER_ERR_NULL", 2: "LQER_ERR_SHAPE", 3: "LQER_
 # every symbol include/lqer.h declares
 EXPORTS = ("lqer_status_string", "lqer_quantize_mx", "lqer_build_factors", "lqer_build_factors_device",
            "lqer_layer_import",
-           "lqer_layer_export", "lqer_layer_dims", "lqer_layer_free", "lqer_linear_workspace_bytes",
+           "lqer_layer_export", "lqer_layer_dims", "lqer_layer_set_activation_bits", "lqer_layer_free", "lqer_linear_workspace_bytes",
            "lqer_linear_forward", "lqer_linear_forward_q", "lqer_linear_forward_ex", "lqer_linear_path")
 
 
@@ -70,6 +70,8 @@ def lib() -> C.CDLL:
     L.lqer_layer_export.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     L.lqer_layer_dims.restype = i32
     L.lqer_layer_dims.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
+    L.lqer_layer_set_activation_bits.restype = i32
+    L.lqer_layer_set_activation_bits.argtypes = [vp, i32]
     L.lqer_layer_free.restype = i32
     L.lqer_layer_free.argtypes = [vp]
     L.lqer_linear_workspace_bytes.restype = sz
@@ -109,8 +111,8 @@ def lqer_quantize_mx(x, elem_bits: int = 8, exp_bits: int = 8):
     import torch
     rows, cols = x.shape
     ld = x.stride(0) if rows > 1 else max(cols, x.stride(0))
-    code_cols = cols if elem_bits == 8 else cols // 2
-    codes = torch.empty((rows, code_cols), dtype=torch.int8 if elem_bits == 8 else torch.uint8, device=x.device)
+    code_cols = cols if elem_bits >= 6 else cols // 2
+    codes = torch.empty((rows, code_cols), dtype=torch.int8 if elem_bits >= 6 else torch.uint8, device=x.device)
     exps = torch.empty((rows, cols // 16), dtype=torch.uint8, device=x.device)
     _check(lib().lqer_quantize_mx(C.c_void_p(x.data_ptr()), rows, cols, ld, elem_bits, exp_bits,
                                   C.c_void_p(codes.data_ptr()), C.c_void_p(exps.data_ptr()), _stream()),
@@ -128,6 +130,9 @@ class Layer:
                "lqer_layer_dims")
         self.K, self.N, self.k, self.kp = K.value, N.value, k.value, kp.value
         self._ws = None
+
+    def set_activation_bits(self, bits: int):
+        _check(lib().lqer_layer_set_activation_bits(self.handle, int(bits)), "lqer_layer_set_activation_bits")
 
     def free(self):
         if self.handle:

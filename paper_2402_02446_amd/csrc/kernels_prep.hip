@@ -30,6 +30,7 @@ struct PrepArgs {
     float* Tpart;
     int64_t tp_rows;       // rows per slice of Tpart
     int lr;                // CELLS: log2 of the token rows per 16-byte cell column
+    int act_frac;          // fraction bits of the activation codes: 6 (MXINT8) or 4 (MXINT6)
     bool x8;               // CELLS: store MXINT8 codes [block][row][16] and exponent bytes [block][row] instead of bf16 cells
     float* Yz; int64_t ldy, N;   // Yz != null: extra workgroups clear Y[M][N] for a main kernel that adds into it
     int nslices;                 // K slices = the part of grid.y that does the projection
@@ -122,7 +123,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
                     cw = *reinterpret_cast<const u32x4*>(a.Xc + row * a.K + kb * 16);
                     eb = a.Xe[row * nblk + kb];
                 }
-                scale = h_scale(eb);
+                scale = x_scale(eb, a.act_frac);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t w = cw[i];
@@ -144,15 +145,16 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
                                                            __builtin_fmaxf(__builtin_fabsf(v[i].z), __builtin_fabsf(v[i].w))));
                 }
                 eb = (f32_bits(m) >> 23) & 0xFFu;
-                const int sh = 6 - ((int)eb - 127);
-                scale = h_scale(eb);
+                const int sh = a.act_frac - ((int)eb - 127);
+                const float lim = (float)((2 << a.act_frac) - 1);             // 127 or 31
+                scale = x_scale(eb, a.act_frac);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float in[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         float c = __builtin_rintf(__builtin_amdgcn_ldexpf(in[j], sh));
-                        r[4 * i + j] = __builtin_fminf(__builtin_fmaxf(c, -127.0f), 127.0f);
+                        r[4 * i + j] = __builtin_fminf(__builtin_fmaxf(c, -lim), lim);
                     }
                     if constexpr (CELLS)
                         cw[i] = ((uint32_t)(int)r[4 * i] & 0xFFu) | (((uint32_t)(int)r[4 * i + 1] & 0xFFu) << 8) |
@@ -173,7 +175,9 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
                         uint8_t* base = reinterpret_cast<uint8_t*>(a.Xh);
                         const int64_t entry = (blk << a.lr) + row;
                         *reinterpret_cast<u32x4*>(base + entry * 16) = cw;
-                        base[((a.KT * 16) << (a.lr + 4)) + entry] = (uint8_t)eb;
+                        // the main kernel scales codes by 2^(byte - 127 - 6): narrower codes carry the difference in the byte
+                        const uint32_t ebs = eb + (6 - a.act_frac);
+                        base[((a.KT * 16) << (a.lr + 4)) + entry] = (uint8_t)(ebs < 254u ? ebs : 254u);
                     } else {
                         uint16_t* dst = a.Xh + ((((blk * 2) << a.lr) + row) << 3);
                         *reinterpret_cast<u32x4*>(dst) = xf[p][0].u;
@@ -283,6 +287,7 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     a.tp_rows = ws.tp_rows;
     a.lr = ws.lr;
     a.x8 = ws.x8;
+    a.act_frac = L.act_bits - 2;
     a.Yz = y_zero; a.ldy = ldy; a.N = L.N;
     a.nslices = ws.S;
     a.flags = ws.flags; a.nflags = ws.flags ? kTiledFlags : 0;

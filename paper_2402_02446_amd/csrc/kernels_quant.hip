@@ -1,6 +1,6 @@
 // MX block quantizer (Sec. 2.2; block [1,16] of Sec. 4.1): fp32 rows -> MXINT codes + exponent bytes.
 //
-// HBM-bound: 4 B read and 1 + 1/16 B written per element (8-bit codes).  Each lane loads one
+// HBM-bound: 4 B read and 1 + 1/16 B written per element (8- and 6-bit codes, one byte each).  Each lane loads one
 // float4, so a wavefront load is one contiguous 1 KiB; the four lanes of a quad hold one
 // 16-element block and agree on its maximum with two DPP quad permutes.  The shared exponent is
 // the biased exponent field of that fp32 maximum.
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void quantize_mx_kernel(const float* __restric
             const int c2 = mx_code<BITS>(v[u].z, e), c3 = mx_code<BITS>(v[u].w, e);
             if (i < total) {
                 const int64_t elem = row[u] * cols4 * 4 + 4 * c4[u];
-                if (BITS == 8) {
+                if (BITS >= 6) {
                     const uint32_t w = (uint32_t)(c0 & 0xFF) | ((uint32_t)(c1 & 0xFF) << 8) |
                                        ((uint32_t)(c2 & 0xFF) << 16) | ((uint32_t)(c3 & 0xFF) << 24);
                     *reinterpret_cast<uint32_t*>(codes + elem) = w;
@@ -82,6 +82,9 @@ hipError_t launch_quantize_mx(const float* x, int64_t rows, int64_t cols, int64_
     dim3 grid((unsigned)blocks), block(256);
     if (bits == 8)
         hipLaunchKernelGGL((quantize_mx_kernel<8, UNROLL>), grid, block, 0, s, x, rows, cols4, ld,
+                           (uint8_t*)codes, exps);
+    else if (bits == 6)
+        hipLaunchKernelGGL((quantize_mx_kernel<6, UNROLL>), grid, block, 0, s, x, rows, cols4, ld,
                            (uint8_t*)codes, exps);
     else
         hipLaunchKernelGGL((quantize_mx_kernel<4, UNROLL>), grid, block, 0, s, x, rows, cols4, ld,

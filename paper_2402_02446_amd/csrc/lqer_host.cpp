@@ -341,7 +341,7 @@ const char* lqer_status_string(int status) {
 
 int lqer_quantize_mx(const float* x_dev, int64_t rows, int64_t cols, int64_t ld, int elem_bits,
                      int exp_bits, void* codes_dev, uint8_t* exps_dev, void* hip_stream) {
-    if (elem_bits != 4 && elem_bits != 8) return LQER_ERR_UNSUPPORTED;
+    if (elem_bits != 4 && elem_bits != 6 && elem_bits != 8) return LQER_ERR_UNSUPPORTED;
     if (exp_bits != 8) return LQER_ERR_UNSUPPORTED;
     if (rows < 0 || cols < 0 || (cols & 15) != 0 || ld < cols) return LQER_ERR_SHAPE;
     if (rows == 0 || cols == 0) return LQER_OK;
@@ -369,6 +369,7 @@ int lqer_layer_import(int64_t K, int64_t N, int k, const uint8_t* Wc, const uint
     L.KT = (K + kTileK - 1) / kTileK;
     L.N32 = (N + 31) / 32;
     L.kp16 = kp / 16;
+    L.act_bits = 8;
     L.Wt = L.At = L.Bt = nullptr;
     if (hipGetDevice(&L.device) != hipSuccess) { delete h; return LQER_ERR_HIP; }
     int st;
@@ -427,6 +428,13 @@ int lqer_layer_dims(const lqer_layer* layer, int64_t* K, int64_t* N, int* k, int
     if (N) *N = layer->L.N;
     if (k) *k = layer->L.k;
     if (kp) *kp = layer->L.kp;
+    return LQER_OK;
+}
+
+int lqer_layer_set_activation_bits(lqer_layer* layer, int bits) {
+    if (!layer) return LQER_ERR_NULL;
+    if (bits != 8 && bits != 6) return LQER_ERR_UNSUPPORTED;
+    layer->L.act_bits = bits;
     return LQER_OK;
 }
 

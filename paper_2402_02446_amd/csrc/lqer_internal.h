@@ -56,6 +56,7 @@ struct Layer {
     int64_t N32;       // column groups of 32
     int kp16;          // rank groups (= MXINT blocks along k) of 16
     int device;
+    int act_bits;      // width of the activation codes: 8 or 6
     uint8_t* Wt;       // device, N32*KT records
     uint8_t* At;       // device, kp16*KT records
     uint8_t* Bt;       // device, N32*kp16 records

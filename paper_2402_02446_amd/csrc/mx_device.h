@@ -66,6 +66,12 @@ __device__ __forceinline__ float h_scale(uint32_t eb) {
                       : f32_from_bits((eb + 18u) << 23) * 0x1p-24f;
 }
 
+// fp32 scale 2^(eb - 127 - frac) of an MXINT block with `frac` fraction bits (6 for 8-bit codes, 4 for 6-bit).
+__device__ __forceinline__ float x_scale(uint32_t eb, int frac) {
+    return (eb > (uint32_t)frac) ? f32_from_bits((eb - frac) << 23)
+                                 : f32_from_bits((eb + 24u - frac) << 23) * 0x1p-24f;
+}
+
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }

@@ -34,14 +34,14 @@ def _check(x_np, bits, ld=None):
     assert np.array_equal(codes.view(np.uint8), oc.view(np.uint8))
 
 
-@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("bits", [8, 6, 4])
 def test_adversarial_blocks(bits):
     rng = np.random.default_rng(0)
     blocks = synth.adversarial_blocks(rng, 4096)            # ties, saturation, zeros, subnormals, huge
     _check(blocks.reshape(256, 256), bits)
 
 
-@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("bits", [8, 6, 4])
 @pytest.mark.parametrize("shape", [(1, 16), (3, 48), (16, 512), (17, 4096), (257, 1040)])
 def test_shapes_and_ragged_tails(bits, shape):
     rng = np.random.default_rng(1)

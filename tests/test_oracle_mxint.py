@@ -68,7 +68,7 @@ def _brute_block(vals, bits):
     return codes, e + 127
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [4, 6, 8])
 def test_brute_force_rational(bits):
     rng = np.random.default_rng(7)
     blocks = synth.adversarial_blocks(rng, 96)
@@ -88,7 +88,7 @@ def test_exponent_byte_is_fp32_exponent_field():
     assert np.array_equal(x[:, 0].astype(np.uint32), field)
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [4, 6, 8])
 def test_idempotence(bits):
     rng = np.random.default_rng(11)
     v = np.concatenate([synth.adversarial_blocks(rng, 256),
@@ -101,7 +101,7 @@ def test_idempotence(bits):
     assert np.array_equal(x, x2)
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [4, 6, 8])
 def test_error_bound(bits):
     rng = np.random.default_rng(5)
     v = (rng.standard_normal((2000, 16)) * np.exp2(rng.integers(-20, 20, (2000, 1)))).astype(np.float32)
@@ -116,7 +116,7 @@ def test_error_bound(bits):
     assert np.all(err < 2 * half_step)           # saturated elements lose at most one step
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [4, 6, 8])
 def test_antisymmetry_and_scale_covariance(bits):
     rng = np.random.default_rng(9)
     v = rng.standard_normal((300, 16)).astype(np.float32)
