@@ -183,6 +183,24 @@ int lqer_linear_forward_ex(const lqer_layer* layer, const float* X_dev, int64_t 
                            void* workspace_dev, size_t workspace_bytes, void* hip_stream,
                            const lqer_launch_opts* opts);
 
+/*
+ * Forward pass whose result leaves as MXINT8, ready to be the next layer's X_q: the
+ * weight-activation flow of Table 1 quantizes a layer's output again; here the quantizer
+ * (Sec. 2.2, block [1,16] of Sec. 4.1) is applied to the fp32 accumulators in the epilogue of
+ * the main kernel instead of in a pass over a stored Y.
+ *   Yc_dev  int8 [M][ldyc] device (ldyc >= N, multiple of 4; Yc_dev 4-byte aligned)
+ *   Ye_dev  uint8 [M][N/16] device; N must be a multiple of 16
+ *   opts    as for lqer_linear_forward_ex, or NULL.  Shapes of the streaming kernel that run
+ *           pairs of workgroups cannot quantize in the kernel: automatic choice avoids them,
+ *           forcing one returns LQER_ERR_SHAPE.
+ * The codes and exponent bytes are those lqer_quantize_mx gives for the fp32 Y that
+ * lqer_linear_forward_ex produces with the same path and variant.  Same contract otherwise.
+ */
+int lqer_linear_forward_requant(const lqer_layer* layer, const float* X_dev, int64_t M, int64_t ldx,
+                                int8_t* Yc_dev, int64_t ldyc, uint8_t* Ye_dev,
+                                void* workspace_dev, size_t workspace_bytes, void* hip_stream,
+                                const lqer_launch_opts* opts);
+
 /* Which path the dispatcher picks for this layer at M tokens: 1 = streaming, 2 = tiled MFMA. */
 int lqer_linear_path(const lqer_layer* layer, int64_t M);
 

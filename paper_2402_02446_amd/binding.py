@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "LQER_OK", 1: "LQER_ERR_NULL", 2: "LQER_ERR_SHAPE", 3: "LQER_
 EXPORTS = ("lqer_status_string", "lqer_quantize_mx", "lqer_build_factors", "lqer_build_factors_device",
            "lqer_layer_import",
            "lqer_layer_export", "lqer_layer_dims", "lqer_layer_set_activation_bits", "lqer_layer_free", "lqer_linear_workspace_bytes",
-           "lqer_linear_forward", "lqer_linear_forward_q", "lqer_linear_forward_ex", "lqer_linear_path")
+           "lqer_linear_forward", "lqer_linear_forward_q", "lqer_linear_forward_ex", "lqer_linear_forward_requant", "lqer_linear_path")
 
 
 class LqerError(RuntimeError):
@@ -82,6 +82,8 @@ def lib() -> C.CDLL:
     L.lqer_linear_forward_q.argtypes = [vp, vp, vp, i64, vp, i64, vp, sz, vp]
     L.lqer_linear_forward_ex.restype = i32
     L.lqer_linear_forward_ex.argtypes = [vp, vp, i64, i64, vp, i64, vp, sz, vp, C.POINTER(LaunchOpts)]
+    L.lqer_linear_forward_requant.restype = i32
+    L.lqer_linear_forward_requant.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, sz, vp, vp]
     L.lqer_linear_path.restype = i32
     L.lqer_linear_path.argtypes = [vp, i64]
     _lib = L
@@ -264,3 +266,19 @@ def lqer_linear_forward_ex(layer: Layer, X, Y=None, workspace=None, path=0, vari
                                         _stream(), C.byref(opts)),
            "lqer_linear_forward_ex")
     return Y
+
+
+def lqer_linear_forward_requant(layer: Layer, X, workspace=None, path=0, variant=0):
+    """Forward pass with Y leaving as MXINT8: returns (codes int8 [M][N], exps uint8 [M][N/16])."""
+    import torch
+    M = X.shape[0]
+    codes = torch.empty((M, layer.N), dtype=torch.int8, device=X.device)
+    exps = torch.empty((M, layer.N // 16), dtype=torch.uint8, device=X.device)
+    ws = layer.workspace(M) if workspace is None else workspace
+    ldx = X.stride(0) if M > 1 else max(layer.K, X.stride(0))
+    opts = LaunchOpts(path, variant, 0)
+    _check(lib().lqer_linear_forward_requant(layer.handle, C.c_void_p(X.data_ptr()), M, ldx,
+                                             C.c_void_p(codes.data_ptr()), layer.N, C.c_void_p(exps.data_ptr()),
+                                             C.c_void_p(ws.data_ptr()), ws.numel(), _stream(), C.byref(opts)),
+           "lqer_linear_forward_requant")
+    return codes, exps

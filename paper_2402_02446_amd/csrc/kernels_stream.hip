@@ -39,6 +39,7 @@ struct StreamArgs {
     const uint8_t* Xcell;          // activations: bf16 as 16-byte cells [KT*32][R rows] (R = 4), or MXINT8 codes [KT*16][R][16] + exponent bytes [KT*16][R]
     const float* Tpart; int S;
     float* Y; int64_t ldy;
+    int8_t* Yc; uint8_t* Ye; int64_t ldyc;           // Yc != null: store Y as MXINT8 (blocks of 16 along N) instead of fp32
     int64_t M, N, KT, N32;
     int kp, kp16;
 };
@@ -427,6 +428,38 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     // rows of 32 consecutive columns (two cache lines) instead of 64 scattered dwords: the finished
     // sums go through LDS once more to change the lane order.
     float* yt = red + NWK * NGV * 1024;                                // [NG][32 rows][32 columns], behind the partial sums
+    // As MXINT8 for the next layer (one workgroup per column block only): a unit is one block of 16
+    // columns of a (group, token block) - quarters 2 b and 2 b + 1, eight values in this lane and
+    // eight in lane ^ 32 (the same token).
+    if (KSP == 1 && a.Yc != nullptr) {
+        for (int u = wave; u < NGV * 2; u += NW) {
+            const int qv = u >> 1, b = u & 1;
+            const int q = qv / MB, row = t + 32 * (qv % MB);
+            float v[8];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                f32x4 s4 = *red_at(0, qv, 2 * b + h);
+#pragma unroll
+                for (int k = 1; k < NWK; ++k) {
+                    const f32x4 o = *red_at(k, qv, 2 * b + h);
+                    s4[0] += o[0]; s4[1] += o[1]; s4[2] += o[2]; s4[3] += o[3];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[4 * h + j] = s4[j];
+            }
+            uint32_t w0, w1;
+            const uint32_t eb = requant_half_block(v, w0, w1);
+            const int64_t grp = cb * NG + q;
+            const int64_t n0 = grp * 32 + 16 * b;
+            if (grp < a.N32 && row < a.M && n0 < a.N) {
+                int8_t* dst = a.Yc + (int64_t)row * a.ldyc + n0 + 4 * hh;
+                *reinterpret_cast<uint32_t*>(dst) = w0;
+                *reinterpret_cast<uint32_t*>(dst + 8) = w1;
+                if (hh == 0) a.Ye[(int64_t)row * (a.N >> 4) + (n0 >> 4)] = (uint8_t)eb;
+            }
+        }
+        return;
+    }
     for (int u = wave; u < NGV * 4; u += NW) {
         const int qv = u >> 2, r4 = u & 3;
         const int q = qv / MB, row = t + 32 * (qv % MB);
@@ -525,16 +558,19 @@ int stream_variant(const Layer& L, int64_t M, int variant) {
     return (M <= 16) ? 11181 : 11241;
 }
 bool stream_variant_adds_into_y(int variant) { return variant / 10000 == 2; }
+int stream_variant_unpaired(int64_t M) { return M <= 16 ? 11181 : 11241; }
 bool stream_takes_codes(int variant, int lr) { return lr >= 4 && !stream_variant_adds_into_y(variant); }
 
-hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
+hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy, const Requant& rq,
                          int variant, hipStream_t s) {
     if (M == 0) return hipSuccess;
     StreamArgs a;
     a.Wt = L.Wt; a.Bt = L.Bt; a.Xcell = reinterpret_cast<const uint8_t*>(ws.Xh);
     a.Tpart = ws.Tpart; a.S = ws.S;
     a.Y = Y; a.ldy = ldy; a.M = M; a.N = L.N; a.KT = L.KT; a.N32 = L.N32; a.kp = L.kp; a.kp16 = L.kp16;
+    a.Yc = rq.codes; a.Ye = rq.exps; a.ldyc = rq.ld;
     const int v = stream_variant(L, M, variant);
+    if (rq.codes != nullptr && stream_variant_adds_into_y(v)) return hipErrorInvalidValue;   // a pair's sum is complete only in memory
     switch (v) {
         case 11441: return launch_stream_rows<1, 4, 4, 1>(a, s);
         case 11421: return launch_stream_rows<1, 4, 2, 1>(a, s);

@@ -37,6 +37,7 @@ struct TiledArgs {
     const uint16_t* Xh; int64_t ldxh;
     const float* Tpart; int S; int64_t tp_stride;    // S > 1: T as S fp32 partial sums [S][tp_stride / kp rows][kp]
     float* Y; int64_t ldy;
+    int8_t* Yc; uint8_t* Ye; int64_t ldyc;           // Yc != null: store Y as MXINT8 (blocks of 16 along N) instead of fp32
     int64_t M, N, KT, N32;
     int kp, kp16;
     int grid_m, grid_n;
@@ -442,6 +443,36 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     }
 
     // ---- store: lane (t, hh) holds columns 8 r4 + 4 hh .. + 3 of token t for every MFMA tile ------
+    // As MXINT8 for the next layer: block b of a column group is columns 16 b .. 16 b + 15 = accumulator
+    // registers 8 b .. 8 b + 7 of this lane and of lane ^ 32 (the same token).
+    if (a.Yc != nullptr) {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            const int64_t row = m0 + (wr * TM + tm) * 32 + t_e;
+            if (row >= a.M) continue;
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const int64_t cg = g0 + tn;
+                if (cg >= a.N32) continue;
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    float v[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[i] = acc[tm][tn][8 * b + i];
+                    uint32_t w0, w1;
+                    const uint32_t eb = requant_half_block(v, w0, w1);
+                    const int64_t n0 = cg * 32 + 16 * b;
+                    if (n0 < a.N) {
+                        int8_t* dst = a.Yc + row * a.ldyc + n0 + 4 * hh_e;
+                        *reinterpret_cast<uint32_t*>(dst) = w0;
+                        *reinterpret_cast<uint32_t*>(dst + 8) = w1;
+                        if (hh_e == 0) a.Ye[row * (a.N >> 4) + (n0 >> 4)] = (uint8_t)eb;
+                    }
+                }
+            }
+        }
+        if constexpr (!SPLIT) break; else continue;
+    }
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
         const int64_t row = m0 + (wr * TM + tm) * 32 + t_e;
@@ -589,11 +620,12 @@ int compute_units() {
     return cus;
 }
 
-hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
+hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy, const Requant& rq,
                         int variant, hipStream_t s) {
     if (M == 0) return hipSuccess;
     TiledArgs a;
     a.Wt = L.Wt; a.Bt = L.Bt; a.Xh = ws.Xh; a.ldxh = ws.ldxh; a.Y = Y; a.ldy = ldy;
+    a.Yc = rq.codes; a.Ye = rq.exps; a.ldyc = rq.ld;
     a.Tpart = ws.Tpart; a.S = ws.S; a.tp_stride = ws.tp_rows * L.kp;
     a.M = M; a.N = L.N; a.KT = L.KT; a.N32 = L.N32; a.kp = L.kp; a.kp16 = L.kp16;
     a.grid_m = a.grid_n = 0; a.group_m = 8;

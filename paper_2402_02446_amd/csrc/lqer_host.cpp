@@ -278,12 +278,20 @@ static int pick_path(const Layer& L, int64_t M) {
 
 static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, const int8_t* Xc,
                         const uint8_t* Xe, int64_t M, float* Y, int64_t ldy, void* wsp, size_t ws_bytes,
-                        void* stream, const lqer_launch_opts* opts) {
+                        void* stream, const lqer_launch_opts* opts, const Requant& rq = Requant{nullptr, nullptr, 0}) {
     if (!layer) return LQER_ERR_NULL;
     const Layer& L = layer->L;
     if (M < 0) return LQER_ERR_SHAPE;
     if (M == 0) return LQER_OK;
-    if (!Y) return LQER_ERR_NULL;
+    const bool requant = rq.codes != nullptr;
+    if (requant) {
+        // Y leaves as MXINT8 with blocks of 16 along N: the next layer's contraction axis
+        if (!rq.exps) return LQER_ERR_NULL;
+        if ((L.N & 15) != 0 || rq.ld < L.N || (rq.ld & 3) != 0 || ((uintptr_t)rq.codes & 3) != 0) return LQER_ERR_SHAPE;
+        ldy = L.N;                                   // no fp32 Y: keep the checks below quiet
+    } else if (!Y) {
+        return LQER_ERR_NULL;
+    }
     if (Xc) {
         if (!Xe) return LQER_ERR_NULL;
         if (((uintptr_t)Xc & 15) != 0) return LQER_ERR_SHAPE;
@@ -291,13 +299,16 @@ static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, co
         if (!X) return LQER_ERR_NULL;
         if (ldx < L.K || (ldx & 3) != 0 || ((uintptr_t)X & 15) != 0) return LQER_ERR_SHAPE;
     }
-    if (ldy < L.N || (ldy & 3) != 0 || ((uintptr_t)Y & 15) != 0) return LQER_ERR_SHAPE;
+    if (!requant && (ldy < L.N || (ldy & 3) != 0 || ((uintptr_t)Y & 15) != 0)) return LQER_ERR_SHAPE;
     int path = opts ? opts->path : 0;
-    const int variant = opts ? opts->variant : 0;
+    int variant = opts ? opts->variant : 0;
     int stages = opts ? opts->stages : 0;
     if (path < 0 || path > 2 || (stages & ~3) != 0) return LQER_ERR_SHAPE;
     if (path == 0) path = pick_path(L, M);
     if (path == 1 && M > stream_max_rows()) return LQER_ERR_SHAPE;
+    // a pair of workgroups completes its sum only in memory: with MXINT8 output take the unpaired shape
+    if (requant && path == 1 && variant == 0 && stream_variant_adds_into_y(stream_variant(L, M, 0)))
+        variant = stream_variant_unpaired(M);
     if (stages == 0) stages = 3;
     if (!wsp || ((uintptr_t)wsp & 255) != 0) return LQER_ERR_WORKSPACE;
     Workspace ws = plan_workspace(L, M, path, wsp);
@@ -310,8 +321,8 @@ static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, co
     }
     if (stages & 2) {
         if (!(stages & 1) && path == 2 && launch_clear_flags(ws, s) != hipSuccess) return LQER_ERR_HIP;
-        const hipError_t e = (path == 1) ? launch_stream(L, M, ws, Y, ldy, variant, s)
-                                         : launch_tiled(L, M, ws, Y, ldy, variant, s);
+        const hipError_t e = (path == 1) ? launch_stream(L, M, ws, Y, ldy, rq, variant, s)
+                                         : launch_tiled(L, M, ws, Y, ldy, rq, variant, s);
         if (e == hipErrorInvalidValue) return LQER_ERR_SHAPE;
         if (e != hipSuccess) return LQER_ERR_HIP;
     }
@@ -454,6 +465,14 @@ size_t lqer_linear_workspace_bytes(const lqer_layer* layer, int64_t M) {
         if (b1 > best) best = b1;
     }
     return best;
+}
+
+int lqer_linear_forward_requant(const lqer_layer* layer, const float* X_dev, int64_t M, int64_t ldx,
+                                int8_t* Yc_dev, int64_t ldyc, uint8_t* Ye_dev, void* workspace_dev,
+                                size_t workspace_bytes, void* hip_stream, const lqer_launch_opts* opts) {
+    if (!Yc_dev) return LQER_ERR_NULL;
+    return forward_impl(layer, X_dev, ldx, nullptr, nullptr, M, nullptr, 0, workspace_dev, workspace_bytes,
+                        hip_stream, opts, Requant{Yc_dev, Ye_dev, ldyc});
 }
 
 int lqer_linear_path(const lqer_layer* layer, int64_t M) {

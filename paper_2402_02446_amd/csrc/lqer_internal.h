@@ -94,16 +94,24 @@ hipError_t launch_quantize_mx(const float* x, int64_t rows, int64_t cols, int64_
 hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t* Xc, const uint8_t* Xe,
                        int64_t M, const Workspace& ws, float* y_zero, int64_t ldy, hipStream_t s);
 
+// Output of the main kernels as MXINT8 (blocks of 16 along N) instead of fp32 Y; codes == null: fp32.
+struct Requant {
+    int8_t* codes;       // [M][ld] int8
+    uint8_t* exps;       // [M][N/16]
+    int64_t ld;
+};
+
 // Streaming (small M) main kernel.  variant 0 = automatic.
-hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
+hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy, const Requant& rq,
                          int variant, hipStream_t s);
+int stream_variant_unpaired(int64_t M);                          // the shape used when pairs of workgroups are ruled out
 int stream_max_rows();
 int stream_variant(const Layer& L, int64_t M, int variant);      // resolves 0 = automatic
 bool stream_variant_adds_into_y(int variant);                    // Y must be zero before the launch
 bool stream_takes_codes(int variant, int lr);                    // activations as MXINT8 codes + exponent bytes instead of bf16 cells
 int stream_cell_rows_log2(int64_t M);
 // Tiled MFMA (large M) main kernel.
-hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy,
+hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy, const Requant& rq,
                         int variant, hipStream_t s);
 
 hipError_t launch_clear_flags(const Workspace& ws, hipStream_t s);

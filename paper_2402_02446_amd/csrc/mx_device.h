@@ -82,6 +82,27 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// Eight values of one MXINT8 block held by this lane (the other eight sit in lane ^ 32): the block's
+// exponent byte from the maximum over both lanes, and this lane's codes as two words of four bytes.
+__device__ __forceinline__ uint32_t requant_half_block(const float (&v)[8], uint32_t& w0, uint32_t& w1) {
+    float m = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m = __builtin_fmaxf(m, __builtin_fabsf(v[i]));
+    m = __builtin_fmaxf(m, __shfl_xor(m, 32));
+    const uint32_t eb = (f32_bits(m) >> 23) & 0xFFu;
+    const int e = (int)eb - 127;
+    uint32_t w[2] = {0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float r = __builtin_rintf(__builtin_amdgcn_ldexpf(v[i], 6 - e));
+        r = __builtin_fminf(__builtin_fmaxf(r, -127.0f), 127.0f);
+        w[i >> 2] |= ((uint32_t)(int)r & 0xFFu) << (8 * (i & 3));
+    }
+    w0 = w[0];
+    w1 = w[1];
+    return eb;
+}
+
 // MXINT8 quantization of one value given the block's exponent byte: code = sat(rne(v * 2^(6-e))).
 __device__ __forceinline__ int mx8_code(float v, int e_unbiased) {
     float r = __builtin_rintf(__builtin_amdgcn_ldexpf(v, 6 - e_unbiased));

@@ -278,6 +278,58 @@ def test_six_bit_activations(M, K, N, k):
     h.free()
 
 
+@pytest.mark.parametrize("M,K,N,k,path,variant", [
+    (1, 1024, 272, 32, 1, 11181), (16, 4096, 64, 16, 1, 11181), (20, 2304, 528, 33, 1, 11241), (5, 1024, 4096, 8, 1, 12241),
+    (40, 512, 16384, 8, 1, 11421), (300, 1024, 528, 64, 2, 111), (300, 1024, 528, 64, 2, 112), (513, 4352, 1104, 16, 2, 211),
+    (700, 2304, 272, 33, 2, 204), (100, 272, 48, 0, 2, 104)])
+def test_output_as_mxint8(M, K, N, k, path, variant):
+    # The result leaves as MXINT8 (blocks of 16 along N) from the epilogue of the main kernel: codes and
+    # exponent bytes must be exactly what the oracle's quantizer makes of the fp32 Y the same kernel shape stores
+    import torch
+    from paper_2402_02446_amd import binding
+    if N > 2048:
+        layer = factors.PackedLayer(**synth.random_packed_layer(np.random.default_rng(N), K, N, k))
+        ch = synth.gen_outlier_channels(np.random.default_rng(1), K, 4)
+    else:
+        layer, ch = oracle_layer_small(K, N, k, seed=M + k)
+    h = upload(layer)
+    X = synth.gen_activations(np.random.default_rng(M), M, K, ch, 30.0)
+    Xd = torch.from_numpy(X).cuda()
+    Y = binding.lqer_linear_forward_ex(h, Xd, path=path, variant=variant).cpu().numpy()
+    codes, exps = binding.lqer_linear_forward_requant(h, Xd, path=path, variant=variant)
+    torch.cuda.synchronize()
+    oc, oe = mxint.mx_quantize(Y, 8, axis=-1)
+    assert np.array_equal(exps.cpu().numpy(), oe)
+    assert np.array_equal(codes.cpu().numpy(), oc)
+    # and the dequantized output is the oracle's Y to within the 8-bit step of each block
+    Yq = mxint.mx_dequantize(codes.cpu().numpy(), exps.cpu().numpy(), 8, axis=-1)
+    assert forward.rel_frobenius(Yq, forward.forward(X, layer)) < 2.0 ** -6
+    h.free()
+
+
+def test_output_as_mxint8_automatic_shape_and_errors():
+    import torch
+    from paper_2402_02446_amd import binding
+    # a layer whose automatic streaming shape runs pairs of workgroups: the MXINT8 output must avoid them
+    layer, ch = oracle_layer_big(4096, 4096, 32, seed=3)
+    h = upload(layer)
+    for M in (1, 16, 32):
+        X = synth.gen_activations(np.random.default_rng(M), M, 4096, ch, 50.0)
+        Xd = torch.from_numpy(X).cuda()
+        codes, exps = binding.lqer_linear_forward_requant(h, Xd)
+        Yq = mxint.mx_dequantize(codes.cpu().numpy(), exps.cpu().numpy(), 8, axis=-1)
+        assert forward.rel_frobenius(Yq, forward.forward(X, layer)) < 2.0 ** -6
+        with pytest.raises(binding.LqerError):
+            binding.lqer_linear_forward_requant(h, Xd, path=1, variant=21181 if M <= 16 else 21141)
+    h.free()
+    odd, ch = oracle_layer_small(512, 40, 8, seed=1)             # N is no multiple of 16: no MXINT8 blocks along N
+    h = upload(odd)
+    Xd = torch.from_numpy(synth.gen_activations(np.random.default_rng(0), 4, 512, ch, 30.0)).cuda()
+    with pytest.raises((binding.LqerError, RuntimeError)):
+        binding.lqer_linear_forward_requant(h, Xd)
+    h.free()
+
+
 def test_split_is_refused_for_shapes_without_it():
     from paper_2402_02446_amd import binding
     layer, ch = oracle_layer_small(1024, 272, 8, seed=2)
