@@ -330,6 +330,49 @@ def test_output_as_mxint8_automatic_shape_and_errors():
     h.free()
 
 
+def test_split_tiles_in_hip_graph_and_on_two_streams():
+    # The flags of the hand-over are cleared by the projection kernel of every call, so replays of a captured
+    # forward pass and two calls in flight on two streams (distinct workspaces) all reproduce the eager result.
+    import torch
+    from paper_2402_02446_amd import binding
+    layer, ch = oracle_layer_small(2304, 528, 33, seed=21)
+    h = upload(layer)
+    M = 300
+    X = torch.from_numpy(synth.gen_activations(np.random.default_rng(1), M, 2304, ch, 30.0)).cuda()
+    X2 = torch.from_numpy(synth.gen_activations(np.random.default_rng(2), M, 2304, ch, 30.0)).cuda()
+    for variant in (211, 212):
+        want = binding.lqer_linear_forward_ex(h, X, path=2, variant=variant).clone()
+        want2 = binding.lqer_linear_forward_ex(h, X2, path=2, variant=variant).clone()
+        torch.cuda.synchronize()
+        Xg, Yg = X.clone(), torch.empty_like(want)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            binding.lqer_linear_forward_ex(h, Xg, Y=Yg, path=2, variant=variant)
+        for rep, (src, w) in enumerate([(X, want), (X2, want2), (X, want)]):
+            Xg.copy_(src)
+            Yg.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(Yg, w), f"replay {rep} differs (variant {variant})"
+            _ = binding.lqer_linear_forward_ex(h, X2, path=2, variant=variant)
+        # two streams, two workspaces
+        nbytes = binding.lqer_linear_workspace_bytes(h, M)
+        wsa = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        wsb = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        Ya, Yb = torch.empty_like(want), torch.empty_like(want)
+        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        for _ in range(5):
+            with torch.cuda.stream(sa):
+                binding.lqer_linear_forward_ex(h, X, Y=Ya, workspace=wsa, path=2, variant=variant)
+            with torch.cuda.stream(sb):
+                binding.lqer_linear_forward_ex(h, X2, Y=Yb, workspace=wsb, path=2, variant=variant)
+        torch.cuda.synchronize()
+        assert torch.equal(Ya, want) and torch.equal(Yb, want2)
+    h.free()
+
+
 def test_split_is_refused_for_shapes_without_it():
     from paper_2402_02446_amd import binding
     layer, ch = oracle_layer_small(1024, 272, 8, seed=2)
