@@ -141,6 +141,8 @@ int lqer_layer_free(lqer_layer* layer);
  *   X_dev  [M][ldx] fp32 device (ldx >= K);  Y_dev [M][ldy] fp32 device (ldy >= N)
  *   workspace_dev  device scratch of at least lqer_linear_workspace_bytes(layer, M)
  *                  bytes, 256-byte aligned, caller-owned; its contents are scratch.
+ *                  (lqer_linear_workspace_bytes_ex: the same for a forced path of lqer_linear_forward_ex,
+ *                  0 = the automatic one; a few hundred KiB for small M, 64 MiB more for the tiled kernel)
  * Steps, all in this library's kernels: quantize X to MXINT8 (Sec. 4.1), T = X_q A_k,
  * Y = X_q W_q + T B_k accumulated in fp32 in one pass over Y.  M == 0 is a no-op.
  * Calls on different streams need distinct workspaces.  The library allocates nothing here,
@@ -155,6 +157,7 @@ int lqer_layer_free(lqer_layer* layer);
  * (Xc int8 [M][K], Xe uint8 [M][K/16], canonical, device).
  */
 size_t lqer_linear_workspace_bytes(const lqer_layer* layer, int64_t M);
+size_t lqer_linear_workspace_bytes_ex(const lqer_layer* layer, int64_t M, int path);
 int lqer_linear_forward(const lqer_layer* layer, const float* X_dev, int64_t M, int64_t ldx,
                         float* Y_dev, int64_t ldy,
                         void* workspace_dev, size_t workspace_bytes, void* hip_stream);

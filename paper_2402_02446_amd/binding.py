@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "LQER_OK", 1: "LQER_ERR_NULL", 2: "LQER_ERR_SHAPE", 3: "LQER_
 # every symbol include/lqer.h declares
 EXPORTS = ("lqer_status_string", "lqer_quantize_mx", "lqer_build_factors", "lqer_build_factors_device",
            "lqer_layer_import",
-           "lqer_layer_export", "lqer_layer_dims", "lqer_layer_set_activation_bits", "lqer_layer_free", "lqer_linear_workspace_bytes",
+           "lqer_layer_export", "lqer_layer_dims", "lqer_layer_set_activation_bits", "lqer_layer_free", "lqer_linear_workspace_bytes", "lqer_linear_workspace_bytes_ex",
            "lqer_linear_forward", "lqer_linear_forward_q", "lqer_linear_forward_ex", "lqer_linear_forward_requant", "lqer_linear_path")
 
 
@@ -76,6 +76,8 @@ def lib() -> C.CDLL:
     L.lqer_layer_free.argtypes = [vp]
     L.lqer_linear_workspace_bytes.restype = sz
     L.lqer_linear_workspace_bytes.argtypes = [vp, i64]
+    L.lqer_linear_workspace_bytes_ex.restype = sz
+    L.lqer_linear_workspace_bytes_ex.argtypes = [vp, i64, i32]
     L.lqer_linear_forward.restype = i32
     L.lqer_linear_forward.argtypes = [vp, vp, i64, i64, vp, i64, vp, sz, vp]
     L.lqer_linear_forward_q.restype = i32
@@ -148,10 +150,10 @@ class Layer:
         except Exception:
             pass
 
-    def workspace(self, M: int):
-        """A cached torch allocation of lqer_linear_workspace_bytes(M) bytes."""
+    def workspace(self, M: int, path: int = 0):
+        """A cached torch allocation of lqer_linear_workspace_bytes_ex(M, path) bytes."""
         import torch
-        need = lib().lqer_linear_workspace_bytes(self.handle, M)
+        need = lib().lqer_linear_workspace_bytes_ex(self.handle, M, path)
         if self._ws is None or self._ws.numel() < need:
             self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
         return self._ws
@@ -216,8 +218,8 @@ def lqer_build_factors_device(W, calib, k: int, mode: int = 1, cfg=None) -> Laye
     return Layer(out.value)
 
 
-def lqer_linear_workspace_bytes(layer: Layer, M: int) -> int:
-    return int(lib().lqer_linear_workspace_bytes(layer.handle, M))
+def lqer_linear_workspace_bytes(layer: Layer, M: int, path: int = 0) -> int:
+    return int(lib().lqer_linear_workspace_bytes_ex(layer.handle, M, path))
 
 
 def lqer_linear_path(layer: Layer, M: int) -> int:
@@ -257,7 +259,7 @@ def lqer_linear_forward_ex(layer: Layer, X, Y=None, workspace=None, path=0, vari
     M = X.shape[0]
     if Y is None:
         Y = torch.empty((M, layer.N), dtype=torch.float32, device=X.device)
-    ws = layer.workspace(M) if workspace is None else workspace
+    ws = layer.workspace(M, path) if workspace is None else workspace
     ldx = X.stride(0) if M > 1 else max(layer.K, X.stride(0))
     ldy = Y.stride(0) if M > 1 else max(layer.N, Y.stride(0))
     opts = LaunchOpts(path, variant, stages)
@@ -274,7 +276,7 @@ def lqer_linear_forward_requant(layer: Layer, X, workspace=None, path=0, variant
     M = X.shape[0]
     codes = torch.empty((M, layer.N), dtype=torch.int8, device=X.device)
     exps = torch.empty((M, layer.N // 16), dtype=torch.uint8, device=X.device)
-    ws = layer.workspace(M) if workspace is None else workspace
+    ws = layer.workspace(M, path) if workspace is None else workspace
     ldx = X.stride(0) if M > 1 else max(layer.K, X.stride(0))
     opts = LaunchOpts(path, variant, 0)
     _check(lib().lqer_linear_forward_requant(layer.handle, C.c_void_p(X.data_ptr()), M, ldx,

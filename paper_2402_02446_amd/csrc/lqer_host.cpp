@@ -456,15 +456,16 @@ int lqer_layer_free(lqer_layer* layer) {
     return LQER_OK;
 }
 
-size_t lqer_linear_workspace_bytes(const lqer_layer* layer, int64_t M) {
-    if (!layer || M <= 0) return 0;
+size_t lqer_linear_workspace_bytes_ex(const lqer_layer* layer, int64_t M, int path) {
+    if (!layer || M <= 0 || path < 0 || path > 2) return 0;
     const Layer& L = layer->L;
-    size_t best = plan_workspace(L, M, 2, nullptr).bytes;
-    if (M <= stream_max_rows()) {
-        const size_t b1 = plan_workspace(L, M, 1, nullptr).bytes;
-        if (b1 > best) best = b1;
-    }
-    return best;
+    if (path == 0) path = pick_path(L, M);
+    if (path == 1 && M > stream_max_rows()) return 0;
+    return plan_workspace(L, M, path, nullptr).bytes;
+}
+
+size_t lqer_linear_workspace_bytes(const lqer_layer* layer, int64_t M) {
+    return lqer_linear_workspace_bytes_ex(layer, M, 0);
 }
 
 int lqer_linear_forward_requant(const lqer_layer* layer, const float* X_dev, int64_t M, int64_t ldx,

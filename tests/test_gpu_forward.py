@@ -357,7 +357,7 @@ def test_split_tiles_in_hip_graph_and_on_two_streams():
             assert torch.equal(Yg, w), f"replay {rep} differs (variant {variant})"
             _ = binding.lqer_linear_forward_ex(h, X2, path=2, variant=variant)
         # two streams, two workspaces
-        nbytes = binding.lqer_linear_workspace_bytes(h, M)
+        nbytes = binding.lqer_linear_workspace_bytes(h, M, 2)
         wsa = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
         wsb = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
         Ya, Yb = torch.empty_like(want), torch.empty_like(want)
