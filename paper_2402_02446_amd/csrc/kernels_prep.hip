@@ -1,5 +1,6 @@
-// Stage 1 of the forward pass: quantize activations to MXINT8 (Sec. 4.1, block [1,16]) and
-// compute the low-rank projection T = X_q A_k (Eq. 3 / Eq. 6, first small matmul).
+// Stage 1 of the forward pass: quantize activations to MXINT8 (Sec. 4.1, block [1,16]; MXINT6 for the
+// W4A6 setup of Table 2) and compute the low-rank projection T = X_q A_k (Eq. 3 / Eq. 6, first small
+// matmul).
 //
 // One workgroup owns 16 token rows and a K slice; its eight wavefronts take the slice's 256-wide
 // K tiles in turn.  Lane (t = lane % 16, q = lane / 16) owns the blocks q + 4p (p = 0..3) of a
@@ -11,6 +12,9 @@
 // S == 1: T is final; it is split into two bf16 terms T_hi + T_lo and stored behind the
 //         activations of the same row, where the main kernel treats it as 2*kp more K columns.
 // S  > 1: each K slice stores an fp32 partial T; the main kernel adds the slices in a fixed order.
+// For the streaming kernel the activations are stored as 16-byte cells [K / 8][token row] instead
+// (or as the codes themselves, see the store below); extra workgroups clear Y or the tiled
+// kernel's flags where the main kernel needs that.
 #include "lqer_internal.h"
 #include "mx_device.h"
 

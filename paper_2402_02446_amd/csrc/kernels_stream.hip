@@ -11,8 +11,10 @@
 //
 // A workgroup is NWC x NWK wavefronts; wavefront (wc, wk) owns G column groups of 32 and, in step
 // it, the K tile NWK it + wk.  The projection kernel leaves the activations as 16-byte cells
-// [K / 8][token row] (bf16, exact dequantized X_q), so the NWK tiles of a step are one contiguous
-// range that the workgroup copies into one of two LDS stages.  A step walks its tile in four
+// [K / 8][token row] (bf16, exact dequantized X_q) - or, from 16 token rows up, as the MXINT8 codes
+// themselves, [K / 16][token row][16 B] with the exponent bytes behind, which the staging wavefront
+// scales to the same bf16 cells - so the NWK tiles of a step are one contiguous range that the
+// workgroup brings into one of two LDS stages.  A step walks its tile in four
 // 64-wide chunks; in chunk c every column group does four 32x32x16 MFMAs against the same four
 // operands read from LDS, and the registers that held chunk c of the weight records are refilled
 // at once with chunk c of the next tile, so a wavefront always has G whole records in flight and
@@ -24,7 +26,8 @@
 // "K columns": T_hi and T_lo against B_k's codes, spread over the wavefronts.  T arrives as S
 // partial sums (one per K slice of the projection kernel) that the workgroup adds in slice order
 // and keeps in LDS as two bf16 terms.  At the end the NWK partial sums of every column group are
-// added through LDS in slice order.
+// added through LDS in slice order and stored as fp32, or as MXINT8 blocks of 16 along N for the
+// next layer.  Up to 64 tokens are two blocks of 32 per wavefront sharing each expanded weight operand.
 #include <type_traits>
 
 #include "lqer_internal.h"
