@@ -45,6 +45,8 @@ struct StreamArgs {
     int8_t* Yc; uint8_t* Ye; int64_t ldyc;           // Yc != null: store Y as MXINT8 (blocks of 16 along N) instead of fp32
     int64_t M, N, KT, N32;
     int kp, kp16;
+    int rec_bytes;                 // bytes of a weight record
+    int exp_bias;                  // >= 0: exponent nibbles (byte = nibble + exp_bias); -1: exponent bytes
 };
 
 // LR = log2 of the token rows per activation cell column (4, 16 or 32 rows).
@@ -99,9 +101,16 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     for (int g = 0; g < G; ++g) {
         int64_t grp = g0 + g;
         if (grp >= a.N32) grp = a.N32 - 1;
-        wrec[g] = a.Wt + grp * kWRecordBytes + lane * 16;
+        wrec[g] = a.Wt + grp * a.rec_bytes + lane * 16;
     }
-    const int e_adj = -(lane * 8);                   // exponent words sit at lane * 8, not lane * 16
+    // Exponent of block 2 c + j of the lane's eight, without a branch in the main loop (a branch there
+    // makes the compiler's wait counts worst-case): word c / 2, shifted by (c % 2) * es1 + j * es0,
+    // masked, plus the bias.  Bytes: (16, 8, 0xFF, 0); nibbles: (8, 4, 0xF, bias), the second word being
+    // the first one shifted down by 16 when it is loaded.
+    const bool exp4 = a.exp_bias >= 0;               // wave-uniform
+    const int es1 = exp4 ? 8 : 16, es0 = exp4 ? 4 : 8;
+    const uint32_t emask = exp4 ? 0xFu : 0xFFu, ebias = exp4 ? (uint32_t)a.exp_bias : 0u;
+    const int e_adj = exp4 ? -(lane * 12) : -(lane * 8);    // exponent words sit at lane * 4 or lane * 8, not lane * 16
     int trow[MB];
 #pragma unroll
     for (int b = 0; b < MB; ++b) {
@@ -179,12 +188,14 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     for (int b = 0; b < MB; ++b) rd_base[b] = (((32 * wk + 4 * hh) << LR) + trow[b]) << 4;
     const int rd_flip = hh << 7;                     // swz() of an operand address: its cell has bit 2 = hh
 
-    const int64_t tile_stride = a.N32 * kWRecordBytes;             // records are ordered [K tile][column group]
+    const int64_t tile_stride = a.N32 * a.rec_bytes;             // records are ordered [K tile][column group]
     auto load_wc = [&](int g, int64_t tile, int c) {
         return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrec[g] + tile * tile_stride + c * 1024));
     };
     auto load_we = [&](int g, int64_t tile) {
-        return __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(wrec[g] + tile * tile_stride + kWExpOffset + e_adj));
+        // always 8 bytes wide: with nibbles only the first word is used (the buffer is padded behind the last record)
+        const u32x2_a4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x2_a4*>(wrec[g] + tile * tile_stride + kWExpOffset + e_adj));
+        return u32x2{w[0], exp4 ? w[0] >> 16 : w[1]};
     };
 
     f32x16 acc[G][MB];
@@ -329,8 +340,9 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
                     for (int g = 0; g < G; ++g) {
 #pragma unroll
                         for (int s = 0; s < 4; ++s) {
-                            const uint32_t ew = we_[g][c >> 1] >> (16 * (c & 1) + 8 * (s >> 1));
-                            const bf16x8 wv = unpack_w8(wc_[g][c][s], w_scale(ew & 0xFFu));
+                            // exponent byte of block 2 c + s / 2 of the lane's eight: a byte, or a nibble plus the layer's bias
+                            const uint32_t eb = ((we_[g][c >> 1] >> ((c & 1) * es1 + (s >> 1) * es0)) & emask) + ebias;
+                            const bf16x8 wv = unpack_w8(wc_[g][c][s], w_scale(eb));
 #pragma unroll
                             for (int b = 0; b < MB; ++b) acc[g][b] = mfma32(wv, xf[b][s].v, acc[g][b]);
                         }
@@ -572,6 +584,7 @@ hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* 
     a.Tpart = ws.Tpart; a.S = ws.S;
     a.Y = Y; a.ldy = ldy; a.M = M; a.N = L.N; a.KT = L.KT; a.N32 = L.N32; a.kp = L.kp; a.kp16 = L.kp16;
     a.Yc = rq.codes; a.Ye = rq.exps; a.ldyc = rq.ld;
+    a.rec_bytes = L.w_rec_bytes; a.exp_bias = L.w_exp_bias;
     const int v = stream_variant(L, M, variant);
     if (rq.codes != nullptr && stream_variant_adds_into_y(v)) return hipErrorInvalidValue;   // a pair's sum is complete only in memory
     switch (v) {

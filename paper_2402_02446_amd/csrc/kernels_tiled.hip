@@ -49,6 +49,8 @@ struct TiledArgs {
     float* Part;               // [gridDim.x][BM * BN] accumulators handed over
     uint32_t* flags;           // [gridDim.x], zero before the launch; 1 = slot written
     int spin_limit;            // polls of a flag before the waiting workgroup gives up (and stores NaN)
+    int rec_bytes;             // bytes of a weight record
+    int exp_bias;              // >= 0: exponent nibbles (byte = nibble + exp_bias); -1: exponent bytes
 };
 
 // MINW = wavefronts per SIMD the register allocation must allow (2 lets two four-wavefront workgroups share a compute unit)
@@ -99,6 +101,10 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     for (int s4 = 0; s4 < 4; ++s4)
         rd_off[s4] = (wr * TM * 32 + t) * 128 + (((4 * hh + s4) ^ ((t >> 1) & 7)) << 4);
     const int lane16 = lane * 16;
+    // exponent of a block without a branch in the main loop: bytes (16, 8, 0xFF, 0) or nibbles (8, 4, 0xF, bias)
+    const bool exp4 = a.exp_bias >= 0;                          // wave-uniform
+    const int es1 = exp4 ? 8 : 16, es0 = exp4 ? 4 : 8;
+    const uint32_t emask = exp4 ? 0xFu : 0xFFu, ebias = exp4 ? (uint32_t)a.exp_bias : 0u;
 
     int64_t dp_next = lin;                                     // next whole tile of this workgroup
     int64_t u = a.sk_share * lin;                              // its range of the shared K tiles
@@ -173,7 +179,7 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         const int cc = ch & 3;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
-            const uint8_t* rec = a.Wt + (tile * a.N32 + group_of(tn)) * kWRecordBytes;   // wave-uniform
+            const uint8_t* rec = a.Wt + (tile * a.N32 + group_of(tn)) * a.rec_bytes;   // wave-uniform
             w.c[tn] = *reinterpret_cast<const u32x4*>(rec + cc * 1024 + lane16);
         }
     };
@@ -181,8 +187,10 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         const int64_t tile = tile_i;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
-            const uint8_t* rec = a.Wt + (tile * a.N32 + group_of(tn)) * kWRecordBytes;
-            x.e[tn] = *reinterpret_cast<const u32x2*>(rec + kWExpOffset + (lane16 >> 1));
+            const uint8_t* rec = a.Wt + (tile * a.N32 + group_of(tn)) * a.rec_bytes;
+            // always 8 bytes wide: with nibbles only the first word is used (the buffer is padded behind the last record)
+            const u32x2_a4 w = *reinterpret_cast<const u32x2_a4*>(rec + kWExpOffset + (exp4 ? lane16 >> 2 : lane16 >> 1));
+            x.e[tn] = u32x2{w[0], exp4 ? w[0] >> 16 : w[1]};
         }
     };
     auto fetch_x = [&](u32x4 (&st)[LPT], int ch) {
@@ -243,9 +251,9 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         float sc[TN][2];
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
-            const uint32_t ew = x.e[tn][c >> 1] >> (16 * (c & 1));
-            sc[tn][0] = w_scale(ew & 0xFFu);
-            sc[tn][1] = w_scale((ew >> 8) & 0xFFu);
+            const uint32_t ew = x.e[tn][c >> 1] >> ((c & 1) * es1);
+            sc[tn][0] = w_scale((ew & emask) + ebias);
+            sc[tn][1] = w_scale(((ew >> es0) & emask) + ebias);
         }
 #pragma unroll
         for (int s4 = 0; s4 < 4; ++s4) {
@@ -630,6 +638,7 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
     a.M = M; a.N = L.N; a.KT = L.KT; a.N32 = L.N32; a.kp = L.kp; a.kp16 = L.kp16;
     a.grid_m = a.grid_n = 0; a.group_m = 8;
     a.Part = ws.Part; a.flags = ws.flags;
+    a.rec_bytes = L.w_rec_bytes; a.exp_bias = L.w_exp_bias;
     a.spin_limit = 1 << 22;                                  // about a second of polling
     a.dp_tiles = a.sk_units = 0; a.sk_share = 1;
     const int cus = compute_units();

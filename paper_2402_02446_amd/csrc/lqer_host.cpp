@@ -47,16 +47,26 @@ static void decode_word(uint32_t w, int8_t* c) {
 static inline int nibble_to_code(uint32_t v) { return v < 8 ? (int)v : (int)v - 16; }
 
 // canonical Wc/We -> tiled records.  Returns LQER_ERR_VALUE on a -8 nibble or an exponent byte > 247.
-static int tile_weights(const Layer& L, const uint8_t* Wc, const uint8_t* We, std::vector<uint8_t>& out) {
+// Chooses the record form: exponent nibbles when the layer's exponent bytes span at most 16 values.
+static int tile_weights(Layer& L, const uint8_t* Wc, const uint8_t* We, std::vector<uint8_t>& out) {
     const int64_t nblk = L.K / 16;
-    out.assign((size_t)(L.N32 * L.KT) * kWRecordBytes, 0);
+    int lo = 255, hi = 0;
     for (int64_t n = 0; n < L.N; ++n)
-        for (int64_t kb = 0; kb < nblk; ++kb)
-            if (We[n * nblk + kb] > kMaxWExpByte) return LQER_ERR_VALUE;
+        for (int64_t kb = 0; kb < nblk; ++kb) {
+            const int e = We[n * nblk + kb];
+            if (e > kMaxWExpByte) return LQER_ERR_VALUE;
+            lo = e < lo ? e : lo;
+            hi = e > hi ? e : hi;
+        }
+    const bool compact = hi - lo <= 15;
+    L.w_exp_bias = compact ? lo : -1;
+    L.w_rec_bytes = compact ? kWRecordBytesCompact : kWRecordBytes;
+    const int kRec = L.w_rec_bytes, bias = L.w_exp_bias;
+    out.assign((size_t)(L.N32 * L.KT) * kRec + kWTailPad, 0);
     std::atomic<int> bad{0};
     parallel_for(L.N32, [&](int64_t g) {
         for (int64_t tile = 0; tile < L.KT; ++tile) {
-            uint8_t* rec = out.data() + (size_t)(tile * L.N32 + g) * kWRecordBytes;
+            uint8_t* rec = out.data() + (size_t)(tile * L.N32 + g) * kRec;
             for (int lane = 0; lane < 64; ++lane) {
                 const int i = lane & 31, hh = lane >> 5;
                 const int64_t n = g * 32 + i;
@@ -64,7 +74,7 @@ static int tile_weights(const Layer& L, const uint8_t* Wc, const uint8_t* We, st
                     for (int j = 0; j < 2; ++j) {
                         const int64_t kb = tile * 16 + 4 * c + 2 * hh + j;
                         int8_t codes[16] = {0};
-                        uint8_t eb = 0;
+                        uint8_t eb = (uint8_t)(bias >= 0 ? bias : 0);       // padding blocks: zero codes, any exponent
                         if (n < L.N && kb < nblk) {
                             const uint8_t* src = Wc + n * (L.K / 2) + kb * 8;
                             for (int e = 0; e < 8; ++e) {
@@ -79,7 +89,12 @@ static int tile_weights(const Layer& L, const uint8_t* Wc, const uint8_t* We, st
                         uint8_t* dst = rec + c * 1024 + lane * 16 + j * 8;
                         memcpy(dst, &w0, 4);
                         memcpy(dst + 4, &w1, 4);
-                        rec[kWExpOffset + lane * 8 + 2 * c + j] = eb;
+                        if (bias >= 0) {
+                            uint8_t& b2 = rec[kWExpOffset + lane * 4 + c];              // nibble 2c + j of the lane's word
+                            b2 = (uint8_t)(b2 | ((eb - bias) << (4 * j)));
+                        } else {
+                            rec[kWExpOffset + lane * 8 + 2 * c + j] = eb;
+                        }
                     }
             }
         }
@@ -91,7 +106,7 @@ static void untile_weights(const Layer& L, const std::vector<uint8_t>& in, uint8
     const int64_t nblk = L.K / 16;
     parallel_for(L.N32, [&](int64_t g) {
         for (int64_t tile = 0; tile < L.KT; ++tile) {
-            const uint8_t* rec = in.data() + (size_t)(tile * L.N32 + g) * kWRecordBytes;
+            const uint8_t* rec = in.data() + (size_t)(tile * L.N32 + g) * L.w_rec_bytes;
             for (int lane = 0; lane < 64; ++lane) {
                 const int i = lane & 31, hh = lane >> 5;
                 const int64_t n = g * 32 + i;
@@ -112,7 +127,9 @@ static void untile_weights(const Layer& L, const std::vector<uint8_t>& in, uint8
                             for (int e = 0; e < 8; ++e)
                                 dst[e] = (uint8_t)((codes[2 * e] & 0xF) | ((codes[2 * e + 1] & 0xF) << 4));
                         }
-                        if (We) We[n * nblk + kb] = rec[kWExpOffset + lane * 8 + 2 * c + j];
+                        if (We) We[n * nblk + kb] = L.w_exp_bias >= 0
+                                ? (uint8_t)(((rec[kWExpOffset + lane * 4 + c] >> (4 * j)) & 0xF) + L.w_exp_bias)
+                                : rec[kWExpOffset + lane * 8 + 2 * c + j];
                     }
             }
         }
@@ -381,6 +398,8 @@ int lqer_layer_import(int64_t K, int64_t N, int k, const uint8_t* Wc, const uint
     L.N32 = (N + 31) / 32;
     L.kp16 = kp / 16;
     L.act_bits = 8;
+    L.w_rec_bytes = kWRecordBytes;
+    L.w_exp_bias = -1;
     L.Wt = L.At = L.Bt = nullptr;
     if (hipGetDevice(&L.device) != hipSuccess) { delete h; return LQER_ERR_HIP; }
     int st;
@@ -416,7 +435,7 @@ int lqer_layer_export(const lqer_layer* layer, uint8_t* Wc, uint8_t* We, int8_t*
     std::vector<uint8_t> buf;
     int st;
     if (Wc || We) {
-        st = download(L.Wt, (size_t)(L.N32 * L.KT) * kWRecordBytes, buf);
+        st = download(L.Wt, (size_t)(L.N32 * L.KT) * L.w_rec_bytes, buf);
         if (st != LQER_OK) return st;
         untile_weights(L, buf, Wc, We);
     }

@@ -24,6 +24,10 @@ namespace lqer {
 //   exps[64 lanes][8 B]              byte 2c + j = exponent byte of block 4c + 2hh + j
 //   records are ordered [K tile][column group]: what the streaming kernel reads at one time is then one
 //   contiguous range (a few percent more HBM bandwidth than group-major order).
+//   Compact form (chosen at import when the layer's exponent bytes span at most 16 values, which real
+//   weight matrices do): exps[64 lanes][4 B], nibble 2c + j = exponent byte of block 4c + 2hh + j minus
+//   the layer's smallest exponent byte; 4352 B per record, 0.53125 B per weight - the footprint of
+//   the 4-bit shared exponents Sec. 4.1 gives the weights.  The canonical bytes are unchanged.
 //
 // A 32-bit code word holds 8 consecutive K elements e0..e7 as sign-magnitude nibbles placed so
 // that two mask operations yield fp8 (E4M3) subnormal bytes  s0000mmm = +-m * 2^-9:
@@ -43,8 +47,10 @@ namespace lqer {
 //      + exps[32 columns][1 B]; ordered [column group][rank block].
 
 constexpr int kTileK = 256;          // K covered by one W / A record
-constexpr int kWRecordBytes = 4608;
+constexpr int kWRecordBytes = 4608;  // with one exponent byte per block
+constexpr int kWRecordBytesCompact = 4352;   // with exponent nibbles (below)
 constexpr int kWExpOffset = 4096;
+constexpr int kWTailPad = 16;        // bytes behind the last record: exponent words are read 8 bytes wide in both forms
 constexpr int kARecordBytes = 8192;
 constexpr int kBRecordBytes = 544;
 constexpr int kMaxWExpByte = 247;    // (byte + 7) must stay a finite fp32 exponent field
@@ -56,6 +62,8 @@ struct Layer {
     int64_t N32;       // column groups of 32
     int kp16;          // rank groups (= MXINT blocks along k) of 16
     int device;
+    int w_rec_bytes;   // kWRecordBytes or kWRecordBytesCompact
+    int w_exp_bias;    // compact records: exponent byte = nibble + this; -1: one byte per block
     int act_bits;      // width of the activation codes: 8 or 6
     uint8_t* Wt;       // device, N32*KT records
     uint8_t* At;       // device, kp16*KT records

@@ -12,6 +12,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// an 8-byte load from a 4-byte aligned address (exponent words of the compact weight records)
+typedef u32x2 u32x2_a4 __attribute__((aligned(4)));
+
 union Frag {            // one bf16 MFMA operand (16x16x32 or 32x32x16): 8 bf16 per lane
     bf16x8 v;
     u32x4 u;
