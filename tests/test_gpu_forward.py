@@ -373,6 +373,40 @@ def test_split_tiles_in_hip_graph_and_on_two_streams():
     h.free()
 
 
+@pytest.mark.parametrize("M,K,N,k,path,variant", [(5, 1024, 272, 32, 1, 0), (16, 2304, 528, 33, 1, 12241), (40, 512, 16384, 8, 1, 0),
+                                                  (300, 1024, 528, 64, 2, 111), (300, 2304, 272, 33, 2, 212)])
+def test_both_forms_of_weight_exponents_on_the_device(M, K, N, k, path, variant):
+    # The device copy keeps W_q's exponents as nibbles when the layer spans at most 16 exponent values and as
+    # bytes otherwise; the same layer is run in both forms (one far-off exponent byte on a block of zero
+    # codes forces bytes without changing a single product) and must give the same bits, and export must
+    # return the canonical bytes either way.
+    import torch
+    from paper_2402_02446_amd import binding
+    if N > 2048:
+        layer = factors.PackedLayer(**synth.random_packed_layer(np.random.default_rng(N), K, N, k))
+        ch = synth.gen_outlier_channels(np.random.default_rng(1), K, 4)
+    else:
+        layer, ch = oracle_layer_small(K, N, k, seed=M + k)
+    assert int(layer.We.max()) - int(layer.We.min()) <= 15
+    wide = factors.PackedLayer(K=layer.K, N=layer.N, k=layer.k, kp=layer.kp, Wc=layer.Wc.copy(), We=layer.We.copy(),
+                               Ac=layer.Ac, Ae=layer.Ae, Bc=layer.Bc, Be=layer.Be)
+    wide.Wc[3, 8:16] = 0                                       # block 1 of column 3: all codes zero ...
+    wide.We[3, 1] = 40                                         # ... so its exponent byte is free
+    narrow = factors.PackedLayer(K=layer.K, N=layer.N, k=layer.k, kp=layer.kp, Wc=wide.Wc, We=layer.We,
+                                 Ac=layer.Ac, Ae=layer.Ae, Bc=layer.Bc, Be=layer.Be)
+    X = synth.gen_activations(np.random.default_rng(M), M, K, ch, 30.0)
+    Xd = torch.from_numpy(X).cuda()
+    outs = []
+    for lay in (narrow, wide):
+        h = upload(lay)
+        outs.append(binding.lqer_linear_forward_ex(h, Xd, path=path, variant=variant).clone())
+        ex = binding.lqer_layer_export(h)
+        assert np.array_equal(ex["Wc"], lay.Wc) and np.array_equal(ex["We"], lay.We)
+        h.free()
+    assert torch.equal(outs[0], outs[1])
+    _assert_close(outs[0].cpu().numpy(), forward.forward(X, narrow))
+
+
 def test_split_is_refused_for_shapes_without_it():
     from paper_2402_02446_amd import binding
     layer, ch = oracle_layer_small(1024, 272, 8, seed=2)
