@@ -101,7 +101,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     for (int g = 0; g < G; ++g) {
         int64_t grp = g0 + g;
         if (grp >= a.N32) grp = a.N32 - 1;
-        wrec[g] = a.Wt + grp * a.rec_bytes + lane * 16;
+        wrec[g] = a.Wt + grp * a.rec_bytes + lane * 16 + (a.exp_bias >= 0 ? kWCompactCodeOffset : 0);   // this lane's codes
     }
     // Exponent of block 2 c + j of the lane's eight, without a branch in the main loop (a branch there
     // makes the compiler's wait counts worst-case): word c / 2, shifted by (c % 2) * es1 + j * es0,
@@ -110,7 +110,8 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     const bool exp4 = a.exp_bias >= 0;               // wave-uniform
     const int es1 = exp4 ? 8 : 16, es0 = exp4 ? 4 : 8;
     const uint32_t emask = exp4 ? 0xFu : 0xFFu, ebias = exp4 ? (uint32_t)a.exp_bias : 0u;
-    const int e_adj = exp4 ? -(lane * 12) : -(lane * 8);    // exponent words sit at lane * 4 or lane * 8, not lane * 16
+    // from wrec to this lane's exponent word: nibbles in front of the codes at lane * 4, bytes behind them at lane * 8
+    const int e_adj = exp4 ? -(lane * 12) - kWCompactCodeOffset : kWExpOffset - (lane * 8);
     int trow[MB];
 #pragma unroll
     for (int b = 0; b < MB; ++b) {
@@ -194,7 +195,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     };
     auto load_we = [&](int g, int64_t tile) {
         // always 8 bytes wide: with nibbles only the first word is used (the buffer is padded behind the last record)
-        const u32x2_a4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x2_a4*>(wrec[g] + tile * tile_stride + kWExpOffset + e_adj));
+        const u32x2_a4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x2_a4*>(wrec[g] + tile * tile_stride + e_adj));
         return u32x2{w[0], exp4 ? w[0] >> 16 : w[1]};
     };
 

@@ -105,6 +105,8 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     const bool exp4 = a.exp_bias >= 0;                          // wave-uniform
     const int es1 = exp4 ? 8 : 16, es0 = exp4 ? 4 : 8;
     const uint32_t emask = exp4 ? 0xFu : 0xFFu, ebias = exp4 ? (uint32_t)a.exp_bias : 0u;
+    // nibbles sit in front of the codes (lane * 4), bytes behind them (lane * 8)
+    const int code_off = exp4 ? kWCompactCodeOffset : 0, exp_off = exp4 ? lane16 >> 2 : kWExpOffset + (lane16 >> 1);
 
     int64_t dp_next = lin;                                     // next whole tile of this workgroup
     int64_t u = a.sk_share * lin;                              // its range of the shared K tiles
@@ -180,7 +182,7 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
             const uint8_t* rec = a.Wt + (tile * a.N32 + group_of(tn)) * a.rec_bytes;   // wave-uniform
-            w.c[tn] = *reinterpret_cast<const u32x4*>(rec + cc * 1024 + lane16);
+            w.c[tn] = *reinterpret_cast<const u32x4*>(rec + code_off + cc * 1024 + lane16);
         }
     };
     auto load_eset = [&](ESet& x, int tile_i) {
@@ -189,7 +191,7 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
         for (int tn = 0; tn < TN; ++tn) {
             const uint8_t* rec = a.Wt + (tile * a.N32 + group_of(tn)) * a.rec_bytes;
             // always 8 bytes wide: with nibbles only the first word is used (the buffer is padded behind the last record)
-            const u32x2_a4 w = *reinterpret_cast<const u32x2_a4*>(rec + kWExpOffset + (exp4 ? lane16 >> 2 : lane16 >> 1));
+            const u32x2_a4 w = *reinterpret_cast<const u32x2_a4*>(rec + exp_off);
             x.e[tn] = u32x2{w[0], exp4 ? w[0] >> 16 : w[1]};
         }
     };

@@ -62,6 +62,7 @@ static int tile_weights(Layer& L, const uint8_t* Wc, const uint8_t* We, std::vec
     L.w_exp_bias = compact ? lo : -1;
     L.w_rec_bytes = compact ? kWRecordBytesCompact : kWRecordBytes;
     const int kRec = L.w_rec_bytes, bias = L.w_exp_bias;
+    const int code_off = compact ? kWCompactCodeOffset : 0;
     out.assign((size_t)(L.N32 * L.KT) * kRec + kWTailPad, 0);
     std::atomic<int> bad{0};
     parallel_for(L.N32, [&](int64_t g) {
@@ -86,11 +87,11 @@ static int tile_weights(Layer& L, const uint8_t* Wc, const uint8_t* We, std::vec
                             eb = We[n * nblk + kb];
                         }
                         const uint32_t w0 = encode_word(codes), w1 = encode_word(codes + 8);
-                        uint8_t* dst = rec + c * 1024 + lane * 16 + j * 8;
+                        uint8_t* dst = rec + code_off + c * 1024 + lane * 16 + j * 8;
                         memcpy(dst, &w0, 4);
                         memcpy(dst + 4, &w1, 4);
                         if (bias >= 0) {
-                            uint8_t& b2 = rec[kWExpOffset + lane * 4 + c];              // nibble 2c + j of the lane's word
+                            uint8_t& b2 = rec[lane * 4 + c];                            // nibble 2c + j of the lane's word
                             b2 = (uint8_t)(b2 | ((eb - bias) << (4 * j)));
                         } else {
                             rec[kWExpOffset + lane * 8 + 2 * c + j] = eb;
@@ -116,7 +117,7 @@ static void untile_weights(const Layer& L, const std::vector<uint8_t>& in, uint8
                         const int64_t kb = tile * 16 + 4 * c + 2 * hh + j;
                         if (kb >= nblk) continue;
                         uint32_t w0, w1;
-                        const uint8_t* src = rec + c * 1024 + lane * 16 + j * 8;
+                        const uint8_t* src = rec + (L.w_exp_bias >= 0 ? kWCompactCodeOffset : 0) + c * 1024 + lane * 16 + j * 8;
                         memcpy(&w0, src, 4);
                         memcpy(&w1, src + 4, 4);
                         int8_t codes[16];
@@ -128,7 +129,7 @@ static void untile_weights(const Layer& L, const std::vector<uint8_t>& in, uint8
                                 dst[e] = (uint8_t)((codes[2 * e] & 0xF) | ((codes[2 * e + 1] & 0xF) << 4));
                         }
                         if (We) We[n * nblk + kb] = L.w_exp_bias >= 0
-                                ? (uint8_t)(((rec[kWExpOffset + lane * 4 + c] >> (4 * j)) & 0xF) + L.w_exp_bias)
+                                ? (uint8_t)(((rec[lane * 4 + c] >> (4 * j)) & 0xF) + L.w_exp_bias)
                                 : rec[kWExpOffset + lane * 8 + 2 * c + j];
                     }
             }

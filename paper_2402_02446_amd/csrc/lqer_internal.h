@@ -25,8 +25,8 @@ namespace lqer {
 //   records are ordered [K tile][column group]: what the streaming kernel reads at one time is then one
 //   contiguous range (a few percent more HBM bandwidth than group-major order).
 //   Compact form (chosen at import when the layer's exponent bytes span at most 16 values, which real
-//   weight matrices do): exps[64 lanes][4 B], nibble 2c + j = exponent byte of block 4c + 2hh + j minus
-//   the layer's smallest exponent byte; 4352 B per record, 0.53125 B per weight - the footprint of
+//   weight matrices do): exps[64 lanes][4 B] in front of the codes, nibble 2c + j = exponent byte of block
+//   4c + 2hh + j minus the layer's smallest exponent byte; 4352 B per record, 0.53125 B per weight - the footprint of
 //   the 4-bit shared exponents Sec. 4.1 gives the weights.  The canonical bytes are unchanged.
 //
 // A 32-bit code word holds 8 consecutive K elements e0..e7 as sign-magnitude nibbles placed so
@@ -49,7 +49,8 @@ namespace lqer {
 constexpr int kTileK = 256;          // K covered by one W / A record
 constexpr int kWRecordBytes = 4608;  // with one exponent byte per block
 constexpr int kWRecordBytesCompact = 4352;   // with exponent nibbles (below)
-constexpr int kWExpOffset = 4096;
+constexpr int kWExpOffset = 4096;     // exponent bytes sit behind the codes; exponent nibbles (256 B) in front of them:
+constexpr int kWCompactCodeOffset = 256;   // their 8-byte reads then run over into a line the wavefront needs anyway
 constexpr int kWTailPad = 16;        // bytes behind the last record: exponent words are read 8 bytes wide in both forms
 constexpr int kARecordBytes = 8192;
 constexpr int kBRecordBytes = 544;
