@@ -77,6 +77,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
     // Workgroups behind the a.nslices K slices (grid.y) only clear Y for a main kernel that adds into it,
     // so the clearing runs beside the projection instead of in front of it.
     if ((int)blockIdx.y >= a.nslices) {
+        if (blockIdx.z != 0) return;                 // one plane of grid.z clears
         const int64_t n4 = (a.N + 3) / 4;
         const int64_t nthreads = (int64_t)gridDim.x * (gridDim.y - a.nslices) * blockDim.x;
         const int64_t me = ((int64_t)(blockIdx.y - a.nslices) * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
@@ -285,6 +286,11 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     a.tiles_per_slice = (int)((L.KT + ws.S - 1) / ws.S);
     a.kp = L.kp; a.kp16 = L.kp16;
     a.groups_per_wg = L.kp16;
+    // Few-token calls are bound by the latency of reading A_k (1 MB for K = 8192, kp = 64) with a handful of
+    // workgroups: there every rank group gets workgroups of its own (grid.z), each quantizing the few
+    // rows again; 1 us less on the 70B-shaped layer.
+    int gz = 1;
+    if (ws.cells && L.kp16 > 1) { gz = L.kp16; a.groups_per_wg = 1; }
     a.At = L.At; a.Xh = ws.Xh; a.ldxh = ws.ldxh;
     a.tail_cols = ws.ldxh - L.KT * kTileK;
     a.Tpart = ws.Tpart;
@@ -303,7 +309,7 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     // clearing workgroups: about four 16-byte stores per thread
     const int64_t rg = (M + 15) / 16;
     const int64_t zero_wgs = y_zero ? (M * ((L.N + 3) / 4) + 4 * block.x * rg - 1) / (4 * block.x * rg) : 0;
-    dim3 grid((unsigned)rg, (unsigned)(ws.S + zero_wgs), 1);
+    dim3 grid((unsigned)rg, (unsigned)(ws.S + zero_wgs), (unsigned)gz);
     const bool from_codes = (Xc != nullptr);
     const bool fin = (ws.Tpart == nullptr);          // T final (hi/lo behind the row) or partial sums
     if (cells && fin && L.kp > 0) return hipErrorInvalidValue;
