@@ -80,3 +80,16 @@ def test_forward_rejects_null_layer(L):
     assert L.lqer_linear_workspace_bytes(None, 4) == 0
     assert L.lqer_linear_path(None, 4) == 0
     assert L.lqer_layer_free(None) == 0
+
+
+def test_newer_entry_points_reject_bad_arguments_on_the_host(L):
+    out = C.c_void_p()
+    bfd = L.lqer_build_factors_device
+    assert bfd(None, 16, 16, None, 0, 0, 2, 0, None, None, C.byref(out)) == 1      # W missing
+    assert bfd(None, 20, 16, None, 0, 0, 2, 0, None, None, C.byref(out)) == 2      # K % 16
+    assert bfd(None, 16, 16, None, 0, 0, 2, 7, None, None, C.byref(out)) == 3      # mode
+    assert bfd(None, 16, 16, None, 0, 0, 2, 0, None, None, None) == 1
+    assert L.lqer_layer_set_activation_bits(None, 6) == 1
+    assert L.lqer_linear_forward_requant(None, None, 4, 16, None, 16, None, None, 0, None, None) == 1
+    assert L.lqer_linear_workspace_bytes_ex(None, 4, 2) == 0
+    assert L.lqer_quantize_mx(None, 4, 32, 32, 6, 8, None, None, None) == 1        # 6-bit codes are a supported width
