@@ -268,6 +268,34 @@ def run_crossover(rng, steps=10):
     return {"workload": "cfg4: 8192 x 28672, k = 64, whole step", "sweep": out, "first_M_at_1p5x_of_M1": ridge}
 
 
+def run_added_rows(rng):
+    """Whole-step times of the widened rows beside the plain forward pass, same layer and tokens: result
+    leaving as MXINT8 from the epilogue (lqer_linear_forward_requant) and MXINT6 activations (W4A6)."""
+    import torch
+    from paper_2402_02446_amd import binding, synth
+    out = []
+    for (name, K, N, k, M) in (("cfg3 up", 4096, 11008, 32, 2048), ("cfg4", 8192, 28672, 64, 16), ("cfg4", 8192, 28672, 64, 4096)):
+        d = synth.random_packed_layer(rng, K, N, k)
+        layer = binding.lqer_layer_import(K, N, k, d["Wc"], d["We"], d["Ac"], d["Ae"], d["Bc"], d["Be"])
+        X = torch.randn((M, K), device="cuda", dtype=torch.float32)
+        Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        f_plain = lambda i: binding.lqer_linear_forward_ex(layer, X, Y=Y)
+        f_rq = lambda i: binding.lqer_linear_forward_requant(layer, X)
+        f_plain(0); f_rq(0)
+        torch.cuda.synchronize()
+        rec = {"workload": name, "M": M, "K": K, "N": N, "k": k}
+        rec["ms_fp32_output"] = sorted(_graph_ms(f_plain, 6) for _ in range(3))[1]
+        rec["ms_mxint8_output"] = sorted(_graph_ms(f_rq, 6) for _ in range(3))[1]
+        layer.set_activation_bits(6)
+        f_plain(0)
+        torch.cuda.synchronize()
+        rec["ms_fp32_output_mxint6_activations"] = sorted(_graph_ms(f_plain, 6) for _ in range(3))[1]
+        out.append(rec)
+        layer.free()
+        del X, Y
+    return out
+
+
 def time_build_factors(rng):
     """Wall time of the offline step per layer shape of cfg5: lqer_build_factors (host fp64 + upload, from host
     arrays) and lqer_build_factors_device (device kernels + small host steps, from device tensors; second call,
@@ -431,6 +459,7 @@ def main():
     if args.cases == "full":
         extra["crossover"] = run_crossover(rng)
         extra["cfg5"] = run_cfg5(3, rng)
+        extra["added_rows"] = run_added_rows(rng)
         extra["build_factors_seconds_per_layer"] = time_build_factors(rng)
     kp = 32
     cpu = cpu_baseline(ctx, M, K, N, kp)
