@@ -519,7 +519,8 @@ static const TileShape kShapes[] = {
     {11, 128, 512, 1, 1372.0, 1372.0}, {12, 128, 256, 2, 1300.0, 1000.0}, {4, 128, 128, 2, 1058.0, 900.0},
 };
 constexpr double kPieceUs = 4.0;       // filling the pipeline and storing the tile, per piece
-constexpr double kHandOverUs = 30.0;   // measured cost of handing accumulators over, per workgroup sharing a compute unit
+constexpr double kSplitFixedUs = 30.0; // what a split launch was measured to take beyond this, per workgroup sharing a compute unit: the
+                                       // pieces' drain and refill, not the slots' way through memory (the time is the same without them)
 
 struct Split { int64_t grid, dp_tiles, sk_units, sk_share; };
 
@@ -555,7 +556,7 @@ static double time_split(const TileShape& sh, int64_t tiles, int64_t KT, int cus
     if (sp.sk_units == 0) return time_whole(sh, tiles, KT, cus);
     const double rounds = (double)(sp.dp_tiles / sp.grid);
     return (rounds * (double)KT + (double)sp.sk_share) * unit_us(sh, sh.share, cus) + (rounds + 2.0) * kPieceUs +
-           kHandOverUs * sh.share;
+           kSplitFixedUs * sh.share;
 }
 
 // the split has to promise a clear gain: its estimate is the rougher of the two
