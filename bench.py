@@ -232,10 +232,32 @@ def run_cfg5(steps, rng):
             total_fl += fl * len(names)
             layer.free()
             del X, Y
+        # q/k/v and gate/up consume the same activations: one quantization per group (lqer_linear_forward_shared)
+        shared, saved_ms = [], 0.0
+        for names, K, N in ((("q", "k", "v"), 4096, 4096), (("gate", "up"), 4096, 11008)):
+            group = []
+            for _ in names:
+                d = synth.random_packed_layer(rng, K, N, k)
+                group.append(binding.lqer_layer_import(K, N, k, d["Wc"], d["We"], d["Ac"], d["Ae"], d["Bc"], d["Be"]))
+            X = torch.randn((M, K), generator=g, device="cuda", dtype=torch.float32)
+            Ys = [torch.empty((M, N), dtype=torch.float32, device="cuda") for _ in names]
+            ws = torch.empty(binding.lqer_linear_shared_workspace_bytes(group, M), dtype=torch.uint8, device="cuda")
+            f_sh = lambda i: binding.lqer_linear_forward_shared(group, X, Ys=Ys, workspace=ws)
+            f_sep = lambda i: [binding.lqer_linear_forward(l, X, Y=y, workspace=ws) for l, y in zip(group, Ys)]
+            f_sh(0); f_sep(0)
+            torch.cuda.synchronize()
+            ms_sh, ms_sep = _event_ms(f_sh, steps), _event_ms(f_sep, steps)
+            shared.append({"linears": list(names), "ms_shared": ms_sh, "ms_separate": ms_sep})
+            saved_ms += ms_sep - ms_sh
+            for l in group:
+                l.free()
+            del X, Ys, ws
         out.append({"workload": "cfg5: LLaMA-7B decoder block, 7 LQER linears, M=%d" % M, "k": k,
                     "ms_per_block": total_ms, "tflops": total_fl / (total_ms * 1e-3) / 1e12,
                     "frac_of_mfma_peak": total_fl / (total_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                    "per_shape": per_shape})
+                    "per_shape": per_shape, "shared_activations": shared,
+                    "ms_per_block_shared": total_ms - saved_ms,
+                    "tflops_shared": total_fl / ((total_ms - saved_ms) * 1e-3) / 1e12})
     return out
 
 

@@ -204,6 +204,23 @@ int lqer_linear_forward_requant(const lqer_layer* layer, const float* X_dev, int
                                 void* workspace_dev, size_t workspace_bytes, void* hip_stream,
                                 const lqer_launch_opts* opts);
 
+/*
+ * Several layers applied to the same activations (q/k/v, or gate/up, of a decoder block): in the
+ * weight-activation flow of Table 1 the activations are quantized once (Sec. 4.1) and every
+ * layer that consumes them sees the same X_q.  Here X is quantized by the first layer's
+ * projection step; for the others only T = X_q A_k (Eq. 3) is computed, from the X_q already in the
+ * workspace.  Each Y_dev[i] holds the same bits as lqer_linear_forward(layers[i], ...) gives.
+ *   layers   n_layers handles with the same K and the same activation width (LQER_ERR_SHAPE otherwise)
+ *   Y_dev    n_layers device pointers, Y_dev[i] fp32 [M][ldy[i]], ldy[i] >= N of layer i
+ *   workspace_dev  at least lqer_linear_shared_workspace_bytes(layers, n_layers, M) bytes
+ * For token counts that take the streaming kernel the call is n_layers full forward passes.
+ * Same contract as lqer_linear_forward otherwise.
+ */
+size_t lqer_linear_shared_workspace_bytes(const lqer_layer* const* layers, int n_layers, int64_t M);
+int lqer_linear_forward_shared(const lqer_layer* const* layers, int n_layers, const float* X_dev,
+                               int64_t M, int64_t ldx, float* const* Y_dev, const int64_t* ldy,
+                               void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
 /* Which path the dispatcher picks for this layer at M tokens: 1 = streaming, 2 = tiled MFMA. */
 int lqer_linear_path(const lqer_layer* layer, int64_t M);
 

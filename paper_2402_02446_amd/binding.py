@@ -23,7 +23,8 @@ STATUS_NAMES = {0: "LQER_OK", 1: "LQER_ERR_NULL", 2: "LQER_ERR_SHAPE", 3: "LQER_
 EXPORTS = ("lqer_status_string", "lqer_quantize_mx", "lqer_build_factors", "lqer_build_factors_device",
            "lqer_layer_import",
            "lqer_layer_export", "lqer_layer_dims", "lqer_layer_set_activation_bits", "lqer_layer_free", "lqer_linear_workspace_bytes", "lqer_linear_workspace_bytes_ex",
-           "lqer_linear_forward", "lqer_linear_forward_q", "lqer_linear_forward_ex", "lqer_linear_forward_requant", "lqer_linear_path")
+           "lqer_linear_forward", "lqer_linear_forward_q", "lqer_linear_forward_ex", "lqer_linear_forward_requant", "lqer_linear_path",
+           "lqer_linear_shared_workspace_bytes", "lqer_linear_forward_shared")
 
 
 class LqerError(RuntimeError):
@@ -86,6 +87,10 @@ def lib() -> C.CDLL:
     L.lqer_linear_forward_ex.argtypes = [vp, vp, i64, i64, vp, i64, vp, sz, vp, C.POINTER(LaunchOpts)]
     L.lqer_linear_forward_requant.restype = i32
     L.lqer_linear_forward_requant.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, sz, vp, vp]
+    L.lqer_linear_shared_workspace_bytes.restype = sz
+    L.lqer_linear_shared_workspace_bytes.argtypes = [C.POINTER(vp), i32, i64]
+    L.lqer_linear_forward_shared.restype = i32
+    L.lqer_linear_forward_shared.argtypes = [C.POINTER(vp), i32, vp, i64, i64, C.POINTER(vp), C.POINTER(i64), vp, sz, vp]
     L.lqer_linear_path.restype = i32
     L.lqer_linear_path.argtypes = [vp, i64]
     _lib = L
@@ -284,3 +289,28 @@ def lqer_linear_forward_requant(layer: Layer, X, workspace=None, path=0, variant
                                              C.c_void_p(ws.data_ptr()), ws.numel(), _stream(), C.byref(opts)),
            "lqer_linear_forward_requant")
     return codes, exps
+
+
+def lqer_linear_shared_workspace_bytes(layers, M: int) -> int:
+    arr = (C.c_void_p * len(layers))(*[l.handle for l in layers])
+    return int(lib().lqer_linear_shared_workspace_bytes(arr, len(layers), M))
+
+
+def lqer_linear_forward_shared(layers, X, Ys=None, workspace=None):
+    """Several layers applied to the same X (quantized once): returns the list of their Y."""
+    import torch
+    M = X.shape[0]
+    n = len(layers)
+    if Ys is None:
+        Ys = [torch.empty((M, l.N), dtype=torch.float32, device=X.device) for l in layers]
+    arr = (C.c_void_p * n)(*[l.handle for l in layers])
+    if workspace is None:
+        need = lib().lqer_linear_shared_workspace_bytes(arr, n, M)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    ldx = X.stride(0) if M > 1 else max(layers[0].K, X.stride(0))
+    yarr = (C.c_void_p * n)(*[C.c_void_p(y.data_ptr()) for y in Ys])
+    ldys = (C.c_int64 * n)(*[(y.stride(0) if M > 1 else max(l.N, y.stride(0))) for y, l in zip(Ys, layers)])
+    _check(lib().lqer_linear_forward_shared(arr, n, C.c_void_p(X.data_ptr()), M, ldx, yarr, ldys,
+                                            C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream()),
+           "lqer_linear_forward_shared")
+    return Ys

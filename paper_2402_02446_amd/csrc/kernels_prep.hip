@@ -52,7 +52,10 @@ constexpr int kPrepWaves = 8;
 
 // CELLS: the activations are stored for the streaming kernel, as 16-byte cells (8 consecutive K
 // elements) ordered [K / 8][token row]; otherwise row-major for the tiled kernel.
-template <bool FROM_CODES, bool FINAL, int MAXG, bool CELLS>
+// SRC: where the activations come from: 0 = fp32 X (quantized here), 1 = MXINT codes and exponent bytes,
+// 2 = the bf16 matrix an earlier launch on the same X left in the workspace (nothing is stored again: only T
+// is computed, for another layer applied to the same activations).
+template <int SRC, bool FINAL, int MAXG, bool CELLS>
 __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
     __shared__ float red[kPrepWaves][MAXG][64][4];
 
@@ -64,7 +67,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
     const bool row_ok = row < a.M;
     const int slice = blockIdx.y;
     const int g0 = blockIdx.z * a.groups_per_wg;
-    const bool store_x = (blockIdx.z == 0);
+    const bool store_x = (blockIdx.z == 0) && SRC != 2;
     const int64_t nblk = a.K / 16;
 
     f32x4 acc[MAXG];
@@ -123,7 +126,12 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
             float r[16];
             u32x4 cw = u32x4{0, 0, 0, 0};                     // the block's 16 codes as bytes (FROM_CODES, or CELLS of 16+ rows)
             uint32_t eb = 0;
-            if (FROM_CODES) {
+            if constexpr (SRC == 2) {
+                static_assert(SRC != 2 || !CELLS, "the stored matrix is read back in its row-major form only");
+                const uint16_t* src = a.Xh + row * a.ldxh + kb * 16;
+                xf[p][0].u = ok ? *reinterpret_cast<const u32x4*>(src) : u32x4{0, 0, 0, 0};
+                xf[p][1].u = ok ? *reinterpret_cast<const u32x4*>(src + 8) : u32x4{0, 0, 0, 0};
+            } else if constexpr (SRC == 1) {
                 if (ok) {
                     cw = *reinterpret_cast<const u32x4*>(a.Xc + row * a.K + kb * 16);
                     eb = a.Xe[row * nblk + kb];
@@ -166,11 +174,13 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
                                 (((uint32_t)(int)r[4 * i + 2] & 0xFFu) << 16) | ((uint32_t)(int)r[4 * i + 3] << 24);
                 }
             }
+            if constexpr (SRC != 2) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+                for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    xf[p][h].u[i] = pack_bf16_exact(r[8 * h + 2 * i] * scale, r[8 * h + 2 * i + 1] * scale);
+                    for (int i = 0; i < 4; ++i)
+                        xf[p][h].u[i] = pack_bf16_exact(r[8 * h + 2 * i] * scale, r[8 * h + 2 * i + 1] * scale);
+            }
             if (store_x && row_ok) {
                 if (CELLS) {
                     const int64_t blk = tile * 16 + q + 4 * p;
@@ -278,8 +288,9 @@ int prep_slices(const Layer& L, int64_t M, int path) {
 }
 
 hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t* Xc, const uint8_t* Xe,
-                       int64_t M, const Workspace& ws, float* y_zero, int64_t ldy, hipStream_t s) {
+                       int64_t M, const Workspace& ws, float* y_zero, int64_t ldy, hipStream_t s, bool reuse_xh) {
     if (M == 0) return hipSuccess;
+    if (reuse_xh && (ws.cells || X != nullptr || Xc != nullptr)) return hipErrorInvalidValue;
     PrepArgs a;
     a.X = X; a.ldx = ldx; a.Xc = Xc; a.Xe = Xe;
     a.M = M; a.K = L.K; a.KT = L.KT;
@@ -310,14 +321,15 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     const int64_t rg = (M + 15) / 16;
     const int64_t zero_wgs = y_zero ? (M * ((L.N + 3) / 4) + 4 * block.x * rg - 1) / (4 * block.x * rg) : 0;
     dim3 grid((unsigned)rg, (unsigned)(ws.S + zero_wgs), (unsigned)gz);
-    const bool from_codes = (Xc != nullptr);
+    const int src = reuse_xh ? 2 : (Xc != nullptr ? 1 : 0);
     const bool fin = (ws.Tpart == nullptr);          // T final (hi/lo behind the row) or partial sums
     if (cells && fin && L.kp > 0) return hipErrorInvalidValue;
     if (a.groups_per_wg > 4) return hipErrorInvalidValue;      // kp > 64 is rejected at import
 #define LQER_PREP(FC, FN, MG, CL) hipLaunchKernelGGL((prep_kernel<FC, FN, MG, CL>), grid, block, 0, s, a)
 #define LQER_PREP_G(FC, FN, CL) do { if (a.groups_per_wg <= 1) LQER_PREP(FC, FN, 1, CL); else LQER_PREP(FC, FN, 4, CL); } while (0)
-#define LQER_PREP_C(FN, CL) do { if (from_codes) LQER_PREP_G(true, FN, CL); else LQER_PREP_G(false, FN, CL); } while (0)
+#define LQER_PREP_C(FN, CL) do { if (src == 1) LQER_PREP_G(1, FN, CL); else LQER_PREP_G(0, FN, CL); } while (0)
     if (cells) LQER_PREP_C(false, true);
+    else if (src == 2) { if (fin) LQER_PREP_G(2, true, false); else LQER_PREP_G(2, false, false); }
     else if (fin) LQER_PREP_C(true, false);
     else LQER_PREP_C(false, false);
 #undef LQER_PREP_C

@@ -347,6 +347,30 @@ static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, co
     return LQER_OK;
 }
 
+// One workspace plan that serves every layer of a group applied to the same activations on the tiled path:
+// the plan of a layer with the group's K and its widest padded rank.
+static Layer shared_plan_layer(const lqer_layer* const* layers, int n) {
+    Layer Lp = layers[0]->L;
+    for (int i = 1; i < n; ++i)
+        if (layers[i]->L.kp > Lp.kp) { Lp.kp = layers[i]->L.kp; Lp.kp16 = layers[i]->L.kp16; }
+    return Lp;
+}
+
+static bool shared_group_ok(const lqer_layer* const* layers, int n) {
+    if (!layers || n < 1) return false;
+    for (int i = 0; i < n; ++i) {
+        if (!layers[i]) return false;
+        if (layers[i]->L.K != layers[0]->L.K || layers[i]->L.act_bits != layers[0]->L.act_bits) return false;
+    }
+    return true;
+}
+
+static bool shared_group_tiled(const lqer_layer* const* layers, int n, int64_t M) {
+    for (int i = 0; i < n; ++i)
+        if (pick_path(layers[i]->L, M) != 2) return false;
+    return true;
+}
+
 }  // namespace lqer
 
 using namespace lqer;
@@ -494,6 +518,61 @@ int lqer_linear_forward_requant(const lqer_layer* layer, const float* X_dev, int
     if (!Yc_dev) return LQER_ERR_NULL;
     return forward_impl(layer, X_dev, ldx, nullptr, nullptr, M, nullptr, 0, workspace_dev, workspace_bytes,
                         hip_stream, opts, Requant{Yc_dev, Ye_dev, ldyc});
+}
+
+size_t lqer_linear_shared_workspace_bytes(const lqer_layer* const* layers, int n_layers, int64_t M) {
+    if (!shared_group_ok(layers, n_layers) || M <= 0) return 0;
+    size_t need = 0;
+    for (int i = 0; i < n_layers; ++i) {
+        const size_t b = plan_workspace(layers[i]->L, M, pick_path(layers[i]->L, M), nullptr).bytes;
+        if (b > need) need = b;
+    }
+    if (shared_group_tiled(layers, n_layers, M)) {
+        const size_t b = plan_workspace(shared_plan_layer(layers, n_layers), M, 2, nullptr).bytes;
+        if (b > need) need = b;
+    }
+    return need;
+}
+
+int lqer_linear_forward_shared(const lqer_layer* const* layers, int n_layers, const float* X_dev, int64_t M,
+                               int64_t ldx, float* const* Y_dev, const int64_t* ldy, void* workspace_dev,
+                               size_t workspace_bytes, void* hip_stream) {
+    if (!layers || !Y_dev || !ldy || n_layers < 1) return LQER_ERR_NULL;
+    for (int i = 0; i < n_layers; ++i)
+        if (!layers[i] || !Y_dev[i]) return LQER_ERR_NULL;
+    if (!shared_group_ok(layers, n_layers)) return LQER_ERR_SHAPE;
+    if (M < 0) return LQER_ERR_SHAPE;
+    if (M == 0) return LQER_OK;
+    if (!X_dev) return LQER_ERR_NULL;
+    const int64_t K = layers[0]->L.K;
+    if (ldx < K || (ldx & 3) != 0 || ((uintptr_t)X_dev & 15) != 0) return LQER_ERR_SHAPE;
+    for (int i = 0; i < n_layers; ++i)
+        if (ldy[i] < layers[i]->L.N || (ldy[i] & 3) != 0 || ((uintptr_t)Y_dev[i] & 15) != 0) return LQER_ERR_SHAPE;
+    if (!workspace_dev || ((uintptr_t)workspace_dev & 255) != 0) return LQER_ERR_WORKSPACE;
+    if (workspace_bytes < lqer_linear_shared_workspace_bytes(layers, n_layers, M)) return LQER_ERR_WORKSPACE;
+    if (!shared_group_tiled(layers, n_layers, M)) {
+        // few tokens: the streaming path keeps its per-layer activation layouts; one full call per layer
+        for (int i = 0; i < n_layers; ++i) {
+            const int st = forward_impl(layers[i], X_dev, ldx, nullptr, nullptr, M, Y_dev[i], ldy[i], workspace_dev,
+                                        workspace_bytes, hip_stream, nullptr);
+            if (st != LQER_OK) return st;
+        }
+        return LQER_OK;
+    }
+    const Workspace ws = plan_workspace(shared_plan_layer(layers, n_layers), M, 2, workspace_dev);
+    hipStream_t s = (hipStream_t)hip_stream;
+    for (int i = 0; i < n_layers; ++i) {
+        const Layer& L = layers[i]->L;
+        hipError_t e;
+        if (i == 0) e = launch_prep(L, X_dev, ldx, nullptr, nullptr, M, ws, nullptr, 0, s);
+        else if (L.kp > 0) e = launch_prep(L, nullptr, 0, nullptr, nullptr, M, ws, nullptr, 0, s, true);
+        else e = launch_clear_flags(ws, s);          // nothing to project; the main kernel still wants its flags cleared
+        if (e != hipSuccess) return LQER_ERR_HIP;
+        e = launch_tiled(L, M, ws, Y_dev[i], ldy[i], Requant{nullptr, nullptr, 0}, 0, s);
+        if (e == hipErrorInvalidValue) return LQER_ERR_SHAPE;
+        if (e != hipSuccess) return LQER_ERR_HIP;
+    }
+    return LQER_OK;
 }
 
 int lqer_linear_path(const lqer_layer* layer, int64_t M) {

@@ -100,8 +100,10 @@ hipError_t launch_quantize_mx(const float* x, int64_t rows, int64_t cols, int64_
 // S > 1 writes fp32 partial sums per K slice.
 // y_zero != null: also clears Y[M][N] (row stride ldy) for a main kernel that adds into it.
 // Clears ws.flags when the workspace has them.
+// reuse_xh (tiled path, X and Xc null): Xh already holds these activations from an earlier launch with the same
+// workspace plan; only T is computed, for another layer applied to them.
 hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t* Xc, const uint8_t* Xe,
-                       int64_t M, const Workspace& ws, float* y_zero, int64_t ldy, hipStream_t s);
+                       int64_t M, const Workspace& ws, float* y_zero, int64_t ldy, hipStream_t s, bool reuse_xh = false);
 
 // Output of the main kernels as MXINT8 (blocks of 16 along N) instead of fp32 Y; codes == null: fp32.
 struct Requant {

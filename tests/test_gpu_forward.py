@@ -330,6 +330,45 @@ def test_output_as_mxint8_automatic_shape_and_errors():
     h.free()
 
 
+def test_layers_sharing_their_activations():
+    # q/k/v or gate/up of a block see the same X_q (Sec. 4.1: one quantizer per activation tensor; Eq. 3 per layer):
+    # the shared call quantizes X once and must give every layer the bits its own forward pass gives, and the
+    # oracle's Y within the bound.  Ranks differ between the layers (one has none), token counts cover the tiled
+    # kernel with and without split tiles and the streaming kernel (where the call is one pass per layer).
+    import torch
+    from paper_2402_02446_amd import binding
+    K = 2304
+    specs = [(528, 33, 21), (1000, 8, 22), (272, 0, 23), (4128, 64, 24)]
+    layers, hs = [], []
+    ch = None
+    for (N, k, seed) in specs:
+        layer, ch = (oracle_layer_small if N < 2000 else oracle_layer_big)(K, N, k, seed=seed)
+        layers.append(layer)
+        hs.append(upload(layer))
+    for M in (300, 130, 70, 16):
+        X = synth.gen_activations(np.random.default_rng(M), M, K, ch, 30.0)
+        Xd = torch.from_numpy(X).cuda()
+        alone = [binding.lqer_linear_forward(h, Xd).clone() for h in hs]
+        torch.cuda.synchronize()
+        for order in ([0, 1, 2, 3], [2, 3, 0], [3]):
+            group = [hs[i] for i in order]
+            Ys = [torch.full((M, layers[i].N), float("nan"), dtype=torch.float32, device="cuda") for i in order]
+            binding.lqer_linear_forward_shared(group, Xd, Ys=Ys)
+            torch.cuda.synchronize()
+            for i, Y in zip(order, Ys):
+                assert torch.equal(Y, alone[i]), (M, order, i)
+        for i in (0, 3):
+            assert forward.rel_frobenius(alone[i].cpu().numpy(), forward.forward(X, layers[i])) < Y_TOL
+    # layers of different K cannot share activations
+    other, _ = oracle_layer_small(512, 64, 8, seed=1)
+    ho = upload(other)
+    with pytest.raises(binding.LqerError):
+        binding.lqer_linear_forward_shared([hs[0], ho], torch.zeros((4, K), device="cuda"))
+    ho.free()
+    for h in hs:
+        h.free()
+
+
 def test_split_tiles_in_hip_graph_and_on_two_streams():
     # The flags of the hand-over are cleared by the projection kernel of every call, so replays of a captured
     # forward pass and two calls in flight on two streams (distinct workspaces) all reproduce the eager result.
