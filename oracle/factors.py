@@ -62,10 +62,10 @@ def calibrate_scale(calib) -> np.ndarray:
     return abar / np.sqrt(abar.min() * abar.max())
 
 
-def quantize_weight(W):
+def quantize_weight(W, exp_bits: int = 8):
     """W_q = q(W): returns (codes[K][N] int8, exps[K/16][N] uint8, dequantized fp64)."""
     W = np.asarray(W, dtype=np.float64)
-    codes, exps = mxint.mx_quantize(W, W_BITS, axis=0)
+    codes, exps = mxint.mx_quantize(W, W_BITS, axis=0, exp_bits=exp_bits)
     return codes, exps, mxint.mx_dequantize(codes, exps, W_BITS, axis=0)
 
 
@@ -83,7 +83,7 @@ def error_factors(E, s, k: int):
     return A, B, sig
 
 
-def pack_layer(w_codes, w_exps, A, B, k: int) -> PackedLayer:
+def pack_layer(w_codes, w_exps, A, B, k: int, exp_bits: int = 8) -> PackedLayer:
     """Quantize A, B to MXINT8 and lay every tensor out canonically."""
     K, N = w_codes.shape
     kp = padded_rank(k)
@@ -91,8 +91,8 @@ def pack_layer(w_codes, w_exps, A, B, k: int) -> PackedLayer:
     Bp = np.zeros((kp, N), dtype=np.float64)
     Ap[:, :k] = A
     Bp[:k, :] = B
-    a_codes, a_exps = mxint.mx_quantize(Ap, H_BITS, axis=0)      # blocks down K
-    b_codes, b_exps = mxint.mx_quantize(Bp, H_BITS, axis=0)      # blocks down k
+    a_codes, a_exps = mxint.mx_quantize(Ap, H_BITS, axis=0, exp_bits=exp_bits)      # blocks down K
+    b_codes, b_exps = mxint.mx_quantize(Bp, H_BITS, axis=0, exp_bits=exp_bits)      # blocks down k
     return PackedLayer(
         K=K, N=N, k=k, kp=kp,
         Wc=mxint.pack_int4(np.ascontiguousarray(w_codes.T)),
@@ -104,20 +104,21 @@ def pack_layer(w_codes, w_exps, A, B, k: int) -> PackedLayer:
     )
 
 
-def build_factors(W, calib, k: int, mode: int = 1) -> PackedLayer:
-    """The whole offline step.  mode 0 = LQER (S = I), mode 1 = L2QER."""
+def build_factors(W, calib, k: int, mode: int = 1, exp_bits: int = 8) -> PackedLayer:
+    """The whole offline step.  mode 0 = LQER (S = I), mode 1 = L2QER.
+    exp_bits: width of the shared exponents of W_q, A_k and B_k (Sec. 4.1 uses 4)."""
     W = np.asarray(W, dtype=np.float64)
     K, N = W.shape
     if not 0 <= k <= min(K, N):
         raise ValueError("rank k must lie in [0, min(K, N)]")
-    w_codes, w_exps, W_hat = quantize_weight(W)
+    w_codes, w_exps, W_hat = quantize_weight(W, exp_bits)
     E = W - W_hat
     s = calibrate_scale(calib) if mode == 1 else np.ones(K)
     if k > 0:
         A, B, _ = error_factors(E, s, k)
     else:
         A, B = np.zeros((K, 0)), np.zeros((0, N))
-    return pack_layer(w_codes, w_exps, A, B, k)
+    return pack_layer(w_codes, w_exps, A, B, k, exp_bits)
 
 
 def dequantize_layer(layer: PackedLayer):

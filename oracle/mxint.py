@@ -17,6 +17,17 @@ so the reading taken here is:
 
 Rounding that reaches 2^(b-1) saturates; the exponent is never bumped.
 All arithmetic is fp64; every step above is exact in fp64 for fp32 inputs.
+
+Sec. 4.1 gives W_q, A_k and B_k 4-bit shared exponents (activations keep 8 bits)
+and states no bias for them.  Reading taken for exp_bits = 4: one bias per tensor,
+chosen so that the tensor's largest block keeps its own exponent,
+
+  top   = max over the tensor's blocks of e
+  floor = max(top - 15, -127)
+  e'    = max(e, floor)                              stored as the nibble e' - floor
+
+and a block below the floor is quantized with e' (its codes shrink towards zero:
+the narrow exponent cannot reach it).  Everything else is as above with e' for e.
 """
 from __future__ import annotations
 
@@ -50,18 +61,24 @@ def block_exponent(amax: np.ndarray) -> np.ndarray:
     return np.clip(e, E_MIN, E_MAX).astype(np.int64)
 
 
-def mx_quantize(v, bits: int, axis: int = -1):
+def mx_quantize(v, bits: int, axis: int = -1, exp_bits: int = 8):
     """Quantize `v` to MXINT with `bits`-bit mantissas in blocks of 16 along `axis`.
 
     Returns (codes, exps): codes is int8 with the shape of `v`; exps is uint8
-    (biased by 127) with `axis` shrunk by 16.
+    (biased by 127) with `axis` shrunk by 16.  With exp_bits = 4 the bytes of one
+    call span at most 16 consecutive values (see the head of this file);
+    exp4_bias() and pack_exp4() turn them into the stored nibbles.
     """
     v = np.asarray(v, dtype=np.float64)
     if not np.all(np.isfinite(v)):
         raise ValueError("MXINT quantizer requires finite inputs")
+    if exp_bits not in (4, 8):
+        raise ValueError("shared exponents are 4 or 8 bits wide")
     blk = _to_blocks(v, axis)
     amax = np.max(np.abs(blk), axis=-1)
     e = block_exponent(amax)
+    if exp_bits == 4 and e.size:
+        e = np.maximum(e, max(int(e.max()) - 15, E_MIN))
     shift = e - (bits - 2)                                   # log2(scale)
     q = np.rint(np.ldexp(blk, (-shift)[..., None]))          # v / scale, exact, then RNE
     lim = code_limit(bits)
@@ -109,6 +126,36 @@ def unpack_int4(packed: np.ndarray) -> np.ndarray:
     out[..., 1::2] = hi
     out = np.where(out >= 8, out - 16, out)
     return out.astype(np.int8)
+
+
+def exp4_bias(exps) -> int:
+    """The byte a zero nibble stands for in a tensor whose exponent bytes span at
+    most 16 values: its largest byte minus 15 (not below 0)."""
+    e = np.asarray(exps)
+    top = int(e.max()) if e.size else 0
+    if e.size and top - int(e.min()) > 15:
+        raise ValueError("exponent bytes span more than 16 values")
+    return max(top - 15, 0)
+
+
+def pack_exp4(exps):
+    """[..., n] exponent bytes of one tensor -> ([..., n/2] uint8, bias): block 2i
+    in the low nibble, block 2i+1 in the high nibble, each byte minus the bias."""
+    e = np.asarray(exps).astype(np.int16)
+    if e.shape[-1] % 2:
+        raise ValueError("need an even number of exponents")
+    bias = exp4_bias(e)
+    n = e - bias
+    return (n[..., 0::2] | (n[..., 1::2] << 4)).astype(np.uint8), bias
+
+
+def unpack_exp4(packed, bias: int) -> np.ndarray:
+    """Inverse of pack_exp4."""
+    p = np.asarray(packed).astype(np.int16)
+    out = np.empty(p.shape[:-1] + (p.shape[-1] * 2,), dtype=np.int16)
+    out[..., 0::2] = p & 0xF
+    out[..., 1::2] = (p >> 4) & 0xF
+    return (out + bias).astype(np.uint8)
 
 
 def average_bits(mant_bits: int, exp_bits: int, block: int = BLOCK) -> float:

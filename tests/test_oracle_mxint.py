@@ -177,3 +177,77 @@ def test_average_bits_closed_forms():
     assert any(round(g, 1) == target for g in got)
     assert all(abs(g - target) < 0.1 for g in got)
     assert all(g > 4.25 for g in got)
+
+
+# ---- 4-bit shared exponents (Sec. 4.1: W_q, A_k, B_k), per-tensor bias ------------------------------
+
+def _wide_range_tensor(rng, rows):
+    """Blocks whose maxima spread over far more than 16 binades, plus an all-zero block."""
+    v = (rng.standard_normal((rows, 16)) * np.exp2(rng.integers(-30, 3, (rows, 1)))).astype(np.float32)
+    v[rows // 2] = 0.0
+    return v
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_exp4_bytes_span_sixteen_values_and_keep_the_largest_block(bits):
+    rng = np.random.default_rng(21)
+    v = _wide_range_tensor(rng, 400)
+    c8, x8 = mxint.mx_quantize(v, bits)
+    c4, x4 = mxint.mx_quantize(v, bits, exp_bits=4)
+    top = int(x8.max())
+    assert int(x4.max()) == top and int(x4.min()) == top - 15          # the spread of this tensor reaches the floor
+    # blocks the narrow exponent can reach are those of the 8-bit-exponent quantizer, bit for bit
+    reach = x8[:, 0] >= top - 15
+    assert reach.any() and (~reach).any()
+    assert np.array_equal(c4[reach], c8[reach]) and np.array_equal(x4[reach], x8[reach])
+    assert np.all(x4[~reach] == top - 15)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_exp4_blocks_below_the_floor_by_exact_rationals(bits):
+    rng = np.random.default_rng(22)
+    v = _wide_range_tensor(rng, 60)
+    c4, x4 = mxint.mx_quantize(v, bits, exp_bits=4)
+    floor = int(mxint.mx_quantize(v, bits)[1].max()) - 15 - 127
+    lim = 2 ** (bits - 1) - 1
+    for i in range(v.shape[0]):
+        _, nat = _brute_block(v[i], bits)
+        e = max(nat - 127, floor)
+        assert int(x4[i, 0]) == e + 127
+        scale = Fraction(2) ** (e - (bits - 2))
+        for j in range(16):
+            x = Fraction(float(v[i, j])) / scale
+            fl = x.numerator // x.denominator
+            rem = x - fl
+            c = fl + 1 if rem > Fraction(1, 2) else fl if rem < Fraction(1, 2) else (fl if fl % 2 == 0 else fl + 1)
+            assert int(c4[i, j]) == max(-lim, min(lim, c)), (i, j)
+
+
+def test_exp4_equals_exp8_on_a_narrow_tensor_and_is_idempotent():
+    rng = np.random.default_rng(23)
+    v = (rng.standard_normal((300, 16)) * 0.02).astype(np.float32)      # weights: a few binades
+    for bits in (4, 8):
+        a = mxint.mx_quantize(v, bits)
+        b = mxint.mx_quantize(v, bits, exp_bits=4)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    w = _wide_range_tensor(rng, 300)
+    c, x = mxint.mx_quantize(w, 8, exp_bits=4)
+    c2, x2 = mxint.mx_quantize(mxint.mx_dequantize(c, x, 8), 8, exp_bits=4)
+    assert np.array_equal(c, c2) and np.array_equal(x, x2)
+    # error bound with the exponent actually used
+    err = np.abs(w.astype(np.float64) - mxint.mx_dequantize(c, x, 8))
+    assert np.all(err <= np.ldexp(1.0, x.astype(np.int64) - 127 - 6))
+
+
+def test_exp4_packing_round_trip_and_layout():
+    x = np.array([[130, 121, 125, 136], [122, 122, 130, 131]], dtype=np.uint8)
+    packed, bias = mxint.pack_exp4(x)
+    assert bias == 121
+    assert packed.tolist() == [[(130 - 121) | ((121 - 121) << 4), (125 - 121) | ((136 - 121) << 4)],
+                               [(122 - 121) | ((122 - 121) << 4), (130 - 121) | ((131 - 121) << 4)]]
+    assert np.array_equal(mxint.unpack_exp4(packed, bias), x)
+    with pytest.raises(ValueError):
+        mxint.pack_exp4(np.array([[100, 120]], dtype=np.uint8))
+    assert mxint.exp4_bias(np.array([3, 9], dtype=np.uint8)) == 0       # small bytes: the bias stops at zero
+    # App. D: 4-bit mantissas with a 4-bit exponent per 16 cost 4.25 bits
+    assert mxint.average_bits(4, 4) == 4.25
