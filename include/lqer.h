@@ -52,11 +52,20 @@ typedef enum {
     LQER_ERR_VALUE = 8            /* packed bytes hold a value the format excludes (nibble -8, exponent byte out of range) */
 } lqer_status;
 
-/* Number-format description for lqer_build_factors.  Only {4, 8, 8, 16} is supported. */
+/*
+ * Number-format description for lqer_build_factors: {4, 8, 8, 16} or {4, 8, 4, 16}.
+ * exp_bits is the width of the shared exponents of W_q, A_k and B_k (Sec. 4.1 gives them 4 bits;
+ * activations always keep 8).  The paper states no bias for the 4-bit field; here each of the
+ * three tensors has one bias of its own, chosen so that its largest block keeps its exponent:
+ * with top = the largest block exponent of the tensor, a block is quantized with
+ * max(own exponent, top - 15), i.e. blocks more than 15 binades below the largest lose their low
+ * bits.  The layer still carries one exponent byte per block (lqer_layer_export); within one tensor
+ * the bytes then span at most 16 consecutive values, so byte - (largest byte - 15) fits a nibble.
+ */
 typedef struct {
     int w_bits;     /* mantissa bits of W_q               (4) */
     int h_bits;     /* mantissa bits of X, A_k, B_k       (8) */
-    int exp_bits;   /* shared exponent bits               (8) */
+    int exp_bits;   /* shared exponent bits of W_q, A_k, B_k   (8 or 4) */
     int block;      /* block size                         (16) */
 } lqer_config;
 
@@ -86,7 +95,7 @@ int lqer_quantize_mx(const float* x_dev, int64_t rows, int64_t cols, int64_t ld,
  *   calib_host  [n_samples][rows_per_sample][K] fp32, host (ignored when mode == 0; may be NULL then)
  *   k           rank, 0 <= k <= min(K, N)
  *   mode        0 = LQER (S = I), 1 = L2QER (S from calib_host)
- *   cfg         NULL = {4, 8, 8, 16}
+ *   cfg         NULL = {4, 8, 8, 16}; {4, 8, 4, 16} selects 4-bit shared exponents (see lqer_config)
  *   out         receives an owning handle; release with lqer_layer_free
  * Computes W_q = q(W), E_q = W - W_q, S, the k leading singular triplets of S E_q,
  * A_k = S^-1 U_k, B_k = Sigma_k V_k^T, quantizes A_k and B_k to MXINT8 and uploads

@@ -10,7 +10,8 @@
 namespace lqer {
 
 // ---- MXINT quantization of one block of 16 doubles (Sec. 2.2 / 4.1 reading, see lqer.h) ---------
-inline void mx_block(const double* v, int stride, int bits, int8_t* codes, uint8_t* ebyte) {
+// The block's own shared exponent: floor(log2 max|v|) clamped to [-127, 127], -127 for an all-zero block.
+inline int mx_block_exponent(const double* v, int stride) {
     double amax = 0.0;
     for (int i = 0; i < 16; ++i) amax = std::max(amax, std::fabs(v[i * stride]));
     int e = -127;
@@ -21,6 +22,19 @@ inline void mx_block(const double* v, int stride, int bits, int8_t* codes, uint8
         if (e < -127) e = -127;
         if (e > 127) e = 127;
     }
+    return e;
+}
+
+// Lowest exponent a tensor with `exp_bits`-bit shared exponents can store when its largest block has
+// exponent `top`: 4-bit exponents reach 15 binades below the largest block (one bias per tensor).
+inline int mx_exponent_floor(int top, int exp_bits) {
+    return exp_bits == 4 ? std::max(top - 15, -127) : -127;
+}
+
+// e_floor: blocks below it are quantized with e_floor (4-bit shared exponents; -127 = no floor).
+inline void mx_block(const double* v, int stride, int bits, int8_t* codes, uint8_t* ebyte, int e_floor = -127) {
+    int e = mx_block_exponent(v, stride);
+    if (e < e_floor) e = e_floor;
     const int lim = (1 << (bits - 1)) - 1;
     for (int i = 0; i < 16; ++i) {
         double r = std::nearbyint(std::ldexp(v[i * stride], (bits - 2) - e));   // ties to even

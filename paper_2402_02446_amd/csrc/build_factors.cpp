@@ -135,29 +135,46 @@ static int truncated_split(const std::vector<double>& G, int64_t K, int64_t N, c
 
 // A (K x k) and B (k x N) -> MXINT8 bytes in the canonical layouts, then the layer handle.
 int pack_factors_and_import(int64_t K, int64_t N, int k, const std::vector<uint8_t>& Wc, const std::vector<uint8_t>& We,
-                            const std::vector<double>& A, const std::vector<double>& B, lqer_layer** out) {
+                            const std::vector<double>& A, const std::vector<double>& B, int exp_bits, lqer_layer** out) {
     const int kp = (k + 15) / 16 * 16;
     const int64_t nblk = K / 16;
     std::vector<int8_t> Ac, Bc;
     std::vector<uint8_t> Ae, Be;
     if (k > 0) {
         // A_k: K x k -> MXINT8 blocks down K, stored [kp][K]
+        // (the zero rows and columns of the padding are blocks of the tensor like any other: exponent -127)
         Ac.assign((size_t)kp * K, 0);
         Ae.assign((size_t)kp * nblk, 0);
+        int top = -127;
         for (int r = 0; r < k; ++r)
-            for (int64_t kb = 0; kb < nblk; ++kb)
-                mx_block(&A[(size_t)kb * 16 * k + r], k, 8, &Ac[(size_t)r * K + kb * 16], &Ae[(size_t)r * nblk + kb]);
+            for (int64_t kb = 0; kb < nblk; ++kb) top = std::max(top, mx_block_exponent(&A[(size_t)kb * 16 * k + r], k));
+        const int a_floor = mx_exponent_floor(top, exp_bits);
+        for (int r = 0; r < kp; ++r)
+            for (int64_t kb = 0; kb < nblk; ++kb) {
+                if (r < k) mx_block(&A[(size_t)kb * 16 * k + r], k, 8, &Ac[(size_t)r * K + kb * 16], &Ae[(size_t)r * nblk + kb], a_floor);
+                else Ae[(size_t)r * nblk + kb] = (uint8_t)(a_floor + 127);
+            }
         // B_k: k x N (zero padded to kp) -> MXINT8 blocks down k, stored [N][kp]
         Bc.assign((size_t)N * kp, 0);
         Be.assign((size_t)N * (kp / 16), 0);
         std::vector<double> colb(16);
+        auto b_block = [&](int64_t n, int rb) {
+            for (int i = 0; i < 16; ++i) {
+                const int r = rb * 16 + i;
+                colb[i] = (r < k) ? B[(size_t)r * N + n] : 0.0;
+            }
+        };
+        top = -127;
         for (int64_t n = 0; n < N; ++n)
             for (int rb = 0; rb < kp / 16; ++rb) {
-                for (int i = 0; i < 16; ++i) {
-                    const int r = rb * 16 + i;
-                    colb[i] = (r < k) ? B[(size_t)r * N + n] : 0.0;
-                }
-                mx_block(colb.data(), 1, 8, &Bc[(size_t)n * kp + rb * 16], &Be[(size_t)n * (kp / 16) + rb]);
+                b_block(n, rb);
+                top = std::max(top, mx_block_exponent(colb.data(), 1));
+            }
+        const int b_floor = mx_exponent_floor(top, exp_bits);
+        for (int64_t n = 0; n < N; ++n)
+            for (int rb = 0; rb < kp / 16; ++rb) {
+                b_block(n, rb);
+                mx_block(colb.data(), 1, 8, &Bc[(size_t)n * kp + rb * 16], &Be[(size_t)n * (kp / 16) + rb], b_floor);
             }
     }
     return lqer_layer_import(K, N, k, Wc.data(), We.data(), k > 0 ? Ac.data() : nullptr,
@@ -190,8 +207,9 @@ extern "C" int lqer_build_factors(const float* W_host, int64_t K, int64_t N, con
                                   const lqer_config* cfg, lqer_layer** out) {
     if (!out) return LQER_ERR_NULL;
     *out = nullptr;
-    if (cfg && (cfg->w_bits != 4 || cfg->h_bits != 8 || cfg->exp_bits != 8 || cfg->block != 16))
+    if (cfg && (cfg->w_bits != 4 || cfg->h_bits != 8 || (cfg->exp_bits != 8 && cfg->exp_bits != 4) || cfg->block != 16))
         return LQER_ERR_UNSUPPORTED;
+    const int exp_bits = cfg ? cfg->exp_bits : 8;
     if (K <= 0 || N <= 0 || (K & 15) != 0 || k < 0 || k > K || k > N) return LQER_ERR_SHAPE;
     if (mode != 0 && mode != 1) return LQER_ERR_UNSUPPORTED;
     if (!W_host) return LQER_ERR_NULL;
@@ -223,13 +241,21 @@ extern "C" int lqer_build_factors(const float* W_host, int64_t K, int64_t N, con
     if (k > 0) G.resize((size_t)K * N);
     for (int64_t i = 0; i < K * N; ++i)
         if (!std::isfinite(W_host[i])) return LQER_ERR_VALUE;
+    // 4-bit shared exponents: the exponent of the tensor's largest block fixes the lowest one that can be stored
+    int w_floor = -127;
+    if (exp_bits == 4) {
+        float amax = 0.f;
+        for (int64_t i = 0; i < K * N; ++i) amax = std::max(amax, std::fabs(W_host[i]));
+        const double one[16] = {(double)amax};
+        w_floor = mx_exponent_floor(mx_block_exponent(one, 1), exp_bits);
+    }
     parallel_for(N, [&](int64_t n) {
         double col[16];
         int8_t codes[16];
         for (int64_t kb = 0; kb < nblk; ++kb) {
             for (int i = 0; i < 16; ++i) col[i] = (double)W_host[(kb * 16 + i) * N + n];
             uint8_t eb;
-            mx_block(col, 1, 4, codes, &eb);
+            mx_block(col, 1, 4, codes, &eb, w_floor);
             We[n * nblk + kb] = eb;
             for (int i = 0; i < 8; ++i)
                 Wc[n * (K / 2) + kb * 8 + i] = (uint8_t)((codes[2 * i] & 0xF) | ((codes[2 * i + 1] & 0xF) << 4));
@@ -250,5 +276,5 @@ extern "C" int lqer_build_factors(const float* W_host, int64_t K, int64_t N, con
         G.clear();
         G.shrink_to_fit();
     }
-    return pack_factors_and_import(K, N, k, Wc, We, A, B, out);
+    return pack_factors_and_import(K, N, k, Wc, We, A, B, exp_bits, out);
 }

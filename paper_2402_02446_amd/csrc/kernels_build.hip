@@ -32,13 +32,26 @@ __global__ __launch_bounds__(256) void calib_magnitude_kernel(const float* __res
     abar[c] = m;
 }
 
+// Largest |w| of the tensor as fp32 bits (non-negative floats order like their bit patterns): with 4-bit
+// shared exponents its exponent field fixes the lowest exponent the tensor can store.  *out is zero before.
+__global__ __launch_bounds__(256) void absmax_bits_kernel(const float* __restrict__ W, int64_t count, uint32_t* __restrict__ out) {
+    uint32_t m = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
+        m = max(m, f32_bits(__builtin_fabsf(W[i])));
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, d));
+    if ((threadIdx.x & 63) == 0) atomicMax(out, m);
+}
+
 // One thread per MXINT4 block (16 consecutive k of one column n): codes and exponent byte in the
 // canonical layout, and G = s[k] (w - dq(q(w))) in fp32 (the difference itself is exact).
 // flag: set when a weight is not finite.
+// amax_bits != null: 4-bit shared exponents - blocks more than 15 binades below the tensor's largest are
+// quantized with the lowest exponent byte that can be stored.
 __global__ __launch_bounds__(256) void quantize_w_kernel(const float* __restrict__ W, int64_t K, int64_t N,
                                                          const float* __restrict__ s, uint8_t* __restrict__ Wc,
                                                          uint8_t* __restrict__ We, float* __restrict__ G,
-                                                         int* __restrict__ flag) {
+                                                         int* __restrict__ flag, const uint32_t* __restrict__ amax_bits) {
     const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t kb = blockIdx.y;
     if (n >= N) return;
@@ -55,7 +68,12 @@ __global__ __launch_bounds__(256) void quantize_w_kernel(const float* __restrict
         *flag = 1;
         return;
     }
-    const uint32_t eb = (f32_bits(m) >> 23) & 0xFFu;
+    uint32_t eb = (f32_bits(m) >> 23) & 0xFFu;
+    if (amax_bits != nullptr) {
+        const uint32_t top = (*amax_bits >> 23) & 0xFFu;
+        const uint32_t floor_byte = top > 15u ? top - 15u : 0u;
+        if (eb < floor_byte) eb = floor_byte;
+    }
     const int e = (int)eb - 127;
     int c[16];
 #pragma unroll
@@ -362,8 +380,9 @@ extern "C" int lqer_build_factors_device(const float* W_dev, int64_t K, int64_t 
                                          const lqer_config* cfg, void* hip_stream, lqer_layer** out) {
     if (!out) return LQER_ERR_NULL;
     *out = nullptr;
-    if (cfg && (cfg->w_bits != 4 || cfg->h_bits != 8 || cfg->exp_bits != 8 || cfg->block != 16))
+    if (cfg && (cfg->w_bits != 4 || cfg->h_bits != 8 || (cfg->exp_bits != 8 && cfg->exp_bits != 4) || cfg->block != 16))
         return LQER_ERR_UNSUPPORTED;
+    const int exp_bits = cfg ? cfg->exp_bits : 8;
     if (K <= 0 || N <= 0 || (K & 15) != 0 || k < 0 || k > K || k > N) return LQER_ERR_SHAPE;
     if (mode != 0 && mode != 1) return LQER_ERR_UNSUPPORTED;
     if (!W_dev) return LQER_ERR_NULL;
@@ -394,19 +413,24 @@ extern "C" int lqer_build_factors_device(const float* W_dev, int64_t K, int64_t 
     const int l = (int)std::min<int64_t>(k + 16, std::min(K, N));
     DevBuf dWc, dWe, dS, dG, dFlag;
     if (dWc.alloc((size_t)N * (K / 2)) != hipSuccess || dWe.alloc((size_t)N * nblk) != hipSuccess ||
-        dS.alloc((size_t)K * 4) != hipSuccess || dFlag.alloc(4) != hipSuccess ||
+        dS.alloc((size_t)K * 4) != hipSuccess || dFlag.alloc(8) != hipSuccess ||
         (k > 0 && dG.alloc((size_t)K * N * 4) != hipSuccess))
         return LQER_ERR_HIP;
     {
         std::vector<float> sf((size_t)K);
         for (int64_t i = 0; i < K; ++i) sf[i] = (float)sc[i];
         if (hipMemcpyAsync(dS.p, sf.data(), (size_t)K * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
-            hipMemsetAsync(dFlag.p, 0, 4, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
+            hipMemsetAsync(dFlag.p, 0, 8, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
             return LQER_ERR_HIP;
+    }
+    uint32_t* amax_bits = nullptr;                   // the second word of dFlag
+    if (exp_bits == 4) {
+        amax_bits = reinterpret_cast<uint32_t*>(dFlag.p) + 1;
+        hipLaunchKernelGGL(absmax_bits_kernel, dim3(1024), dim3(256), 0, s, W_dev, K * N, amax_bits);
     }
     hipLaunchKernelGGL(quantize_w_kernel, dim3((unsigned)((N + 255) / 256), (unsigned)nblk), dim3(256), 0, s, W_dev, K, N,
                        dS.as<float>(), dWc.as<uint8_t>(), dWe.as<uint8_t>(), k > 0 ? dG.as<float>() : nullptr,
-                       dFlag.as<int>());
+                       dFlag.as<int>(), amax_bits);
     std::vector<uint8_t> Wc((size_t)N * (K / 2)), We((size_t)N * nblk);
     int flag = 0;
     if (hipGetLastError() != hipSuccess ||
@@ -432,5 +456,5 @@ extern "C" int lqer_build_factors_device(const float* W_dev, int64_t K, int64_t 
         const int st = truncated_split_device(w, sc, k, A, B);
         if (st != LQER_OK) return st;
     }
-    return pack_factors_and_import(K, N, k, Wc, We, A, B, out);
+    return pack_factors_and_import(K, N, k, Wc, We, A, B, exp_bits, out);
 }

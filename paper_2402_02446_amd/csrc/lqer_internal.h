@@ -128,8 +128,9 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
 hipError_t launch_clear_flags(const Workspace& ws, hipStream_t s);
 
 // ---- offline construction, shared host steps (build_factors.cpp) ---------------------------
+// exp_bits: width of A_k's and B_k's shared exponents (8, or 4 with one bias per tensor)
 int pack_factors_and_import(int64_t K, int64_t N, int k, const std::vector<uint8_t>& Wc, const std::vector<uint8_t>& We,
-                            const std::vector<double>& A, const std::vector<double>& B, lqer_layer** out);
+                            const std::vector<double>& A, const std::vector<double>& B, int exp_bits, lqer_layer** out);
 int scale_from_magnitudes(const std::vector<double>& abar, std::vector<double>& s);
 
 int prep_slices(const Layer& L, int64_t M, int path);

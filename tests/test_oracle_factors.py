@@ -223,3 +223,32 @@ def test_approximation_error_metric():
     E = np.array([[1.0, -2.0], [0.5, 0.0]])
     Et = np.array([[0.5, -1.0], [0.5, 1.0]])
     assert factors.approximation_error(E, Et) == (0.5 + 1.0 + 0.0 + 1.0) / 4
+
+
+def test_four_bit_shared_exponents_in_the_offline_step():
+    # Sec. 4.1: W_q, A_k, B_k with 4-bit shared exponents (one bias per tensor).  On weights of a few binades
+    # the narrow exponent reaches every block: W_q is that of the 8-bit-exponent build, and so is E_q.
+    rng = np.random.default_rng(5)
+    W = synth.gen_weight(rng, 128, 96)
+    ch = synth.gen_outlier_channels(rng, 128, 4)
+    calib = np.stack([synth.gen_activations(rng, 32, 128, ch, 30.0)])
+    a = factors.build_factors(W, calib, 8, 1)
+    b = factors.build_factors(W, calib, 8, 1, exp_bits=4)
+    assert np.array_equal(a.Wc, b.Wc) and np.array_equal(a.We, b.We)
+    for e in (b.We, b.Ae, b.Be):
+        assert int(e.max()) - int(e.min()) <= 15
+    # the factors may lose low bits of their smallest blocks, never more than the error they correct
+    s = factors.calibrate_scale(calib)
+    W_hat, A8, B8 = factors.dequantize_layer(a)
+    _, A4, B4 = factors.dequantize_layer(b)
+    E = W.astype(np.float64) - W_hat
+    r8 = np.linalg.norm(s[:, None] * (E - A8 @ B8))
+    r4 = np.linalg.norm(s[:, None] * (E - A4 @ B4))
+    assert r4 <= 1.02 * r8 and r4 < np.linalg.norm(s[:, None] * E)
+    # full rank still recovers W up to the quantization of the factors
+    W2 = synth.gen_weight(rng, 64, 48)
+    full = factors.build_factors(W2, None, 48, 0, exp_bits=4)
+    Wh, A, B = factors.dequantize_layer(full)
+    assert np.linalg.norm(W2 - Wh - A @ B) < 0.05 * np.linalg.norm(W2 - Wh)
+    # stored size (App. D): 4.25 bits per weight instead of 4.5, 8.25 instead of 8.5 per factor element
+    assert mxint.lqer_average_weight_bits(4096, 4096, 32, 4, 8, 4, 4) == pytest.approx(4.25 + 8.25 * 32 * 8192 / 4096 ** 2)
