@@ -82,8 +82,10 @@ def test_streaming_kernel_shapes(K, N, k, M, variant):
 
 
 # variant = 100 * mode + tile shape; mode 2 cuts output tiles along K between workgroups wherever the
-# tiles do not fill whole rounds of the chip, mode 1 never does, mode 0 decides by estimate
-@pytest.mark.parametrize("variant", [1, 3, 4, 7, 8, 11, 12, 13, 101, 111, 112, 204, 211, 212])
+# tiles do not fill whole rounds of the chip (along tile boundaries where the chip holds two or more workgroups
+# per remaining tile, otherwise in equal shares of the remaining K tiles), mode 3 always in equal shares,
+# mode 1 never cuts, mode 0 decides by estimate
+@pytest.mark.parametrize("variant", [1, 3, 4, 7, 8, 11, 12, 13, 101, 111, 112, 204, 211, 212, 304, 311, 312])
 @pytest.mark.parametrize("M,K,N,k", [(16, 512, 512, 8), (300, 272, 200, 0), (513, 1024, 528, 64), (100, 2304, 40, 33),
                                      (700, 4352, 1100, 16)])
 def test_tiled_kernel_shapes(variant, M, K, N, k):
@@ -451,7 +453,7 @@ def test_split_is_refused_for_shapes_without_it():
     layer, ch = oracle_layer_small(1024, 272, 8, seed=2)
     h = upload(layer)
     X = synth.gen_activations(np.random.default_rng(2), 300, 1024, ch, 30.0)
-    for variant in (201, 203, 207, 208, 213, 311):
+    for variant in (201, 203, 207, 208, 213, 301, 411):
         with pytest.raises(binding.LqerError):
             _gpu_forward(h, X, path=2, variant=variant)
     h.free()
@@ -475,6 +477,27 @@ def test_split_tiles_give_the_same_bits_every_run(variant):
         Y = torch.full_like(first, 3.0)
         binding.lqer_linear_forward_ex(h, X, Y=Y, path=2, variant=variant)
         assert torch.equal(Y, first)
+    h.free()
+
+
+@pytest.mark.parametrize("variant", [211, 212, 204, 311, 312, 304])
+def test_split_along_tile_boundaries_and_in_equal_shares(variant):
+    # 13 x 4 tiles of 128 x 512 (13 x 8, 13 x 16 for the smaller shapes) with 11 K tiles each: the chip holds
+    # several workgroups per tile, so mode 2 cuts every tile into the same number of pieces (ragged: 11 K tiles
+    # in pieces of 3 or 6, with empty units behind the last one) and mode 3 into equal shares that cross tiles.
+    # Both against the oracle, and the same bits on a second run.
+    import torch
+    from paper_2402_02446_amd import binding
+    K, N, k, M = 2816, 2048, 40, 1664
+    layer, ch = oracle_layer_big(K, N, k, seed=variant)
+    h = upload(layer)
+    Xn = synth.gen_activations(np.random.default_rng(variant), M, K, ch, 50.0)
+    X = torch.from_numpy(Xn).cuda()
+    first = binding.lqer_linear_forward_ex(h, X, path=2, variant=variant).clone()
+    _assert_close(first.cpu().numpy(), forward.forward(Xn, layer))
+    Y = torch.full_like(first, float("nan"))
+    binding.lqer_linear_forward_ex(h, X, Y=Y, path=2, variant=variant)
+    assert torch.equal(Y, first)
     h.free()
 
 
