@@ -3,7 +3,8 @@
 // HBM-bound: 4 B read and 1 + 1/16 B written per element (8- and 6-bit codes, one byte each).  Each lane loads one
 // float4, so a wavefront load is one contiguous 1 KiB; the four lanes of a quad hold one
 // 16-element block and agree on its maximum with two DPP quad permutes.  The shared exponent is
-// the biased exponent field of that fp32 maximum.
+// the biased exponent field of that fp32 maximum.  The activations are read once and with streaming loads
+// (each cache line belongs to exactly one load instruction), which keeps them from displacing the stored codes.
 #include "lqer_internal.h"
 #include "mx_device.h"
 
@@ -30,17 +31,27 @@ __global__ __launch_bounds__(256) void quantize_mx_kernel(const float* __restric
                                                           uint8_t* __restrict__ exps) {
     const int64_t total = rows * cols4;                       // float4 items; a multiple of 4
     const int64_t nthreads = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t base = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; base < total;
-         base += nthreads * UNROLL) {
+    // (row, column) of this thread's items without a division per item: one division here, then every
+    // step of nthreads items moves by the same (rows, columns) with a carry
+    const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t step_r = nthreads / cols4, step_c = nthreads - step_r * cols4;      // wave-uniform
+    int64_t r_next = first / cols4, c_next = first - r_next * cols4;
+    for (int64_t base = first; base < total; base += nthreads * UNROLL) {
         float4 v[UNROLL];
         int64_t row[UNROLL], c4[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int64_t i = base + (int64_t)u * nthreads;
-            row[u] = i / cols4;
-            c4[u] = i - row[u] * cols4;
-            v[u] = (i < total) ? *reinterpret_cast<const float4*>(x + row[u] * ld + 4 * c4[u])
-                               : make_float4(0.f, 0.f, 0.f, 0.f);
+            row[u] = r_next;
+            c4[u] = c_next;
+            c_next += step_c;
+            r_next += step_r;
+            if (c_next >= cols4) { c_next -= cols4; ++r_next; }
+            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i < total) {
+                const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(x + row[u] * ld + 4 * c4[u]));
+                v[u] = make_float4(t[0], t[1], t[2], t[3]);
+            }
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
