@@ -361,6 +361,26 @@ def test_layers_sharing_their_activations():
                 assert torch.equal(Y, alone[i]), (M, order, i)
         for i in (0, 3):
             assert forward.rel_frobenius(alone[i].cpu().numpy(), forward.forward(X, layers[i])) < Y_TOL
+    # the shared call allocates nothing and uses one stream: captured in a HIP graph, every replay reproduces it
+    M = 300
+    group = [hs[0], hs[1], hs[3]]
+    Xg = torch.from_numpy(synth.gen_activations(np.random.default_rng(5), M, K, ch, 30.0)).cuda()
+    want = [binding.lqer_linear_forward(h, Xg).clone() for h in group]
+    ws = torch.empty(binding.lqer_linear_shared_workspace_bytes(group, M), dtype=torch.uint8, device="cuda")
+    Ys = [torch.empty_like(w) for w in want]
+    binding.lqer_linear_forward_shared(group, Xg, Ys=Ys, workspace=ws)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        binding.lqer_linear_forward_shared(group, Xg, Ys=Ys, workspace=ws)
+    for rep in range(3):
+        for Y in Ys:
+            Y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for Y, w in zip(Ys, want):
+            assert torch.equal(Y, w), rep
     # layers of different K cannot share activations
     other, _ = oracle_layer_small(512, 64, 8, seed=1)
     ho = upload(other)
