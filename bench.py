@@ -224,7 +224,7 @@ def run_cfg5(steps, rng):
             f = lambda i: binding.lqer_linear_forward(layer, X, Y=Y)
             f(0)
             torch.cuda.synchronize()
-            ms = _event_ms(f, steps)
+            ms = sorted(_event_ms(f, steps) for _ in range(3))[1]
             fl = flops_forward(M, K, N, layer.kp)
             per_shape.append({"K": K, "N": N, "linears": names, "ms_per_linear": ms,
                               "tflops": fl / (ms * 1e-3) / 1e12})
@@ -246,7 +246,8 @@ def run_cfg5(steps, rng):
             f_sep = lambda i: [binding.lqer_linear_forward(l, X, Y=y, workspace=ws) for l, y in zip(group, Ys)]
             f_sh(0); f_sep(0)
             torch.cuda.synchronize()
-            ms_sh, ms_sep = _event_ms(f_sh, steps), _event_ms(f_sep, steps)
+            ms_sh = sorted(_event_ms(f_sh, steps) for _ in range(3))[1]
+            ms_sep = sorted(_event_ms(f_sep, steps) for _ in range(3))[1]
             shared.append({"linears": list(names), "ms_shared": ms_sh, "ms_separate": ms_sep})
             saved_ms += ms_sep - ms_sh
             for l in group:
