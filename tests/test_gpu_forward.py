@@ -591,3 +591,31 @@ def test_forward_in_hip_graph_replays():
             torch.cuda.synchronize()
         del g
     h.free()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_random_shapes_on_the_automatic_path(seed):
+    # Shapes nobody picked by hand: token counts on both sides of every dispatch boundary, K any multiple of 16,
+    # N any size (ragged column groups), ranks from none to the limit; the automatic path and shape, against the
+    # oracle, and the pre-quantized entry point giving the same bits.
+    import torch
+    from paper_2402_02446_amd import binding
+    rng = np.random.default_rng(1000 + seed)
+    M = int(rng.choice([1, 2, 3, 4, 5, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 129, 200, 257, 400]))
+    K = 16 * int(rng.integers(1, 160))
+    N = int(rng.integers(1, 1400))
+    k = int(rng.integers(0, min(64, K, N) + 1))
+    layer, ch = oracle_layer_big(K, N, k, seed=seed, n_outlier=max(1, K // 100))
+    h = upload(layer)
+    X = synth.gen_activations(rng, M, K, ch, 50.0)
+    ld = (N + 3) // 4 * 4                                     # the row stride of Y must be a multiple of 4
+    buf = torch.full((M, ld), float("nan"), dtype=torch.float32, device="cuda")
+    binding.lqer_linear_forward(h, torch.from_numpy(X).cuda(), Y=buf[:, :N])
+    Y = buf[:, :N].cpu().numpy()
+    assert torch.isnan(buf[:, N:]).all()                      # nothing is written behind a row
+    _assert_close(Y, forward.forward(X, layer))
+    Xc, Xe = forward.quantize_activations(X, 8)
+    bufq = torch.empty_like(buf)
+    binding.lqer_linear_forward_q(h, torch.from_numpy(Xc).cuda(), torch.from_numpy(Xe).cuda(), Y=bufq[:, :N])
+    assert np.array_equal(bufq[:, :N].cpu().numpy(), Y), (M, K, N, k)
+    h.free()
