@@ -519,11 +519,11 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
 
 // Time estimates in microseconds for one tile shape, launched as one workgroup per tile or with the
 // work split described at the head of this file.
-struct TileShape { int id, bm, bn, share; double pair, single; };
-// whole-chip TFLOP/s measured on an 8192 x 28672 layer at M = 4096: `pair` with `share` workgroups on
-// every compute unit, `single` with one
+struct TileShape { int id, bm, bn, share; double pair, single, cut; };
+// whole-chip TFLOP/s measured on an 8192 x 28672 layer: `pair` with `share` workgroups on every compute unit
+// (M = 4096), `single` with one (M = 128), `cut` for the pieces of tiles cut along K (M = 128 .. 2048)
 static const TileShape kShapes[] = {
-    {11, 128, 512, 1, 1372.0, 1372.0}, {12, 128, 256, 2, 1300.0, 1000.0}, {4, 128, 128, 2, 1058.0, 900.0},
+    {11, 128, 512, 1, 1372.0, 1372.0, 1372.0}, {12, 128, 256, 2, 1300.0, 1000.0, 1150.0}, {4, 128, 128, 2, 1058.0, 800.0, 1058.0},
 };
 constexpr double kPieceUs = 4.0;       // filling the pipeline and storing the tile, per piece
 constexpr double kSplitFixedUs = 30.0; // what a split launch was measured to take beyond this, per workgroup sharing a compute unit: the
@@ -578,8 +578,14 @@ static double time_split(const TileShape& sh, int64_t tiles, int64_t KT, int cus
     const bool one_piece = sp.aligned;                       // cut along tile boundaries: no workgroup gets two pieces
     if (sp.sk_units == 0) return time_whole(sh, tiles, KT, cus);
     const double rounds = (double)(sp.dp_tiles / sp.grid);
-    return (rounds * (double)KT + (double)sp.sk_share) * unit_us(sh, sh.share, cus) +
-           (rounds + (one_piece ? 1.0 : 2.0)) * kPieceUs + (one_piece ? 0.5 : 1.0) * kSplitFixedUs * sh.share;
+    const double whole_part = rounds * (double)KT * unit_us(sh, sh.share, cus);
+    const double cut_part = (double)sp.sk_share * unit_us(sh, sh.share, cus) * sh.pair / sh.cut;
+    if (!one_piece) return whole_part + cut_part + (rounds + 2.0) * kPieceUs + kSplitFixedUs * sh.share;
+    // cut along tiles: one piece per workgroup; the workgroup with a tile's first piece reads the slots of the
+    // others one after the other (about 7 us per 256 KiB slot beyond the first, from launches with 2 and 4 pieces)
+    const double pieces = (double)(sp.sk_tile_units / sp.sk_share);
+    const double slot_us = 7.0 * (double)sh.bm * sh.bn * 4.0 / 262144.0;
+    return whole_part + cut_part + (rounds + 1.0) * kPieceUs + 0.5 * kSplitFixedUs + (pieces - 2.0) * slot_us;
 }
 
 // the split has to promise a clear gain: its estimate is the rougher of the two
@@ -608,7 +614,7 @@ static hipError_t launch_tiled_t(TiledArgs a, int64_t M, int mode, int cus, hipS
     a.grid_n = (int)((a.N + BN - 1) / BN);
     a.group_m = 8;
     const int64_t tiles = (int64_t)a.grid_m * a.grid_n;
-    TileShape me = {0, BM, BN, MINW, 1.0, 1.0};
+    TileShape me = {0, BM, BN, MINW, 1.0, 1.0, 1.0};
     for (const TileShape& sh : kShapes)
         if (sh.bm == BM && sh.bn == BN && sh.share == MINW) me = sh;
     const int64_t slots = (int64_t)cus * MINW;
