@@ -178,7 +178,11 @@ int lqer_linear_forward_q(const lqer_layer* layer, const int8_t* Xc_dev, const u
  * Launch control for measurement and tuning (Sec. 2.1 distinguishes the memory-bound
  * and the compute-bound regime; the dispatcher picks by M, this overrides it).
  *   path    0 = automatic, 1 = streaming kernel (small M), 2 = tiled MFMA kernel (large M)
- *   variant 0 = automatic, otherwise a tile-shape index of the chosen path
+ *   variant 0 = automatic, otherwise a tile-shape index of the chosen path (for tuning; an index the
+ *           path does not have returns LQER_ERR_SHAPE).  Tiled path: 100 * mode + shape, mode 0 = cut
+ *           output tiles along K between workgroups when the estimate says it pays, 1 = never,
+ *           2 = whenever tiles are left over, 3 = the same in equal shares of the left-over K tiles
+ *           instead of along tile boundaries
  *   stages  bit 0 = quantize + T, bit 1 = main product; 0 = both
  * Same contract as lqer_linear_forward otherwise.  Running stage bit 1 alone reuses
  * what an earlier call with bit 0 left in the same workspace - with the same M, path and
