@@ -234,6 +234,15 @@ int lqer_linear_forward_shared(const lqer_layer* const* layers, int n_layers, co
                                int64_t M, int64_t ldx, float* const* Y_dev, const int64_t* ldy,
                                void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * For callers that test the failure path of the bounded wait described at lqer_linear_forward:
+ * the number of polls after which a workgroup waiting for another one's partial sums gives up
+ * (process-wide; the default, 1 << 22, is about a second).  With 0 every such wait gives up at
+ * once: the kernel still ends normally and every output tile that was cut between workgroups
+ * is stored as NaN.  Negative values return LQER_ERR_SHAPE.
+ */
+int lqer_set_wait_limit(int polls);
+
 /* Which path the dispatcher picks for this layer at M tokens: 1 = streaming, 2 = tiled MFMA. */
 int lqer_linear_path(const lqer_layer* layer, int64_t M);
 

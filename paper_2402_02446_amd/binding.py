@@ -24,7 +24,7 @@ EXPORTS = ("lqer_status_string", "lqer_quantize_mx", "lqer_build_factors", "lqer
            "lqer_layer_import",
            "lqer_layer_export", "lqer_layer_dims", "lqer_layer_set_activation_bits", "lqer_layer_free", "lqer_linear_workspace_bytes", "lqer_linear_workspace_bytes_ex",
            "lqer_linear_forward", "lqer_linear_forward_q", "lqer_linear_forward_ex", "lqer_linear_forward_requant", "lqer_linear_path",
-           "lqer_linear_shared_workspace_bytes", "lqer_linear_forward_shared")
+           "lqer_linear_shared_workspace_bytes", "lqer_linear_forward_shared", "lqer_set_wait_limit")
 
 
 class LqerError(RuntimeError):
@@ -91,6 +91,8 @@ def lib() -> C.CDLL:
     L.lqer_linear_shared_workspace_bytes.argtypes = [C.POINTER(vp), i32, i64]
     L.lqer_linear_forward_shared.restype = i32
     L.lqer_linear_forward_shared.argtypes = [C.POINTER(vp), i32, vp, i64, i64, C.POINTER(vp), C.POINTER(i64), vp, sz, vp]
+    L.lqer_set_wait_limit.restype = i32
+    L.lqer_set_wait_limit.argtypes = [i32]
     L.lqer_linear_path.restype = i32
     L.lqer_linear_path.argtypes = [vp, i64]
     _lib = L
@@ -314,3 +316,7 @@ def lqer_linear_forward_shared(layers, X, Ys=None, workspace=None):
                                             C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream()),
            "lqer_linear_forward_shared")
     return Ys
+
+
+def lqer_set_wait_limit(polls: int):
+    _check(lib().lqer_set_wait_limit(int(polls)), "lqer_set_wait_limit")

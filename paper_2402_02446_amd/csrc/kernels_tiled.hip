@@ -27,6 +27,8 @@
 // so only its first piece can be handed over and only its last piece can wait, and the waiting
 // piece needs pieces that are computed first by the workgroups they belong to: no wait depends on
 // another wait.  The sum order is fixed by the split, so the result has the same bits every run.
+#include <atomic>
+
 #include "lqer_internal.h"
 #include "mx_device.h"
 
@@ -650,6 +652,10 @@ hipError_t launch_clear_flags(const Workspace& ws, hipStream_t s) {
     return hipGetLastError();
 }
 
+static std::atomic<int> g_wait_limit{1 << 22};
+int tiled_wait_limit() { return g_wait_limit.load(); }
+void set_tiled_wait_limit(int polls) { g_wait_limit.store(polls); }
+
 int compute_units() {
     static int cus = 0;                                      // one kind of device per process
     if (cus == 0) {
@@ -672,7 +678,7 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
     a.grid_m = a.grid_n = 0; a.group_m = 8;
     a.Part = ws.Part; a.flags = ws.flags;
     a.rec_bytes = L.w_rec_bytes; a.exp_bias = L.w_exp_bias;
-    a.spin_limit = 1 << 22;                                  // about a second of polling
+    a.spin_limit = tiled_wait_limit();                       // by default about a second of polling
     a.dp_tiles = a.sk_units = 0; a.sk_share = 1; a.sk_tile_units = L.KT;
     const int cus = compute_units();
     // variant = 100 * mode + tile shape; mode 0 = split the work when the estimate says so, 1 = never, 2 = always,

@@ -575,6 +575,12 @@ int lqer_linear_forward_shared(const lqer_layer* const* layers, int n_layers, co
     return LQER_OK;
 }
 
+int lqer_set_wait_limit(int polls) {
+    if (polls < 0) return LQER_ERR_SHAPE;
+    set_tiled_wait_limit(polls);
+    return LQER_OK;
+}
+
 int lqer_linear_path(const lqer_layer* layer, int64_t M) {
     if (!layer) return 0;
     return pick_path(layer->L, M);

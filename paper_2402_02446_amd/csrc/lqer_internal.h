@@ -126,6 +126,9 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
                         int variant, hipStream_t s);
 
 hipError_t launch_clear_flags(const Workspace& ws, hipStream_t s);
+// polls of a hand-over flag before a waiting workgroup of the tiled kernel gives up and stores NaN
+int tiled_wait_limit();
+void set_tiled_wait_limit(int polls);
 
 // ---- offline construction, shared host steps (build_factors.cpp) ---------------------------
 // exp_bits: width of A_k's and B_k's shared exponents (8, or 4 with one bias per tensor)

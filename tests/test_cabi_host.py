@@ -95,3 +95,5 @@ def test_newer_entry_points_reject_bad_arguments_on_the_host(L):
     assert L.lqer_quantize_mx(None, 4, 32, 32, 6, 8, None, None, None) == 1        # 6-bit codes are a supported width
     assert L.lqer_linear_forward_shared(None, 2, None, 4, 16, None, None, None, 0, None) == 1
     assert L.lqer_linear_shared_workspace_bytes(None, 2, 4) == 0
+    assert L.lqer_set_wait_limit(-1) == 2
+    assert L.lqer_set_wait_limit(1 << 22) == 0                                     # the default

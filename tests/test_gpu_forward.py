@@ -521,6 +521,37 @@ def test_split_along_tile_boundaries_and_in_equal_shares(variant):
     h.free()
 
 
+def test_a_wait_that_gives_up_ends_the_kernel_and_stores_nan():
+    # The bounded wait of the work split, forced from the host: with a limit of zero polls every workgroup that
+    # waits for another one's partial sums gives up at once.  The kernel must still end normally, every tile
+    # that was cut must come out as NaN (never as a wrong number), tiles computed whole must be right, and with
+    # the default limit back the same call must give the full result again.
+    import torch
+    from paper_2402_02446_amd import binding
+    layer, ch = oracle_layer_big(4096, 4096, 32, seed=9)
+    h = upload(layer)
+    M = 300
+    X = torch.from_numpy(synth.gen_activations(np.random.default_rng(M), M, 4096, ch, 50.0)).cuda()
+    want = binding.lqer_linear_forward_ex(h, X, path=2, variant=211).clone()      # 24 tiles, all cut
+    whole = binding.lqer_linear_forward_ex(h, X, path=2, variant=111).clone()
+    torch.cuda.synchronize()
+    assert torch.isfinite(want).all()
+    try:
+        binding.lqer_set_wait_limit(0)
+        Y = binding.lqer_linear_forward_ex(h, X, path=2, variant=211)
+        torch.cuda.synchronize()                                                # returns: the kernel ended
+        assert torch.isnan(Y).all()
+        Yw = binding.lqer_linear_forward_ex(h, X, path=2, variant=111)            # no cut tiles, no waits
+        torch.cuda.synchronize()
+        assert torch.equal(Yw, whole)
+    finally:
+        binding.lqer_set_wait_limit(1 << 22)
+    Y = binding.lqer_linear_forward_ex(h, X, path=2, variant=211)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, want)
+    h.free()
+
+
 def test_cfg4_70b_shape_sampled():
     # LLaMA-2-70B-shaped MLP (8192 x 28672, k = 64) at M = 1, 16 (streaming kernel) and 4096 (tiled):
     # seeded packed bytes, the oracle evaluated on sampled rows and columns (every tile edge included)
