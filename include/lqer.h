@@ -49,7 +49,8 @@ typedef enum {
     LQER_ERR_WORKSPACE = 5,       /* workspace NULL, misaligned or too small */
     LQER_ERR_HIP = 6,             /* a HIP runtime call or launch failed */
     LQER_ERR_NO_CONVERGENCE = 7,  /* the truncated SVD did not reach its tolerance */
-    LQER_ERR_VALUE = 8            /* packed bytes hold a value the format excludes (nibble -8, exponent byte out of range) */
+    LQER_ERR_VALUE = 8,           /* packed bytes hold a value the format excludes (nibble -8, exponent byte out of range) */
+    LQER_ERR_NO_MEMORY = 9        /* a host allocation failed (import, export and the offline step build host copies) */
 } lqer_status;
 
 /*
@@ -148,6 +149,8 @@ int lqer_layer_free(lqer_layer* layer);
 /*
  * Forward pass (Eq. 3 / Eq. 6).
  *   X_dev  [M][ldx] fp32 device (ldx >= K);  Y_dev [M][ldy] fp32 device (ldy >= N)
+ *          X_dev and Y_dev must be 16-byte aligned and ldx, ldy multiples of 4 (rows are read and written
+ *          16 bytes at a time); LQER_ERR_SHAPE otherwise.  Xc_dev of lqer_linear_forward_q: 16-byte aligned.
  *   workspace_dev  device scratch of at least lqer_linear_workspace_bytes(layer, M)
  *                  bytes, 256-byte aligned, caller-owned; its contents are scratch.
  *                  (lqer_linear_workspace_bytes_ex: the same for a forced path of lqer_linear_forward_ex,

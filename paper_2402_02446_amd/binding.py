@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "liblqer.so")
 LQER_OK = 0
 STATUS_NAMES = {0: "LQER_OK", 1: "LQER_ERR_NULL", 2: "LQER_ERR_SHAPE", 3: "LQER_ERR_UNSUPPORTED",
                 4: "LQER_ERR_SINGULAR_SCALE", 5: "LQER_ERR_WORKSPACE", 6: "LQER_ERR_HIP",
-                7: "LQER_ERR_NO_CONVERGENCE", 8: "LQER_ERR_VALUE"}
+                7: "LQER_ERR_NO_CONVERGENCE", 8: "LQER_ERR_VALUE", 9: "LQER_ERR_NO_MEMORY"}
 
 # every symbol include/lqer.h declares
 EXPORTS = ("lqer_status_string", "lqer_quantize_mx", "lqer_build_factors", "lqer_build_factors_device",

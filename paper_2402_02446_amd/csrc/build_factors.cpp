@@ -204,7 +204,7 @@ using namespace lqer;
 
 extern "C" int lqer_build_factors(const float* W_host, int64_t K, int64_t N, const float* calib_host,
                                   int64_t n_samples, int64_t rows_per_sample, int k, int mode,
-                                  const lqer_config* cfg, lqer_layer** out) {
+                                  const lqer_config* cfg, lqer_layer** out) try {
     if (!out) return LQER_ERR_NULL;
     *out = nullptr;
     if (cfg && (cfg->w_bits != 4 || cfg->h_bits != 8 || (cfg->exp_bits != 8 && cfg->exp_bits != 4) || cfg->block != 16))
@@ -277,4 +277,6 @@ extern "C" int lqer_build_factors(const float* W_host, int64_t K, int64_t N, con
         G.shrink_to_fit();
     }
     return pack_factors_and_import(K, N, k, Wc, We, A, B, exp_bits, out);
+} catch (...) {                                      // a host allocation failed: nothing may leave through the C ABI
+    return LQER_ERR_NO_MEMORY;
 }

@@ -377,7 +377,7 @@ using namespace lqer;
 
 extern "C" int lqer_build_factors_device(const float* W_dev, int64_t K, int64_t N, const float* calib_dev,
                                          int64_t n_samples, int64_t rows_per_sample, int k, int mode,
-                                         const lqer_config* cfg, void* hip_stream, lqer_layer** out) {
+                                         const lqer_config* cfg, void* hip_stream, lqer_layer** out) try {
     if (!out) return LQER_ERR_NULL;
     *out = nullptr;
     if (cfg && (cfg->w_bits != 4 || cfg->h_bits != 8 || (cfg->exp_bits != 8 && cfg->exp_bits != 4) || cfg->block != 16))
@@ -457,4 +457,6 @@ extern "C" int lqer_build_factors_device(const float* W_dev, int64_t K, int64_t 
         if (st != LQER_OK) return st;
     }
     return pack_factors_and_import(K, N, k, Wc, We, A, B, exp_bits, out);
+} catch (...) {                                      // a host allocation failed: nothing may leave through the C ABI
+    return LQER_ERR_NO_MEMORY;
 }

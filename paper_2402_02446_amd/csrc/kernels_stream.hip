@@ -28,6 +28,7 @@
 // and keeps in LDS as two bf16 terms.  At the end the NWK partial sums of every column group are
 // added through LDS in slice order and stored as fp32, or as MXINT8 blocks of 16 along N for the
 // next layer.  Up to 64 tokens are two blocks of 32 per wavefront sharing each expanded weight operand.
+#include <mutex>
 #include <type_traits>
 
 #include "lqer_internal.h"
@@ -528,13 +529,14 @@ static hipError_t launch_stream_t(const StreamArgs& a, hipStream_t s) {
         return hipErrorInvalidValue;                 // this shape does not fit the 160 KB of LDS
     } else {
         auto kern = stream_kernel<G, NWC, NWK, DT, LR, ONE, KSP>;
-        static bool attr_set = false;
-        if (!attr_set) {
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
+        // the dynamic LDS limit of this instance, set once per process (calls may come from several threads)
+        static std::once_flag once;
+        static hipError_t attr_err = hipSuccess;
+        std::call_once(once, [&] {
+            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        });
+        if (attr_err != hipSuccess) return attr_err;
         dim3 grid((unsigned)((a.N32 + NWC * G - 1) / (NWC * G) * KSP)), block(64 * NWC * NWK);
         hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, s, a);
         return hipGetLastError();

@@ -28,6 +28,7 @@
 // piece needs pieces that are computed first by the workgroups they belong to: no wait depends on
 // another wait.  The sum order is fixed by the split, so the result has the same bits every run.
 #include <atomic>
+#include <mutex>
 
 #include "lqer_internal.h"
 #include "mx_device.h"
@@ -415,8 +416,12 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
                     p.f[0] = acc[tm][tn][2 * h8]; p.f[1] = acc[tm][tn][2 * h8 + 1];
                     __hip_atomic_store(slot + ((tm * TN + tn) * 8 + h8) * 64, p.q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");          // this wavefront's stores have completed ...
-        __syncthreads();                                                 // ... and everyone else's
+        // The flag may only be raised once every slot store of every wavefront has been acknowledged by the
+        // memory system: a workgroup-scope fence does not wait for outstanding vector stores on this chip
+        // (and a device-scope release would write the XCD's L2 back), so each wavefront drains its own
+        // store counter explicitly, the barrier collects all wavefronts, and only then is the flag stored.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
         if (tid == 0) __hip_atomic_store(a.flags + lin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         continue;
     }
@@ -595,14 +600,31 @@ static bool split_pays(const TileShape& sh, int64_t tiles, int64_t KT, int cus) 
     return time_split(sh, tiles, KT, cus) < 0.95 * time_whole(sh, tiles, KT, cus);
 }
 
+// What has to be established once per kernel instance and process: the dynamic LDS limit, and how many of its
+// workgroups one compute unit really holds (the work split launches exactly as many workgroups as are resident
+// at once, because owners wait for flags that later workgroups raise).
+struct KernelSetup {
+    std::once_flag once;
+    hipError_t err = hipSuccess;
+    int resident = 0;            // workgroups per compute unit
+};
+
 template <typename Kern>
-static hipError_t launch_kernel(Kern kern, bool& attr_set, int lds_bytes, int64_t grid_x, int threads, const TiledArgs& a, hipStream_t s) {
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+static hipError_t prepare_kernel(Kern kern, KernelSetup& ks, int lds_bytes, int threads) {
+    std::call_once(ks.once, [&] {
+        ks.err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (ks.err != hipSuccess) return;
+        int n = 0;
+        ks.err = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, threads, (size_t)lds_bytes);
+        ks.resident = n;
+    });
+    return ks.err;
+}
+
+template <typename Kern>
+static hipError_t launch_kernel(Kern kern, KernelSetup& ks, int lds_bytes, int64_t grid_x, int threads, const TiledArgs& a, hipStream_t s) {
+    const hipError_t e = prepare_kernel(kern, ks, lds_bytes, threads);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid_x), dim3(threads), lds_bytes, s, a);
     return hipGetLastError();
 }
@@ -619,11 +641,21 @@ static hipError_t launch_tiled_t(TiledArgs a, int64_t M, int mode, int cus, hipS
     TileShape me = {0, BM, BN, MINW, 1.0, 1.0, 1.0};
     for (const TileShape& sh : kShapes)
         if (sh.bm == BM && sh.bn == BN && sh.share == MINW) me = sh;
+    static KernelSetup setup_split, setup_whole;
+    // The split launches one workgroup per slot and its owners wait for workgroups with higher numbers: all of
+    // them must be resident at once.  The number the runtime reports for this instance decides, not the launch
+    // bounds; should it ever be lower than the shape assumes, tiles are not cut.
+    bool can_split = CAN_SPLIT;
+    if constexpr (CAN_SPLIT) {
+        const hipError_t e = prepare_kernel(tiled_kernel<TM, TN, WR, WC, NS, MINW, true>, setup_split, LDS_BYTES, 64 * WR * WC);
+        if (e != hipSuccess) return e;
+        if (setup_split.resident < MINW) can_split = false;
+    }
     const int64_t slots = (int64_t)cus * MINW;
     // mode 0: split when the estimate says so; 1: never; 2: whenever there is a remainder to split; 3: the same, always in
     // equal shares of the remaining K tiles (never along tile boundaries)
     bool split = false;
-    if (CAN_SPLIT && a.Part != nullptr && (int64_t)BM * BN * 4 * slots <= kTiledPartBytesPerCu * (int64_t)cus && slots <= kTiledFlags) {
+    if (can_split && a.Part != nullptr && (int64_t)BM * BN * 4 * slots <= kTiledPartBytesPerCu * (int64_t)cus && slots <= kTiledFlags) {
         if (mode >= 2) split = true;
         else if (mode == 0) split = split_pays(me, tiles, a.KT, cus);
     }
@@ -631,13 +663,10 @@ static hipError_t launch_tiled_t(TiledArgs a, int64_t M, int mode, int cus, hipS
     const Split sp = split ? split_tiles(tiles, a.KT, slots, mode != 3) : whole_tiles(tiles, a.KT);
     a.dp_tiles = sp.dp_tiles; a.sk_units = sp.sk_units; a.sk_share = sp.sk_share; a.sk_tile_units = sp.sk_tile_units;
     if constexpr (CAN_SPLIT) {
-        if (sp.sk_units > 0) {
-            static bool attr_split = false;
-            return launch_kernel(tiled_kernel<TM, TN, WR, WC, NS, MINW, true>, attr_split, LDS_BYTES, sp.grid, 64 * WR * WC, a, s);
-        }
+        if (sp.sk_units > 0)
+            return launch_kernel(tiled_kernel<TM, TN, WR, WC, NS, MINW, true>, setup_split, LDS_BYTES, sp.grid, 64 * WR * WC, a, s);
     }
-    static bool attr_whole = false;
-    return launch_kernel(tiled_kernel<TM, TN, WR, WC, NS, MINW, false>, attr_whole, LDS_BYTES, tiles, 64 * WR * WC, a, s);
+    return launch_kernel(tiled_kernel<TM, TN, WR, WC, NS, MINW, false>, setup_whole, LDS_BYTES, tiles, 64 * WR * WC, a, s);
 }
 
 __global__ void clear_flags_kernel(uint32_t* flags, int n) {

@@ -388,6 +388,7 @@ const char* lqer_status_string(int status) {
         case LQER_ERR_HIP: return "HIP runtime error";
         case LQER_ERR_NO_CONVERGENCE: return "truncated SVD did not converge";
         case LQER_ERR_VALUE: return "packed bytes hold an excluded value";
+        case LQER_ERR_NO_MEMORY: return "host allocation failed";
         default: return "unknown status";
     }
 }
@@ -416,7 +417,7 @@ int lqer_layer_import(int64_t K, int64_t N, int k, const uint8_t* Wc, const uint
     const int kp = (k + 15) / 16 * 16;
     if (kp > 64) return LQER_ERR_UNSUPPORTED;
     lqer_layer* h = new (std::nothrow) lqer_layer;
-    if (!h) return LQER_ERR_HIP;
+    if (!h) return LQER_ERR_NO_MEMORY;
     Layer& L = h->L;
     L.K = K; L.N = N; L.k = k; L.kp = kp;
     L.KT = (K + kTileK - 1) / kTileK;
@@ -428,21 +429,25 @@ int lqer_layer_import(int64_t K, int64_t N, int k, const uint8_t* Wc, const uint
     L.Wt = L.At = L.Bt = nullptr;
     if (hipGetDevice(&L.device) != hipSuccess) { delete h; return LQER_ERR_HIP; }
     int st;
-    {
-        std::vector<uint8_t> buf;
-        st = tile_weights(L, Wc, We, buf);
-        if (st == LQER_OK) st = upload(buf, &L.Wt);
-    }
-    if (st == LQER_OK && kp > 0) {
-        std::vector<uint8_t> buf;
-        st = tile_a(L, Ac, Ae, buf);
-        if (st == LQER_OK) st = upload(buf, &L.At);
-        if (st == LQER_OK) h->Ae_host.assign(Ae, Ae + (size_t)kp * (K / 16));
-    }
-    if (st == LQER_OK && kp > 0) {
-        std::vector<uint8_t> buf;
-        st = tile_b(L, Bc, Be, buf);
-        if (st == LQER_OK) st = upload(buf, &L.Bt);
+    try {
+        {
+            std::vector<uint8_t> buf;
+            st = tile_weights(L, Wc, We, buf);
+            if (st == LQER_OK) st = upload(buf, &L.Wt);
+        }
+        if (st == LQER_OK && kp > 0) {
+            std::vector<uint8_t> buf;
+            st = tile_a(L, Ac, Ae, buf);
+            if (st == LQER_OK) st = upload(buf, &L.At);
+            if (st == LQER_OK) h->Ae_host.assign(Ae, Ae + (size_t)kp * (K / 16));
+        }
+        if (st == LQER_OK && kp > 0) {
+            std::vector<uint8_t> buf;
+            st = tile_b(L, Bc, Be, buf);
+            if (st == LQER_OK) st = upload(buf, &L.Bt);
+        }
+    } catch (...) {                                  // a host allocation failed: nothing may leave through the C ABI
+        st = LQER_ERR_NO_MEMORY;
     }
     if (st != LQER_OK) {
         free_device(L);
@@ -457,6 +462,7 @@ int lqer_layer_export(const lqer_layer* layer, uint8_t* Wc, uint8_t* We, int8_t*
                       uint8_t* Be) {
     if (!layer) return LQER_ERR_NULL;
     const Layer& L = layer->L;
+    try {
     std::vector<uint8_t> buf;
     int st;
     if (Wc || We) {
@@ -475,6 +481,9 @@ int lqer_layer_export(const lqer_layer* layer, uint8_t* Wc, uint8_t* We, int8_t*
         untile_b(L, buf, Bc, Be);
     }
     return LQER_OK;
+    } catch (...) {                                  // a host allocation failed
+        return LQER_ERR_NO_MEMORY;
+    }
 }
 
 int lqer_layer_dims(const lqer_layer* layer, int64_t* K, int64_t* N, int* k, int* kp) {

@@ -147,8 +147,8 @@ def random_packed_layer(rng: np.random.Generator, K: int, N: int, k: int):
     uniformly from [-7, 7] with exponent bytes near 2^-6, int8 factor codes with exponents near
     2^-8 (A_k) and 2^-10 (B_k).  Returns a dict of the six canonical arrays plus kp."""
     kp = ((k + 15) // 16) * 16
-    nib = rng.integers(1, 16, size=(N, K), dtype=np.uint8)            # two's-complement nibbles, never -8
-    nib[nib >= 8] += 1                                                # 8..14 -> 9..15  (codes -7..-1)
+    nib = rng.integers(0, 15, size=(N, K), dtype=np.uint8)            # 15 values: the codes -7 .. 7
+    nib[nib >= 8] += 1                                                # 8..14 -> 9..15 (codes -7..-1); nibble 8 (-8) never occurs
     Wc = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
     We = rng.integers(119, 123, size=(N, K // 16), dtype=np.uint8)
     Ac = rng.integers(-127, 128, size=(kp, K)).astype(np.int8)
