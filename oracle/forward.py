@@ -38,6 +38,42 @@ def forward(X, layer: PackedLayer, act_bits: int = H_BITS) -> np.ndarray:
     return forward_q(Xc, Xe, layer, act_bits)
 
 
+def forward_cols(X, layer: PackedLayer, cols, act_bits: int = H_BITS) -> np.ndarray:
+    """Y[:, cols] of `forward` (Eq. 3, Eq. 6) for layers too wide to dequantize whole: only the
+    selected output columns of W_q and B_k are expanded; A_k and T are the full ones."""
+    cols = np.asarray(cols)
+    Xc, Xe = quantize_activations(X, act_bits)
+    X_hat = mxint.mx_dequantize(Xc, Xe, act_bits, axis=-1)
+    W_sub = mxint.mx_dequantize(mxint.unpack_int4(layer.Wc[cols]), layer.We[cols], W_BITS, axis=1).T      # [K][len(cols)]
+    A_hat = mxint.mx_dequantize(layer.Ac, layer.Ae, H_BITS, axis=1).T                                     # [K][kp]
+    B_sub = mxint.mx_dequantize(layer.Bc[cols], layer.Be[cols], H_BITS, axis=1).T                         # [kp][len(cols)]
+    T = X_hat @ A_hat
+    return X_hat @ W_sub + T @ B_sub
+
+
+def forward_magnitudes(X, layer: PackedLayer, cols=None, act_bits: int = H_BITS):
+    """The sums of absolute values behind every element of Y (Eq. 3, Eq. 6), for elementwise
+    rounding bounds on an implementation that forms exact products and rounds only when adding:
+
+      main[t][j]  = sum_i |X_q[t][i]| |W_q[i][j]|
+      tail[t][j]  = sum_r |T[t][r]| |B_k[r][j]|             with T = X_q A_k
+      proj[t][j]  = sum_r (sum_i |X_q[t][i]| |A_k[i][r]|) |B_k[r][j]|
+
+    A sum of n exact terms added in any order in precision u differs from the exact sum by at most
+    about n u times the sum of the terms' magnitudes (much less in practice); `main` bounds the main
+    product that way, `proj` the rounding inside T carried through B_k, and `tail` both the second
+    product and any rounding of T itself.  Returns (main, tail, proj), fp64, for the columns `cols`."""
+    cols = np.arange(layer.N) if cols is None else np.asarray(cols)
+    Xc, Xe = quantize_activations(X, act_bits)
+    X_abs = np.abs(mxint.mx_dequantize(Xc, Xe, act_bits, axis=-1))
+    X_hat = mxint.mx_dequantize(Xc, Xe, act_bits, axis=-1)
+    W_abs = np.abs(mxint.mx_dequantize(mxint.unpack_int4(layer.Wc[cols]), layer.We[cols], W_BITS, axis=1)).T
+    A_hat = mxint.mx_dequantize(layer.Ac, layer.Ae, H_BITS, axis=1).T
+    B_abs = np.abs(mxint.mx_dequantize(layer.Bc[cols], layer.Be[cols], H_BITS, axis=1)).T
+    T = X_hat @ A_hat
+    return X_abs @ W_abs, np.abs(T) @ B_abs, (X_abs @ np.abs(A_hat)) @ B_abs
+
+
 def forward_int_exact(Xc, Xe, layer: PackedLayer) -> np.ndarray:
     """Same result through integer block dot products (Sec. 2.2).
 

@@ -116,3 +116,63 @@ def test_table1_ordering_on_outlier_heavy_inputs():
         errs.append(np.linalg.norm(forward.forward(X, layer) - ref))
     assert errs[0] >= errs[1] >= errs[2]
     assert errs[2] < 0.9 * errs[0]
+
+
+def test_column_subset_form_equals_the_full_one():
+    # forward_cols is the checker for layers too wide to dequantize whole: every column, a strict
+    # subset in scrambled order with a repeat, and the 6-bit activation width, against forward()
+    _, _, X, layer = _layer(seed=11, K=96, N=80, k=20)
+    Y = forward.forward(X, layer)
+    assert np.array_equal(forward.forward_cols(X, layer, np.arange(layer.N)), Y)
+    cols = np.array([79, 0, 33, 32, 31, 5, 5, 64])
+    sub = forward.forward_cols(X, layer, cols)
+    assert sub.shape == (X.shape[0], len(cols))
+    assert np.allclose(sub, Y[:, cols], rtol=1e-13, atol=1e-18)
+    assert np.allclose(forward.forward_cols(X, layer, cols, act_bits=6), forward.forward(X, layer, act_bits=6)[:, cols],
+                       rtol=1e-13, atol=1e-18)
+    # and against exact rationals on two elements, straight from the bytes
+    Xc, Xe = forward.quantize_activations(X)
+    Wc = mxint.unpack_int4(layer.Wc)
+    two = Fraction(2)
+    for (t, jj) in ((0, 0), (4, 3)):
+        j = int(cols[jj])
+        xh = [int(Xc[t, i]) * two ** (int(Xe[t, i // 16]) - 133) for i in range(layer.K)]
+        T = [sum(xh[i] * int(layer.Ac[r, i]) * two ** (int(layer.Ae[r, i // 16]) - 133) for i in range(layer.K))
+             for r in range(layer.kp)]
+        y = sum(xh[i] * int(Wc[j, i]) * two ** (int(layer.We[j, i // 16]) - 129) for i in range(layer.K))
+        y += sum(T[r] * int(layer.Bc[j, r]) * two ** (int(layer.Be[j, r // 16]) - 133) for r in range(layer.kp))
+        assert abs(float(y) - sub[t, jj]) <= 1e-13 * max(1.0, abs(float(y)))
+
+
+def test_magnitude_sums():
+    # forward_magnitudes feeds the elementwise rounding bound of the GPU tests.  Pins: exact rationals on one
+    # element; with every operand non-negative the sums are the result itself (main + tail = Y, proj = tail);
+    # in general main + tail >= |Y| and proj >= tail (triangle inequality); column subsets select.
+    _, _, X, layer = _layer(seed=12, K=64, N=24, k=16)
+    main, tail, proj = forward.forward_magnitudes(X, layer)
+    Y = forward.forward(X, layer)
+    assert np.all(main + tail >= np.abs(Y) * (1 - 1e-12))
+    assert np.all(proj >= tail * (1 - 1e-12))
+    cols = np.array([3, 20, 7])
+    m2, t2, p2 = forward.forward_magnitudes(X, layer, cols)
+    assert np.array_equal(m2, main[:, cols]) and np.array_equal(t2, tail[:, cols]) and np.array_equal(p2, proj[:, cols])
+    Xc, Xe = forward.quantize_activations(X)
+    Wc = mxint.unpack_int4(layer.Wc)
+    two = Fraction(2)
+    t, j = 2, 7
+    xh = [int(Xc[t, i]) * two ** (int(Xe[t, i // 16]) - 133) for i in range(layer.K)]
+    ah = [[int(layer.Ac[r, i]) * two ** (int(layer.Ae[r, i // 16]) - 133) for i in range(layer.K)] for r in range(layer.kp)]
+    bh = [int(layer.Bc[j, r]) * two ** (int(layer.Be[j, r // 16]) - 133) for r in range(layer.kp)]
+    want_main = sum(abs(xh[i]) * abs(int(Wc[j, i])) * two ** (int(layer.We[j, i // 16]) - 129) for i in range(layer.K))
+    want_tail = sum(abs(sum(xh[i] * ah[r][i] for i in range(layer.K))) * abs(bh[r]) for r in range(layer.kp))
+    want_proj = sum(sum(abs(xh[i]) * abs(ah[r][i]) for i in range(layer.K)) * abs(bh[r]) for r in range(layer.kp))
+    for got, want in ((main[t, j], want_main), (tail[t, j], want_tail), (proj[t, j], want_proj)):
+        assert abs(float(want) - got) <= 1e-13 * float(want)
+    # non-negative operands: the magnitudes are the values
+    pos = factors.PackedLayer(K=layer.K, N=layer.N, k=layer.k, kp=layer.kp,
+                              Wc=mxint.pack_int4(np.abs(Wc).astype(np.int8)), We=layer.We,
+                              Ac=np.abs(layer.Ac), Ae=layer.Ae, Bc=np.abs(layer.Bc), Be=layer.Be)
+    Xp = np.abs(X)
+    main, tail, proj = forward.forward_magnitudes(Xp, pos)
+    assert np.allclose(main + tail, forward.forward(Xp, pos), rtol=1e-13)
+    assert np.allclose(proj, tail, rtol=1e-13)
