@@ -5,23 +5,32 @@
 
 A "step" is one pass of the whole hot path - quantize X to MXINT8, T = X_q A_k,
 Y = X_q W_q + T B_k - over one batch of synthetic activations already resident in HBM.
-The headline workload is the LLaMA-7B-shaped q_proj decode (W 4096 x 4096, k = 32, M = 16); so
-that weights really come from HBM and not from the 256 MB last-level cache, consecutive steps
-walk a ring of distinct layers whose packed weights total more than that cache.
 
-The timed steps are enqueued as one HIP graph (captured once, replayed between two
-synchronisations): decode steps last some 15 microseconds, less than a Python loop needs to
-launch them, so an eager loop would time the interpreter.  The eager figure is reported beside it.
+The headline workload is the largest single-GPU configuration: the LLaMA-2-70B-shaped MLP layer
+(W 8192 x 28672, k = 64) at M = 4096 tokens, the compute-bound regime of Sec. 2.1, priced against the
+dense bf16 MFMA peak.  `cases` holds, first, the same layer at M = 16 and M = 1 (memory-bound regime,
+priced against HBM bandwidth; consecutive steps walk a ring of distinct device copies whose packed
+weights exceed the 256 MB last-level cache, so weights really come from HBM), then the 7B-shaped
+decode and prefill layers, the stand-alone quantizer, the decode-to-prefill sweep of the 70B-shaped
+layer, the seven linears of a 7B decoder block at 65536 tokens for k in {16, 32, 64}, and the offline
+factor construction timed per layer.
 
-Prints ONE JSON line.  `value` is TFLOP/s of the whole step; `roofline` prices the dominant
-kernel (the weight-streaming main kernel) against HBM bandwidth with its duration measured by
-events on the launch stream; `cpu_baseline` is the fp64 oracle timed on the host cores on a
-bounded sample of the same workload; `cases` adds the prefill and 70B-shaped workloads, each
-with its own roofline object.
+Timed steps are enqueued as one HIP graph (captured once, replayed between two synchronisations):
+decode steps last some tens of microseconds, less than a Python loop needs to launch them.  Kernel
+durations come from events on the launch stream around graph replays of one stage alone.
+
+Every roofline object prices a kernel against the vendor peak (`frac`) and against what the same chip
+delivers for a kernel that does nothing else (`frac_measured`: a streaming read with the weight
+kernel's access pattern, a register-resident MFMA loop; csrc/bench_probes.hip), and gives the fraction
+the whole step reaches (`frac_step`).
+
+Prints ONE JSON line.  `cpu_baseline` is the fp64 oracle timed on the host cores on a bounded sample
+of the headline workload.
 """
 from __future__ import annotations
 
 import argparse
+import ctypes as C
 import json
 import os
 import sys
@@ -51,6 +60,11 @@ def bytes_main_kernel(M, K, N, kp):
     """Algorithmic bytes of the main kernel alone: W_q and B_k once, X_q in its MXINT8 form and
     T (fp32) in, fp32 Y out."""
     return K * N * 0.5625 + kp * N * 1.0625 + M * K * 1.0625 + 4.0 * M * kp + 4.0 * M * N
+
+
+def bytes_prep_kernel(M, K, kp):
+    """Algorithmic bytes of the projection kernel at prefill sizes: fp32 X in, bf16 X_q out, A_k once, T out."""
+    return 4.0 * M * K + 2.0 * M * K + K * kp * 1.0625 + 4.0 * M * kp
 
 
 def _event_ms(fn, iters):
@@ -92,22 +106,115 @@ def _graph_ms(fn, iters, reps=3):
     return best
 
 
+# ---- peak probes ---------------------------------------------------------------------------------------------
+
+_probes = None
+
+
+def probes():
+    """liblqer_probes.so (csrc/bench_probes.hip): kernels that only read, only copy, only issue MFMAs."""
+    global _probes
+    if _probes is None:
+        import torch  # noqa: F401  (one HIP runtime for both libraries)
+        path = os.path.join(ROOT, "paper_2402_02446_amd", "liblqer_probes.so")
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it with `python -m paper_2402_02446_amd.build`")
+        L = C.CDLL(path)
+        L.lqer_probe_stream_read.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+        L.lqer_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
+        L.lqer_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        _probes = L
+    return _probes
+
+
+def measure_peaks():
+    """What this chip gives a kernel that does nothing else: HBM read and copy bandwidth on 1 GiB (four times the
+    last-level cache), a read of 132 MB (the 70B-shaped layer's weight bytes, as a ring of five buffers so that
+    each pass comes from HBM), and the 32x32x16 bf16 MFMA rate with one and with two wavefronts per SIMD."""
+    import torch
+    P = probes()
+    cur = lambda: torch.cuda.current_stream().cuda_stream      # read per call: a graph capture runs on a stream of its own
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    big = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")          # 1 GiB
+    dst = torch.empty_like(big)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+
+    def chk(rc):
+        if rc != 0:
+            raise RuntimeError(f"probe launch failed: hip error {rc}")
+
+    out = {}
+    nbytes = big.numel() * 4
+    best = (0.0, None)
+    for wgs in (cus * 2, cus * 4, cus * 8, cus * 16):
+        for fl in (4, 8, 16):
+            f = lambda i: chk(P.lqer_probe_stream_read(big.data_ptr(), nbytes, sink.data_ptr(), wgs, fl, cur()))
+            f(0)
+            gbs = nbytes / (min(_event_ms(f, 4) for _ in range(2)) * 1e-3) / 1e9
+            if gbs > best[0]:
+                best = (gbs, (wgs, fl))
+    out["hbm_read_gbs"] = best[0]
+    out["hbm_read_best_launch"] = {"workgroups_of_256": best[1][0], "loads_of_1KiB_in_flight_per_wavefront": best[1][1]}
+    f = lambda i: chk(P.lqer_probe_copy(big.data_ptr(), dst.data_ptr(), nbytes, cus * 8, cur()))
+    f(0)
+    ms = min(_event_ms(f, 5) for _ in range(3))
+    out["hbm_copy_gbs"] = 2.0 * nbytes / (ms * 1e-3) / 1e9
+    # the weight bytes of the 70B-shaped layer, ring of five distinct ranges of the 1 GiB buffer
+    wbytes = int(8192 * 28672 * 0.5625) // 1024 * 1024
+    wgs, fl = best[1]
+    f = lambda i: chk(P.lqer_probe_stream_read(big.data_ptr() + (i % 5) * (200 << 20), wbytes, sink.data_ptr(), min(wgs, cus * 4), fl, cur()))
+    for i in range(5):
+        f(i)
+    ms = min(_graph_ms(f, 20) for _ in range(2))
+    out["hbm_read_132MB_us"] = ms * 1e3
+    out["hbm_read_132MB_gbs"] = wbytes / (ms * 1e-3) / 1e9
+    del big, dst
+    for waves, key in ((1, "mfma_bf16_tflops_1wave_per_simd"), (2, "mfma_bf16_tflops_2waves_per_simd")):
+        iters, chains = 4096, 8 if waves == 1 else 4
+        wgs = cus * waves
+        f = lambda i: chk(P.lqer_probe_mfma(wgs, iters, chains, sink.data_ptr(), cur()))
+        f(0)
+        ms = min(_event_ms(f, 3) for _ in range(3))
+        out[key] = wgs * 4 * iters * chains * 32768.0 / (ms * 1e-3) / 1e12
+    out["mfma_bf16_tflops"] = max(out["mfma_bf16_tflops_1wave_per_simd"], out["mfma_bf16_tflops_2waves_per_simd"])
+    out["source"] = "csrc/bench_probes.hip, timed by events in this run"
+    return out
+
+
+def roofline(bound, kernel, work, ms_kernel, ms_step, work_step, peaks, traffic=None):
+    """One roofline object: `work` algorithmic bytes (hbm) or flops (mfma) of the kernel per launch."""
+    if bound == "hbm":
+        ach, peak, unit = work / (ms_kernel * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
+        meas = peaks.get("hbm_read_gbs") if peaks else None
+        step = work_step / (ms_step * 1e-3) / 1e9 if ms_step else None
+    else:
+        ach, peak, unit = work / (ms_kernel * 1e-3) / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+        meas = peaks.get("mfma_bf16_tflops") if peaks else None
+        step = work_step / (ms_step * 1e-3) / 1e12 if ms_step else None
+    r = {"bound": bound, "kernel": kernel, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
+         "traffic": traffic}
+    if meas:
+        r["peak_measured"] = meas
+        r["frac_measured"] = ach / meas
+    if step is not None:
+        r["achieved_step"] = step
+        r["frac_step"] = step / peak
+    return r
+
+
 def make_ring(rng, K, N, k, min_bytes):
-    """A ring of distinct layers (random canonical bytes) whose packed weights exceed min_bytes."""
+    """A ring of distinct device copies of one layer (random canonical bytes) whose packed weights exceed
+    min_bytes: what decides whether a step finds its weights in the last-level cache is their addresses."""
     from paper_2402_02446_amd import binding, synth
     per = K * N * 0.5625
     n = max(1, int(np.ceil(min_bytes / per)))
-    layers, packed0 = [], None
-    for i in range(n):
-        d = synth.random_packed_layer(rng, K, N, k)
-        if packed0 is None:
-            packed0 = d
-        layers.append(binding.lqer_layer_import(K, N, k, d["Wc"], d["We"], d["Ac"], d["Ae"], d["Bc"], d["Be"]))
-    return layers, packed0
+    d = synth.random_packed_layer(rng, K, N, k)
+    layers = [binding.lqer_layer_import(K, N, k, d["Wc"], d["We"], d["Ac"], d["Ae"], d["Bc"], d["Be"]) for _ in range(n)]
+    return layers, d
 
 
-def run_case(name, K, N, k, Ms, steps, warmup, rng, ring_bytes, gain, bound):
-    """Times the whole step and the main kernel alone for every M in Ms on one ring of layers.
+def run_case(name, K, N, k, Ms, steps, warmup, rng, ring_bytes, gain, peaks):
+    """Times the whole step and each kernel alone for every M in Ms on one ring of layers.
     Returns (list of result dicts, context of the first M for the oracle leg)."""
     import torch
     from paper_2402_02446_amd import binding, synth
@@ -161,29 +268,27 @@ def run_case(name, K, N, k, Ms, steps, warmup, rng, ring_bytes, gain, bound):
             "tflops": fl / (ms_step * 1e-3) / 1e12,
             "gbs_step": bytes_forward(M, K, N, kp) / (ms_step * 1e-3) / 1e9,
         }
-        if bound == "hbm" or path == 1:
-            ach = bytes_main_kernel(M, K, N, kp) / (ms_main * 1e-3) / 1e9
-            res["roofline"] = {"bound": "hbm", "kernel": "stream_kernel", "achieved": ach,
-                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                               "traffic": None}
+        if path == 1:
+            res["roofline"] = roofline("hbm", "stream_kernel", bytes_main_kernel(M, K, N, kp), ms_main, ms_step,
+                                       bytes_forward(M, K, N, kp), peaks)
         else:
-            ach = fl / (ms_main * 1e-3) / 1e12
-            res["roofline"] = {"bound": "mfma", "kernel": "tiled_kernel", "achieved": ach,
-                               "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                               "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+            res["roofline"] = roofline("mfma", "tiled_kernel", fl, ms_main, ms_step, fl, peaks)
+            if M >= 2048:
+                res["roofline_prep_kernel"] = roofline("hbm", "prep_kernel", bytes_prep_kernel(M, K, kp), ms_prep, None, None, peaks)
         results.append(res)
         if ctx0 is None:
             # leave the result of layer 0 in Y for the oracle leg
             binding.lqer_linear_forward(layers[0], X, Y=Y)
             torch.cuda.synchronize()
-            ctx0 = dict(packed=packed0, X=X_np, Y=Y.cpu().numpy())
+            rows = min(M, 64)
+            ctx0 = dict(packed=packed0, X=X_np[:rows], Y=Y[:rows].cpu().numpy(), M=M)
         del X, Y
     for l in layers:
         l.free()
     return results, ctx0
 
 
-def run_quantizer_case(rows, cols, steps, rng):
+def run_quantizer_case(rows, cols, steps, rng, peaks):
     """lqer_quantize_mx alone on a cfg5-sized activation matrix: HBM-bound, 5.0625 B per element."""
     import torch
     from paper_2402_02446_amd import binding
@@ -193,17 +298,20 @@ def run_quantizer_case(rows, cols, steps, rng):
     f(0)
     torch.cuda.synchronize()
     ms = _event_ms(f, steps)
-    ach = rows * cols * 5.0625 / (ms * 1e-3) / 1e9
+    r = roofline("hbm", "quantize_mx_kernel", rows * cols * 5.0625, ms, None, None, peaks)
+    if peaks:
+        # a quantizer reads 4 bytes and writes 1.0625 per element: the copy probe is the closer measured peak
+        r["peak_measured"] = peaks["hbm_copy_gbs"]
+        r["frac_measured"] = r["achieved"] / peaks["hbm_copy_gbs"]
     return {"workload": "a1 quantizer alone, %d x %d fp32 -> MXINT8" % (rows, cols), "M": rows, "K": cols,
-            "ms_per_call": ms,
-            "roofline": {"bound": "hbm", "kernel": "quantize_mx_kernel", "achieved": ach, "peak": HBM_PEAK_GBS,
-                         "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}}
+            "ms_per_call": ms, "roofline": r}
 
 
-def run_cfg5(steps, rng):
+def run_cfg5(steps, rng, peaks):
     """cfg5: the seven LQER linears of a LLaMA-7B decoder block at M = 32 x 2048 tokens, k in
     {16, 32, 64}; activations are drawn on the device (N(0,1), 1 % of channels x 50).  Returns one
-    record per k with the per-shape times and the whole block's TFLOP/s."""
+    record per k with the per-shape times (whole step, projection kernel, main kernel) and the whole
+    block's TFLOP/s, as seven separate calls and with one quantization per q/k/v and gate/up."""
     import torch
     from paper_2402_02446_amd import binding, synth
     M = synth.CFG5_M
@@ -212,61 +320,71 @@ def run_cfg5(steps, rng):
         shapes.setdefault((K, N), []).append(name)
     out = []
     g = torch.Generator(device="cuda").manual_seed(int(rng.integers(1 << 31)))
+    Xs = {}
+    for K in (4096, 11008):
+        X = torch.randn((M, K), generator=g, device="cuda", dtype=torch.float32)
+        ch = torch.from_numpy(synth.gen_outlier_channels(rng, K, max(1, round(0.01 * K)))).cuda()
+        X[:, ch] *= 50.0
+        Xs[K] = X
+    med = lambda f, n: sorted(_event_ms(f, n) for _ in range(3))[1]
     for k in (16, 32, 64):
-        total_ms, total_fl, per_shape = 0.0, 0.0, []
+        total_ms, total_fl, per_shape, packed = 0.0, 0.0, [], {}
         for (K, N), names in shapes.items():
             d = synth.random_packed_layer(rng, K, N, k)
+            packed[(K, N)] = d
             layer = binding.lqer_layer_import(K, N, k, d["Wc"], d["We"], d["Ac"], d["Ae"], d["Bc"], d["Be"])
-            X = torch.randn((M, K), generator=g, device="cuda", dtype=torch.float32)
-            ch = torch.from_numpy(synth.gen_outlier_channels(rng, K, max(1, round(0.01 * K)))).cuda()
-            X[:, ch] *= 50.0
+            X = Xs[K]
             Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
             f = lambda i: binding.lqer_linear_forward(layer, X, Y=Y)
+            f_prep = lambda i: binding.lqer_linear_forward_ex(layer, X, Y=Y, stages=1)
+            f_main = lambda i: binding.lqer_linear_forward_ex(layer, X, Y=Y, stages=2)
             f(0)
             torch.cuda.synchronize()
-            ms = sorted(_event_ms(f, steps) for _ in range(3))[1]
+            ms, ms_prep, ms_main = med(f, steps), med(f_prep, steps), med(f_main, steps)
             fl = flops_forward(M, K, N, layer.kp)
-            per_shape.append({"K": K, "N": N, "linears": names, "ms_per_linear": ms,
-                              "tflops": fl / (ms * 1e-3) / 1e12})
+            per_shape.append({"K": K, "N": N, "linears": names, "ms_per_linear": ms, "ms_prep_kernel": ms_prep,
+                              "ms_main_kernel": ms_main, "tflops": fl / (ms * 1e-3) / 1e12,
+                              "roofline": roofline("mfma", "tiled_kernel", fl, ms_main, ms, fl, peaks),
+                              "roofline_prep_kernel": roofline("hbm", "prep_kernel", bytes_prep_kernel(M, K, layer.kp),
+                                                               ms_prep, None, None, peaks)})
             total_ms += ms * len(names)
             total_fl += fl * len(names)
             layer.free()
-            del X, Y
+            del Y
         # q/k/v and gate/up consume the same activations: one quantization per group (lqer_linear_forward_shared)
         shared, saved_ms = [], 0.0
         for names, K, N in ((("q", "k", "v"), 4096, 4096), (("gate", "up"), 4096, 11008)):
-            group = []
-            for _ in names:
-                d = synth.random_packed_layer(rng, K, N, k)
-                group.append(binding.lqer_layer_import(K, N, k, d["Wc"], d["We"], d["Ac"], d["Ae"], d["Bc"], d["Be"]))
-            X = torch.randn((M, K), generator=g, device="cuda", dtype=torch.float32)
+            d = packed[(K, N)]
+            group = [binding.lqer_layer_import(K, N, k, d["Wc"], d["We"], d["Ac"], d["Ae"], d["Bc"], d["Be"]) for _ in names]
+            X = Xs[K]
             Ys = [torch.empty((M, N), dtype=torch.float32, device="cuda") for _ in names]
             ws = torch.empty(binding.lqer_linear_shared_workspace_bytes(group, M), dtype=torch.uint8, device="cuda")
             f_sh = lambda i: binding.lqer_linear_forward_shared(group, X, Ys=Ys, workspace=ws)
             f_sep = lambda i: [binding.lqer_linear_forward(l, X, Y=y, workspace=ws) for l, y in zip(group, Ys)]
             f_sh(0); f_sep(0)
             torch.cuda.synchronize()
-            ms_sh = sorted(_event_ms(f_sh, steps) for _ in range(3))[1]
-            ms_sep = sorted(_event_ms(f_sep, steps) for _ in range(3))[1]
+            ms_sh, ms_sep = med(f_sh, steps), med(f_sep, steps)
             shared.append({"linears": list(names), "ms_shared": ms_sh, "ms_separate": ms_sep})
             saved_ms += ms_sep - ms_sh
             for l in group:
                 l.free()
-            del X, Ys, ws
+            del Ys, ws
+        tf = total_fl / (total_ms * 1e-3) / 1e12
+        tf_sh = total_fl / ((total_ms - saved_ms) * 1e-3) / 1e12
         out.append({"workload": "cfg5: LLaMA-7B decoder block, 7 LQER linears, M=%d" % M, "k": k,
-                    "ms_per_block": total_ms, "tflops": total_fl / (total_ms * 1e-3) / 1e12,
-                    "frac_of_mfma_peak": total_fl / (total_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                    "ms_per_block": total_ms, "tflops": tf, "frac_of_mfma_peak": tf / MFMA_BF16_PEAK_TFLOPS,
                     "per_shape": per_shape, "shared_activations": shared,
-                    "ms_per_block_shared": total_ms - saved_ms,
-                    "tflops_shared": total_fl / ((total_ms - saved_ms) * 1e-3) / 1e12})
+                    "ms_per_block_shared": total_ms - saved_ms, "tflops_shared": tf_sh,
+                    "frac_of_mfma_peak_shared": tf_sh / MFMA_BF16_PEAK_TFLOPS})
     return out
 
 
-def run_crossover(rng, steps=10):
+def run_crossover(rng, peaks, steps=10):
     """cfg4: the 70B-shaped MLP layer swept over M = 1 .. 4096 to locate where the forward pass stops
     being bound by the weight stream (Sec. 2.1: memory-bound few-token regime against compute-bound
     prefill).  One layer (132 MB of weights, so successive steps may find part of it in the 256 MB
-    last-level cache: this sweep compares M against M, it is not a bandwidth claim)."""
+    last-level cache: this sweep compares M against M, it is not a bandwidth claim).  Each point gives the
+    whole step against the roofline that binds at that M: max(bytes / 8 TB/s, flops / 2.5 PFLOP/s)."""
     import torch
     from paper_2402_02446_amd import binding, synth
     K, N, k = 8192, 28672, 64
@@ -277,18 +395,25 @@ def run_crossover(rng, steps=10):
         X = torch.randn((M, K), device="cuda", dtype=torch.float32)
         Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
         f = lambda i: binding.lqer_linear_forward(layer, X, Y=Y)
+        f_main = lambda i: binding.lqer_linear_forward_ex(layer, X, Y=Y, stages=2)
         f(0)
         torch.cuda.synchronize()
         ms = _graph_ms(f, steps)
+        ms_main = _graph_ms(f_main, steps)
+        fl, by = flops_forward(M, K, N, layer.kp), bytes_forward(M, K, N, layer.kp)
+        t_hbm, t_mfma = by / (HBM_PEAK_GBS * 1e9) * 1e3, fl / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e3
         out.append({"M": M, "path": "streaming" if binding.lqer_linear_path(layer, M) == 1 else "tiled",
-                    "ms_per_step": ms, "tflops": flops_forward(M, K, N, layer.kp) / (ms * 1e-3) / 1e12,
-                    "gbs": bytes_forward(M, K, N, layer.kp) / (ms * 1e-3) / 1e9})
+                    "ms_per_step": ms, "ms_main_kernel": ms_main, "tflops": fl / (ms * 1e-3) / 1e12, "gbs": by / (ms * 1e-3) / 1e9,
+                    "bound": "hbm" if t_hbm >= t_mfma else "mfma",
+                    "frac_step_of_binding_roofline": max(t_hbm, t_mfma) / ms,
+                    "frac_main_kernel_of_binding_roofline": max(t_hbm, t_mfma) / ms_main})
         del X, Y
     layer.free()
     # the ridge: smallest M whose step takes 1.5 x the M = 1 step or more
     base = out[0]["ms_per_step"]
     ridge = next((r["M"] for r in out if r["ms_per_step"] >= 1.5 * base), None)
-    return {"workload": "cfg4: 8192 x 28672, k = 64, whole step", "sweep": out, "first_M_at_1p5x_of_M1": ridge}
+    return {"workload": "cfg4: 8192 x 28672, k = 64, whole step", "sweep": out, "first_M_at_1p5x_of_M1": ridge,
+            "ideal_ridge_M": 88}
 
 
 def run_added_rows(rng):
@@ -346,19 +471,22 @@ def time_build_factors(rng):
     return res
 
 
-def cpu_baseline(ctx, M, K, N, kp, budget_s=12.0):
-    """The oracle as it stands, timed on this machine's host cores on the headline workload, and the
-    GPU result checked against it.  Only this function touches oracle/."""
+def cpu_baseline(ctx, K, N, kp, budget_s=20.0):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the headline workload
+    (its first rows: rows are independent, so the cost per row is the same for the rest, apart from the
+    dequantization of the layer, which the oracle repeats per call), and the GPU result of those rows checked
+    against it.  Only this function touches oracle/."""
     from oracle import factors, forward
     p = ctx["packed"]
     layer = factors.PackedLayer(K=p["K"], N=p["N"], k=p["k"], kp=p["kp"], Wc=p["Wc"], We=p["We"],
                                 Ac=p["Ac"], Ae=p["Ae"], Bc=p["Bc"], Be=p["Be"])
     X = ctx["X"]
+    rows = X.shape[0]
     t0 = time.perf_counter()
     Yref = forward.forward(X, layer)
     first = time.perf_counter() - t0
     reps, total = 1, first
-    while total < budget_s and reps < 50:
+    while total + first < budget_s and reps < 50:
         t0 = time.perf_counter()
         forward.forward(X, layer)
         total += time.perf_counter() - t0
@@ -376,10 +504,11 @@ def cpu_baseline(ctx, M, K, N, kp, budget_s=12.0):
             cores = min(cores, max(blas))
     except Exception:
         pass
-    return {"value": flops_forward(M, K, N, kp) / sec / 1e12, "unit": "TFLOP/s", "cores": cores,
+    return {"value": flops_forward(rows, K, N, kp) / sec / 1e12, "unit": "TFLOP/s", "cores": cores,
             "kind": "oracle", "seconds_per_forward": sec,
-            "sample": f"whole forward of the headline workload (M={M}, {K}x{N}, kp={kp}) in fp64 numpy, "
-                      f"{reps} repetitions",
+            "sample": f"the first {rows} of the headline workload's {ctx['M']} token rows, all {N} output columns "
+                      f"({K}x{N}, kp={kp}), whole oracle forward in fp64 numpy (layer dequantized per call), "
+                      f"{reps} repetition(s); flops counted for those {rows} rows",
             "gpu_vs_oracle_rel_frobenius": err}
 
 
@@ -387,35 +516,47 @@ PMC_COPY_BYTES = 1 << 30
 
 
 def pmc_probe(rng, which):
-    """Workload for `rocprofv3 --pmc` runs.  `headline`: a plain copy of known size (the calibration of
-    FETCH_SIZE / WRITE_SIZE) followed by the headline ring; `cfg4_decode` / `cfg4_prefill`: the
-    70B-shaped layer at M = 16 / M = 4096 (ring of layers for the decode case), for the counters
-    that show what the streaming and the tiled kernel wait for."""
+    """Workload for `rocprofv3 --pmc` runs.  Every probe starts with three plain copies of 1 GiB
+    (copy_kernel of csrc/bench_probes.hip: reads and writes PMC_COPY_BYTES), which calibrate FETCH_SIZE /
+    WRITE_SIZE in the same run.  `headline` / `cfg4_prefill`: the 70B-shaped layer at M = 4096;
+    `cfg4_decode`: the same layer at M = 16 on a ring of device copies; `cfg2_decode`: the 7B-shaped
+    q_proj at M = 16 on its ring; `cfg3`: the two 7B-shaped MLP layers at M = 2048; `cfg5_prep`: the 7B block's
+    4096- and 11008-wide linears at M = 65536 (projection kernel and main kernel)."""
     import torch
     from paper_2402_02446_amd import binding, synth
     if which == "build":
         print(json.dumps({"build_factors_seconds_per_layer": time_build_factors(rng)}))
         return
-    if which == "headline":
-        src = torch.ones(PMC_COPY_BYTES // 4, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.add(src, 1.0, out=dst)          # one elementwise kernel: reads and writes PMC_COPY_BYTES
-        torch.cuda.synchronize()
-        M, K, N, k, ring, reps = 16, 4096, 4096, 32, 1.25 * LLC_BYTES, 3
-    elif which == "cfg4_decode":
-        M, K, N, k, ring, reps = 16, 8192, 28672, 64, 2.1 * LLC_BYTES, 5
-    else:
-        M, K, N, k, ring, reps = 4096, 8192, 28672, 64, 0, 6
-    layers, _ = make_ring(rng, K, N, k, ring)
-    ch = synth.gen_outlier_channels(rng, K, max(1, round(0.01 * K)))
-    X = torch.from_numpy(synth.gen_activations(rng, M, K, ch, 50.0)).cuda()
-    Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
-    for rep in range(reps):
-        for l in layers:
-            binding.lqer_linear_forward(l, X, Y=Y)
+    src = torch.ones(PMC_COPY_BYTES // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        rc = probes().lqer_probe_copy(src.data_ptr(), dst.data_ptr(), PMC_COPY_BYTES, 2048, torch.cuda.current_stream().cuda_stream)
+        assert rc == 0
     torch.cuda.synchronize()
-    print("pmc-probe %s done: %d-layer ring x%d at M=%d" % (which, len(layers), reps, M))
+    del src, dst
+    plans = {
+        "headline": [(4096, 8192, 28672, 64, 0, 6)], "cfg4_prefill": [(4096, 8192, 28672, 64, 0, 6)],
+        "cfg4_decode": [(16, 8192, 28672, 64, 2.1 * LLC_BYTES, 5)],
+        "cfg2_decode": [(16, 4096, 4096, 32, 1.25 * LLC_BYTES, 3)],
+        "cfg3": [(2048, 4096, 11008, 32, 0, 10), (2048, 11008, 4096, 32, 0, 10)],
+        "cfg5_prep": [(65536, 4096, 4096, 32, 0, 4), (65536, 11008, 4096, 32, 0, 4)],
+    }
+    for (M, K, N, k, ring, reps) in plans[which]:
+        layers, _ = make_ring(rng, K, N, k, ring)
+        if M >= 65536:
+            X = torch.randn((M, K), device="cuda", dtype=torch.float32)
+        else:
+            ch = synth.gen_outlier_channels(rng, K, max(1, round(0.01 * K)))
+            X = torch.from_numpy(synth.gen_activations(rng, M, K, ch, 50.0)).cuda()
+        Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        for rep in range(reps):
+            for l in layers:
+                binding.lqer_linear_forward(l, X, Y=Y)
+        torch.cuda.synchronize()
+        print("pmc-probe %s done: %d-layer ring x%d at M=%d, %dx%d" % (which, len(layers), reps, M, K, N))
+        for l in layers:
+            l.free()
+        del X, Y
 
 
 def read_pmc_traffic(kernel):
@@ -435,15 +576,15 @@ def read_pmc_traffic(kernel):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--cases", default="all", choices=["headline", "all", "full"],
-                    help="headline: cfg2 only; all: + cfg3, cfg4 and the quantizer; full: + cfg5 and build_factors timing")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--cases", default="all", choices=["headline", "all"],
+                    help="headline: the 70B-shaped layer at M = 4096 only; all (default): every workload")
     ap.add_argument("--pmc-probe", nargs="?", const="headline", default=None,
-                    choices=["headline", "cfg4_decode", "cfg4_prefill", "build"],
-                    help="run one workload a few times and exit, for rocprofv3 runs (headline: after a "
-                         "plain 1 GiB copy that calibrates the byte counters; build: the offline step per "
-                         "layer shape of cfg5, host and device path, timings printed as JSON)")
+                    choices=["headline", "cfg4_decode", "cfg4_prefill", "cfg2_decode", "cfg3", "cfg5_prep", "build"],
+                    help="run one workload a few times and exit, for rocprofv3 runs (each after plain 1 GiB "
+                         "copies that calibrate the byte counters; build: the offline step per layer shape "
+                         "of cfg5, host and device path, timings printed as JSON)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (sharding the layer over "
@@ -461,42 +602,45 @@ def main():
         pmc_probe(rng, args.pmc_probe)
         return
 
-    M, K, N, k = 16, 4096, 4096, 32
-    heads, ctx = run_case("cfg2: LLaMA-7B q_proj decode", K, N, k, [16, 1], args.steps, args.warmup, rng,
-                          ring_bytes=1.25 * LLC_BYTES, gain=50.0, bound="hbm")
+    t_start = time.perf_counter()
+    peaks = measure_peaks()
+    K, N, k, kp, M = 8192, 28672, 64, 64, 4096
+    steps = max(1, args.steps)
+    heads, ctx = run_case("cfg4: LLaMA-2-70B MLP, prefill", K, N, k, [M], steps, args.warmup, rng, 0, 50.0, peaks)
     head = heads[0]
-    cases = heads[1:]
-    extra = {}
-    if args.cases in ("all", "full"):
-        ksteps = max(10, args.steps // 10)
+    cases, extra = [], {}
+    if args.cases == "all":
+        dsteps = max(20, steps)
         plan = [
-            ("cfg3: LLaMA-7B MLP up, prefill", 4096, 11008, 32, [2048], ksteps, 0, "mfma"),
-            ("cfg3: LLaMA-7B MLP down, prefill", 11008, 4096, 32, [2048], ksteps, 0, "mfma"),
-            ("cfg4: LLaMA-2-70B MLP", 8192, 28672, 64, [1, 16], ksteps * 2, 2.1 * LLC_BYTES, "hbm"),
-            ("cfg4: LLaMA-2-70B MLP", 8192, 28672, 64, [4096], max(5, ksteps // 4), 0, "mfma"),
+            ("cfg4: LLaMA-2-70B MLP, decode", 8192, 28672, 64, [16, 1], dsteps, 2.1 * LLC_BYTES),
+            ("cfg2: LLaMA-7B q_proj decode", 4096, 4096, 32, [16, 1], 2 * dsteps, 1.25 * LLC_BYTES),
+            ("cfg3: LLaMA-7B MLP up, prefill", 4096, 11008, 32, [2048], dsteps, 0),
+            ("cfg3: LLaMA-7B MLP down, prefill", 11008, 4096, 32, [2048], dsteps, 0),
         ]
-        for (nm, k_, n_, r_, ms_, st_, ring, bound) in plan:
-            res, _ = run_case(nm, k_, n_, r_, ms_, st_, min(args.warmup, st_), rng, ring, 50.0, bound)
+        for (nm, k_, n_, r_, ms_, st_, ring) in plan:
+            res, _ = run_case(nm, k_, n_, r_, ms_, st_, min(args.warmup, st_), rng, ring, 50.0, peaks)
             cases.extend(res)
-        cases.append(run_quantizer_case(32 * 2048, 4096, ksteps, rng))
-    if args.cases == "full":
-        extra["crossover"] = run_crossover(rng)
-        extra["cfg5"] = run_cfg5(3, rng)
+        cases.append(run_quantizer_case(32 * 2048, 4096, 10, rng, peaks))
+        extra["crossover"] = run_crossover(rng, peaks)
+        extra["cfg5"] = run_cfg5(3, rng, peaks)
         extra["added_rows"] = run_added_rows(rng)
         extra["build_factors_seconds_per_layer"] = time_build_factors(rng)
-    kp = 32
-    cpu = cpu_baseline(ctx, M, K, N, kp)
+    t_gpu = time.perf_counter() - t_start
+    cpu = cpu_baseline(ctx, K, N, kp)
+    rf = dict(head["roofline"], traffic=read_pmc_traffic("tiled_kernel.cfg4_M4096"))
     out = {
         "metric": METRIC, "value": head["tflops"], "unit": "TFLOP/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "steps": steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "cfg2: LLaMA-7B-shaped q_proj decode, W 4096x4096 MXINT4, X 16x4096 -> MXINT8, "
-                               "k=32 MXINT8 factors, ring of %d distinct layers" % head["ring_layers"],
+        "config": {"workload": "cfg4: LLaMA-2-70B-shaped MLP layer on one GPU, W 8192x28672 MXINT4, X 4096x8192 fp32 -> MXINT8, "
+                               "k=64 MXINT8 factors, prefill (largest single-GPU configuration)",
                    "M": M, "K": K, "N": N, "k": k},
-        "roofline": dict(head["roofline"], traffic=read_pmc_traffic("stream_kernel.cfg2_M16")),
+        "roofline": rf,
         "cpu_baseline": cpu,
+        "measured_peaks": peaks,
         "headline_detail": head, "cases": cases,
+        "seconds_gpu_part": t_gpu,
     }
     out.update(extra)
     print(json.dumps(out))

@@ -1,9 +1,11 @@
-"""Builds liblqer.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
+"""Builds liblqer.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree, and beside it
+liblqer_probes.so: the benchmark's peak probes (streaming read, copy, MFMA loop), which are not
+part of the library.
 
     python -m paper_2402_02446_amd.build
 
-Objects go to paper_2402_02446_amd/_build/, the library to
-paper_2402_02446_amd/liblqer.so.  hipcc cross-compiles without a GPU.
+Objects go to paper_2402_02446_amd/_build/, the libraries to paper_2402_02446_amd/.
+hipcc cross-compiles without a GPU.
 """
 from __future__ import annotations
 
@@ -18,6 +20,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "liblqer.so")
+PROBES_LIB = os.path.join(PKG, "liblqer_probes.so")
+PROBES_SOURCES = ["bench_probes.hip"]
 
 SOURCES = ["lqer_host.cpp", "build_factors.cpp", "kernels_quant.hip", "kernels_prep.hip",
            "kernels_stream.hip", "kernels_tiled.hip", "kernels_build.hip"]
@@ -50,14 +54,15 @@ def _compile(src: str, extra) -> str:
 
 def build(extra_flags=(), verbose: bool = True) -> str:
     os.makedirs(BUILD, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
-        objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
-    cmd = [_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs, "-lpthread"]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("link failed:\n" + res.stderr)
-    if verbose:
-        print(f"built {LIB}")
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+        all_objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES + PROBES_SOURCES))
+    for lib, objs in ((LIB, all_objs[:len(SOURCES)]), (PROBES_LIB, all_objs[len(SOURCES):])):
+        cmd = [_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", lib, *objs, "-lpthread"]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("link failed:\n" + res.stderr)
+        if verbose:
+            print(f"built {lib}")
     return LIB
 
 

@@ -1,0 +1,104 @@
+// Peak probes for the benchmark (not part of liblqer): what this chip delivers for the two resources the
+// forward pass is priced against (Sec. 2.1: the memory-bound and the compute-bound regime), measured with
+// kernels that do nothing else.
+//   lqer_probe_stream_read  reads a buffer once with the access pattern of the weight stream: every wavefront
+//                           issues contiguous 1 KiB loads (16 bytes per lane, streaming hint), several in flight
+//   lqer_probe_copy         plain copy, 16 bytes per lane (read + write traffic)
+//   lqer_probe_mfma         register-resident loop of 32x32x16 bf16 MFMAs, `chains` independent accumulators
+//                           per wavefront, `waves` wavefronts per SIMD on every compute unit
+// All launches are asynchronous on the given stream; the caller times them with events.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// UNROLL = 1 KiB loads a wavefront keeps in flight
+template <int UNROLL>
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ src, int64_t n_kib, uint32_t* sink) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x >> 6);
+    u32x4 acc = u32x4{0, 0, 0, 0};
+    // wavefront w takes the 1 KiB pieces w, w + nwaves, ... : at any moment the chip reads one contiguous range
+    int64_t i = wave;
+    for (; i + (UNROLL - 1) * nwaves < n_kib; i += UNROLL * nwaves) {
+        u32x4 v[UNROLL];
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) v[j] = __builtin_nontemporal_load(src + (i + j * nwaves) * 64 + lane);
+#pragma unroll
+        for (int j = 0; j < UNROLL; ++j) acc ^= v[j];
+    }
+    for (; i < n_kib; i += nwaves) acc ^= __builtin_nontemporal_load(src + i * 64 + lane);
+    // never true for the buffers the benchmark passes (all ones would be needed): keeps the loads alive
+    if ((acc[0] & acc[1] & acc[2] & acc[3]) == 0xFFFFFFFFu && sink != nullptr) sink[0] = acc[0];
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+template <int CHAINS>
+__global__ __launch_bounds__(256) void mfma_kernel(int iters, float* sink) {
+    f32x16 acc[CHAINS];
+#pragma unroll
+    for (int c = 0; c < CHAINS; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
+    bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (__bf16)(float)((threadIdx.x + e) & 3);
+        b[e] = (__bf16)(float)((threadIdx.x * 3 + e) & 1);
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int c = 0; c < CHAINS; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < CHAINS; ++c) s += acc[c][0] + acc[c][15];
+    if (s == -1.0f && sink != nullptr) sink[0] = s;          // sums of non-negative products: never true
+}
+
+}  // namespace
+
+extern "C" {
+
+// bytes: multiple of 1024; in_flight: 4, 8 or 16 loads of 1 KiB per wavefront.  Returns 0, or the hipError_t of the launch.
+int lqer_probe_stream_read(const void* src_dev, int64_t bytes, void* sink_dev, int workgroups, int in_flight, void* hip_stream) {
+    if (!src_dev || bytes <= 0 || (bytes & 1023) != 0 || workgroups <= 0) return (int)hipErrorInvalidValue;
+    const dim3 grid((unsigned)workgroups), block(256);
+    hipStream_t s = (hipStream_t)hip_stream;
+    const u32x4* src = (const u32x4*)src_dev;
+    uint32_t* sink = (uint32_t*)sink_dev;
+    if (in_flight == 4) hipLaunchKernelGGL(stream_read_kernel<4>, grid, block, 0, s, src, bytes >> 10, sink);
+    else if (in_flight == 8) hipLaunchKernelGGL(stream_read_kernel<8>, grid, block, 0, s, src, bytes >> 10, sink);
+    else if (in_flight == 16) hipLaunchKernelGGL(stream_read_kernel<16>, grid, block, 0, s, src, bytes >> 10, sink);
+    else return (int)hipErrorInvalidValue;
+    return (int)hipGetLastError();
+}
+
+// bytes: multiple of 16.
+int lqer_probe_copy(const void* src_dev, void* dst_dev, int64_t bytes, int workgroups, void* hip_stream) {
+    if (!src_dev || !dst_dev || bytes <= 0 || (bytes & 15) != 0 || workgroups <= 0) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream,
+                       (const u32x4*)src_dev, (u32x4*)dst_dev, bytes >> 4);
+    return (int)hipGetLastError();
+}
+
+// Launches workgroups x 4 wavefronts, each doing iters x chains MFMAs (32 x 32 x 16, 32768 flops each).
+// chains: 4 or 8.  flops of the launch = workgroups * 4 * iters * chains * 32768.
+int lqer_probe_mfma(int workgroups, int iters, int chains, void* sink_dev, void* hip_stream) {
+    if (workgroups <= 0 || iters <= 0) return (int)hipErrorInvalidValue;
+    if (chains == 4) hipLaunchKernelGGL(mfma_kernel<4>, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, (float*)sink_dev);
+    else if (chains == 8) hipLaunchKernelGGL(mfma_kernel<8>, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, (float*)sink_dev);
+    else return (int)hipErrorInvalidValue;
+    return (int)hipGetLastError();
+}
+
+}  // extern "C"
