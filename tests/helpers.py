@@ -53,18 +53,22 @@ def upload(layer):
 
 # Elementwise bar beside the norm.  Every product that enters an accumulator is exact; what rounds is the fp32
 # accumulation (unit roundoff u = 2^-24) over n = K + 2 kp terms, the fp32 accumulation inside T = X_q A_k
-# (K terms) and the split of T into two bf16 terms (relative 2^-16).  A sum of n terms added in fp32 in any
-# order is within n u sum|terms| of the exact sum in the worst case and within about sqrt(n) u sum|terms| with
-# overwhelming probability; the tests assert a quarter of the latter, elementwise:
-#   |Y - Y_ref| <= C u sqrt(n) (main + tail) + 2^-16 tail + C u sqrt(K) proj
-# with the magnitude sums of oracle.forward.forward_magnitudes.
-ELEM_C = 0.25          # measured: the largest |error| / bound over all full-size workloads is 0.17 with this constant
+# (K terms) and the split of T into two bf16 terms, each cut off after 8 significant bits (relative 2^-14 at worst).  A sum of n terms added in fp32 in any
+# order is within n u sum|terms| of the exact sum in the worst case and within a few sqrt(n) u sum|terms| with
+# overwhelming probability; the tests assert, elementwise,
+#   |Y - Y_ref| <= (C sqrt(n) + C0) u (main + tail) + 2^-14 tail + (C sqrt(K) + C0) u proj
+# with the magnitude sums of oracle.forward.forward_magnitudes, C = 1/4 and C0 = 4 (the handful of roundings
+# that do not shrink with K: the hand-over of partial sums, the final store).  For every size tested this is
+# below the worst-case bound n u sum|terms|; the largest |error| / bound measured over the full-size workloads is 0.15.
+ELEM_C = 0.25
+ELEM_C0 = 4.0
 U32 = 2.0 ** -24
 
 
 def elementwise_bound(main, tail, proj, K, kp):
     n = K + 2 * kp
-    return ELEM_C * U32 * np.sqrt(n) * (main + tail) + 2.0 ** -16 * tail + ELEM_C * U32 * np.sqrt(K) * proj
+    return ((ELEM_C * np.sqrt(n) + ELEM_C0) * U32 * (main + tail) + 2.0 ** -14 * tail
+            + (ELEM_C * np.sqrt(K) + ELEM_C0) * U32 * proj)
 
 
 def assert_forward_matches(Y, X, layer, cols=None, act_bits=8, tol=Y_TOL_DERIVED):
