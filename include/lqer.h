@@ -246,6 +246,25 @@ int lqer_linear_forward_shared(const lqer_layer* const* layers, int n_layers, co
  */
 int lqer_set_wait_limit(int polls);
 
+/*
+ * lqer_linear_forward for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments,
+ * same kernels and the same bits in Y as lqer_linear_forward with an automatic launch whose tiles
+ * are not cut between workgroups; the scratch that call takes as `workspace_dev` is a device array
+ * inside the library, 32 MiB on every GPU the library is used on, held until the process ends.
+ *   - Sizes whose scratch need exceeds 32 MiB return LQER_ERR_WORKSPACE before anything is launched
+ *     (the need is about 2 (M + 255) (K + 128) bytes for more than 64 tokens - e.g. M = 1024 at
+ *     K = 8192 fits, M = 4096 does not - and well under 2 MiB up to 64 tokens).
+ *   - The call allocates and frees nothing and synchronises nothing.  Its first use on a device looks
+ *     up the address of that device's array (with that device current): make one call outside any
+ *     graph capture first.
+ *   - Every call on a GPU uses that GPU's one array, which keeps the last call's contents (each call
+ *     overwrites or clears what it reads): calls that overlap in time on one GPU - two streams, two
+ *     threads - race.  Calls on one stream, or ordered by events, are safe.
+ */
+int lqer_linear_forward_static(const lqer_layer* layer, const float* X_dev, int64_t M, int64_t ldx,
+                               float* Y_dev, int64_t ldy, void* hip_stream);
+
 /* Which path the dispatcher picks for this layer at M tokens: 1 = streaming, 2 = tiled MFMA. */
 int lqer_linear_path(const lqer_layer* layer, int64_t M);
 

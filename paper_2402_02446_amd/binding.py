@@ -24,7 +24,8 @@ EXPORTS = ("lqer_status_string", "lqer_quantize_mx", "lqer_build_factors", "lqer
            "lqer_layer_import",
            "lqer_layer_export", "lqer_layer_dims", "lqer_layer_set_activation_bits", "lqer_layer_free", "lqer_linear_workspace_bytes", "lqer_linear_workspace_bytes_ex",
            "lqer_linear_forward", "lqer_linear_forward_q", "lqer_linear_forward_ex", "lqer_linear_forward_requant", "lqer_linear_path",
-           "lqer_linear_shared_workspace_bytes", "lqer_linear_forward_shared", "lqer_set_wait_limit")
+           "lqer_linear_shared_workspace_bytes", "lqer_linear_forward_shared", "lqer_set_wait_limit",
+           "lqer_linear_forward_static")
 
 
 class LqerError(RuntimeError):
@@ -95,6 +96,8 @@ def lib() -> C.CDLL:
     L.lqer_set_wait_limit.argtypes = [i32]
     L.lqer_linear_path.restype = i32
     L.lqer_linear_path.argtypes = [vp, i64]
+    L.lqer_linear_forward_static.restype = i32
+    L.lqer_linear_forward_static.argtypes = [vp, vp, i64, i64, vp, i64, vp]
     _lib = L
     return L
 
@@ -244,6 +247,20 @@ def lqer_linear_forward(layer: Layer, X, Y=None, workspace=None):
     _check(lib().lqer_linear_forward(layer.handle, C.c_void_p(X.data_ptr()), M, ldx, C.c_void_p(Y.data_ptr()),
                                      ldy, C.c_void_p(ws.data_ptr()), ws.numel(), _stream()),
            "lqer_linear_forward")
+    return Y
+
+
+def lqer_linear_forward_static(layer: Layer, X, Y=None):
+    """The forward pass on the library's own static scratch (no workspace argument)."""
+    import torch
+    M = X.shape[0]
+    if Y is None:
+        Y = torch.empty((M, layer.N), dtype=torch.float32, device=X.device)
+    ldx = X.stride(0) if M > 1 else max(layer.K, X.stride(0))
+    ldy = Y.stride(0) if M > 1 else max(layer.N, Y.stride(0))
+    _check(lib().lqer_linear_forward_static(layer.handle, C.c_void_p(X.data_ptr()), M, ldx, C.c_void_p(Y.data_ptr()),
+                                            ldy, _stream()),
+           "lqer_linear_forward_static")
     return Y
 
 

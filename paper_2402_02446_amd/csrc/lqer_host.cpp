@@ -257,7 +257,8 @@ static int download(const uint8_t* dev, size_t bytes, std::vector<uint8_t>& host
 }
 
 // path 1 = streaming kernel (activations as 16-byte cells, T as partial sums), 2 = tiled
-static Workspace plan_workspace(const Layer& L, int64_t M, int path, void* base) {
+// with_slots = false leaves out the slots of the tiled kernel's work split (it then never cuts tiles)
+static Workspace plan_workspace(const Layer& L, int64_t M, int path, void* base, bool with_slots = true) {
     Workspace ws;
     ws.ldxh = L.KT * kTileK + round_up(2 * (int64_t)L.kp, 64);
     ws.S = prep_slices(L, M, path);
@@ -280,8 +281,10 @@ static Workspace plan_workspace(const Layer& L, int64_t M, int path, void* base)
     if (path == 2) {
         ws.flags = (uint32_t*)((uint8_t*)base + ws.bytes);
         ws.bytes += (size_t)kTiledFlags * 4;
-        ws.Part = (float*)((uint8_t*)base + ws.bytes);
-        ws.bytes += (size_t)(kTiledPartBytesPerCu * compute_units());
+        if (with_slots) {
+            ws.Part = (float*)((uint8_t*)base + ws.bytes);
+            ws.bytes += (size_t)(kTiledPartBytesPerCu * compute_units());
+        }
     }
     return ws;
 }
@@ -296,7 +299,8 @@ static int pick_path(const Layer& L, int64_t M) {
 
 static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, const int8_t* Xc,
                         const uint8_t* Xe, int64_t M, float* Y, int64_t ldy, void* wsp, size_t ws_bytes,
-                        void* stream, const lqer_launch_opts* opts, const Requant& rq = Requant{nullptr, nullptr, 0}) {
+                        void* stream, const lqer_launch_opts* opts, const Requant& rq = Requant{nullptr, nullptr, 0},
+                        bool with_slots = true) {
     if (!layer) return LQER_ERR_NULL;
     const Layer& L = layer->L;
     if (M < 0) return LQER_ERR_SHAPE;
@@ -329,7 +333,7 @@ static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, co
         variant = stream_variant_unpaired(M);
     if (stages == 0) stages = 3;
     if (!wsp || ((uintptr_t)wsp & 255) != 0) return LQER_ERR_WORKSPACE;
-    Workspace ws = plan_workspace(L, M, path, wsp);
+    Workspace ws = plan_workspace(L, M, path, wsp, with_slots);
     if (ws.bytes > ws_bytes) return LQER_ERR_WORKSPACE;
     if (path == 1) ws.x8 = stream_takes_codes(stream_variant(L, M, variant), ws.lr);
     hipStream_t s = (hipStream_t)stream;
@@ -369,6 +373,12 @@ static bool shared_group_tiled(const lqer_layer* const* layers, int n, int64_t M
     for (int i = 0; i < n; ++i)
         if (pick_path(layers[i]->L, M) != 2) return false;
     return true;
+}
+
+int forward_in_scratch(const lqer_layer* layer, const float* X, int64_t M, int64_t ldx, float* Y, int64_t ldy,
+                       void* scratch, size_t scratch_bytes, void* stream) {
+    return forward_impl(layer, X, ldx, nullptr, nullptr, M, Y, ldy, scratch, scratch_bytes, stream, nullptr,
+                        Requant{nullptr, nullptr, 0}, false);
 }
 
 }  // namespace lqer

@@ -137,6 +137,10 @@ int pack_factors_and_import(int64_t K, int64_t N, int k, const std::vector<uint8
 int scale_from_magnitudes(const std::vector<double>& abar, std::vector<double>& s);
 
 int prep_slices(const Layer& L, int64_t M, int path);
+// lqer_linear_forward with the given scratch as its workspace, planned without the slots of the tiled kernel's
+// work split (output tiles are then never cut); LQER_ERR_WORKSPACE when the plan does not fit scratch_bytes
+int forward_in_scratch(const lqer_layer* layer, const float* X, int64_t M, int64_t ldx, float* Y, int64_t ldy,
+                       void* scratch, size_t scratch_bytes, void* stream);
 int compute_units();               // of the current device
 
 }  // namespace lqer
