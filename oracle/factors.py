@@ -40,6 +40,7 @@ class PackedLayer:
     Ae: np.ndarray   # uint8 [kp][K/16]
     Bc: np.ndarray   # int8  [N][kp]
     Be: np.ndarray   # uint8 [N][kp/16]
+    w_bits: int = 4  # mantissa width of W_q: 4, or 2 (Wc is then [N][K/4], four codes per byte)
 
 
 def padded_rank(k: int) -> int:
@@ -62,11 +63,12 @@ def calibrate_scale(calib) -> np.ndarray:
     return abar / np.sqrt(abar.min() * abar.max())
 
 
-def quantize_weight(W, exp_bits: int = 8):
-    """W_q = q(W): returns (codes[K][N] int8, exps[K/16][N] uint8, dequantized fp64)."""
+def quantize_weight(W, exp_bits: int = 8, w_bits: int = W_BITS):
+    """W_q = q(W): returns (codes[K][N] int8, exps[K/16][N] uint8, dequantized fp64).
+    w_bits = 2 is the W2A8 setup of Sec. 4.1 / Sec. 4.4."""
     W = np.asarray(W, dtype=np.float64)
-    codes, exps = mxint.mx_quantize(W, W_BITS, axis=0, exp_bits=exp_bits)
-    return codes, exps, mxint.mx_dequantize(codes, exps, W_BITS, axis=0)
+    codes, exps = mxint.mx_quantize(W, w_bits, axis=0, exp_bits=exp_bits)
+    return codes, exps, mxint.mx_dequantize(codes, exps, w_bits, axis=0)
 
 
 def error_factors(E, s, k: int):
@@ -83,7 +85,7 @@ def error_factors(E, s, k: int):
     return A, B, sig
 
 
-def pack_layer(w_codes, w_exps, A, B, k: int, exp_bits: int = 8) -> PackedLayer:
+def pack_layer(w_codes, w_exps, A, B, k: int, exp_bits: int = 8, w_bits: int = W_BITS) -> PackedLayer:
     """Quantize A, B to MXINT8 and lay every tensor out canonically."""
     K, N = w_codes.shape
     kp = padded_rank(k)
@@ -95,7 +97,8 @@ def pack_layer(w_codes, w_exps, A, B, k: int, exp_bits: int = 8) -> PackedLayer:
     b_codes, b_exps = mxint.mx_quantize(Bp, H_BITS, axis=0, exp_bits=exp_bits)      # blocks down k
     return PackedLayer(
         K=K, N=N, k=k, kp=kp,
-        Wc=mxint.pack_int4(np.ascontiguousarray(w_codes.T)),
+        w_bits=w_bits,
+        Wc=mxint.pack_codes(np.ascontiguousarray(w_codes.T), w_bits),
         We=np.ascontiguousarray(w_exps.T),
         Ac=np.ascontiguousarray(a_codes.T),
         Ae=np.ascontiguousarray(a_exps.T),
@@ -104,27 +107,28 @@ def pack_layer(w_codes, w_exps, A, B, k: int, exp_bits: int = 8) -> PackedLayer:
     )
 
 
-def build_factors(W, calib, k: int, mode: int = 1, exp_bits: int = 8) -> PackedLayer:
+def build_factors(W, calib, k: int, mode: int = 1, exp_bits: int = 8, w_bits: int = W_BITS) -> PackedLayer:
     """The whole offline step.  mode 0 = LQER (S = I), mode 1 = L2QER.
-    exp_bits: width of the shared exponents of W_q, A_k and B_k (Sec. 4.1 uses 4)."""
+    exp_bits: width of the shared exponents of W_q, A_k and B_k (Sec. 4.1 uses 4).
+    w_bits: mantissa width of W_q, 4 or 2 (the W2A8 setup, which Sec. 4.1 runs with k = 256)."""
     W = np.asarray(W, dtype=np.float64)
     K, N = W.shape
     if not 0 <= k <= min(K, N):
         raise ValueError("rank k must lie in [0, min(K, N)]")
-    w_codes, w_exps, W_hat = quantize_weight(W, exp_bits)
+    w_codes, w_exps, W_hat = quantize_weight(W, exp_bits, w_bits)
     E = W - W_hat
     s = calibrate_scale(calib) if mode == 1 else np.ones(K)
     if k > 0:
         A, B, _ = error_factors(E, s, k)
     else:
         A, B = np.zeros((K, 0)), np.zeros((0, N))
-    return pack_layer(w_codes, w_exps, A, B, k, exp_bits)
+    return pack_layer(w_codes, w_exps, A, B, k, exp_bits, w_bits)
 
 
 def dequantize_layer(layer: PackedLayer):
     """(W^[K][N], A^[K][kp], B^[kp][N]) in fp64 from the canonical bytes."""
-    Wc = mxint.unpack_int4(layer.Wc)                                        # [N][K]
-    W_hat = mxint.mx_dequantize(Wc, layer.We, W_BITS, axis=1).T
+    Wc = mxint.unpack_codes(layer.Wc, layer.w_bits)                         # [N][K]
+    W_hat = mxint.mx_dequantize(Wc, layer.We, layer.w_bits, axis=1).T
     A_hat = mxint.mx_dequantize(layer.Ac, layer.Ae, H_BITS, axis=1).T
     B_hat = mxint.mx_dequantize(layer.Bc, layer.Be, H_BITS, axis=1).T
     return W_hat, A_hat, B_hat

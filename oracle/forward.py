@@ -44,7 +44,7 @@ def forward_cols(X, layer: PackedLayer, cols, act_bits: int = H_BITS) -> np.ndar
     cols = np.asarray(cols)
     Xc, Xe = quantize_activations(X, act_bits)
     X_hat = mxint.mx_dequantize(Xc, Xe, act_bits, axis=-1)
-    W_sub = mxint.mx_dequantize(mxint.unpack_int4(layer.Wc[cols]), layer.We[cols], W_BITS, axis=1).T      # [K][len(cols)]
+    W_sub = mxint.mx_dequantize(mxint.unpack_codes(layer.Wc[cols], layer.w_bits), layer.We[cols], layer.w_bits, axis=1).T   # [K][len(cols)]
     A_hat = mxint.mx_dequantize(layer.Ac, layer.Ae, H_BITS, axis=1).T                                     # [K][kp]
     B_sub = mxint.mx_dequantize(layer.Bc[cols], layer.Be[cols], H_BITS, axis=1).T                         # [kp][len(cols)]
     T = X_hat @ A_hat
@@ -67,7 +67,7 @@ def forward_magnitudes(X, layer: PackedLayer, cols=None, act_bits: int = H_BITS)
     Xc, Xe = quantize_activations(X, act_bits)
     X_abs = np.abs(mxint.mx_dequantize(Xc, Xe, act_bits, axis=-1))
     X_hat = mxint.mx_dequantize(Xc, Xe, act_bits, axis=-1)
-    W_abs = np.abs(mxint.mx_dequantize(mxint.unpack_int4(layer.Wc[cols]), layer.We[cols], W_BITS, axis=1)).T
+    W_abs = np.abs(mxint.mx_dequantize(mxint.unpack_codes(layer.Wc[cols], layer.w_bits), layer.We[cols], layer.w_bits, axis=1)).T
     A_hat = mxint.mx_dequantize(layer.Ac, layer.Ae, H_BITS, axis=1).T
     B_abs = np.abs(mxint.mx_dequantize(layer.Bc[cols], layer.Be[cols], H_BITS, axis=1)).T
     T = X_hat @ A_hat
@@ -86,7 +86,7 @@ def forward_int_exact(Xc, Xe, layer: PackedLayer) -> np.ndarray:
     M, K = Xc.shape
     nb = K // mxint.BLOCK
     ex = np.asarray(Xe).astype(np.int64) - mxint.EXP_BIAS                    # [M][nb]
-    Wc = mxint.unpack_int4(layer.Wc).astype(np.int64)                        # [N][K]
+    Wc = mxint.unpack_codes(layer.Wc, layer.w_bits).astype(np.int64)         # [N][K]
     ew = layer.We.astype(np.int64) - mxint.EXP_BIAS                          # [N][nb]
     Ac = layer.Ac.astype(np.int64)
     ea = layer.Ae.astype(np.int64) - mxint.EXP_BIAS
@@ -98,7 +98,7 @@ def forward_int_exact(Xc, Xe, layer: PackedLayer) -> np.ndarray:
     for kb in range(nb):
         dw = Xb[:, kb, :] @ Wb[:, kb, :].T                                   # int64 [M][N]
         Y += np.ldexp(dw.astype(np.float64),
-                      ex[:, kb][:, None] + ew[:, kb][None, :] - (H_BITS - 2) - (W_BITS - 2))
+                      ex[:, kb][:, None] + ew[:, kb][None, :] - (H_BITS - 2) - (layer.w_bits - 2))
         da = Xb[:, kb, :] @ Ab[:, kb, :].T
         T += np.ldexp(da.astype(np.float64),
                       ex[:, kb][:, None] + ea[:, kb][None, :] - 2 * (H_BITS - 2))

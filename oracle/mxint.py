@@ -5,7 +5,7 @@ TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 Sec. 2.2 describes MXINT as a block of fixed-point mantissas sharing one
 exponent; Sec. 4.1 fixes the block at 16 elements ([1,16] for activations,
 [16,1] for W_q, A_k, B_k, i.e. always along the contraction axis) and the
-mantissa widths (4 for W_q, 8 for X, A_k, B_k).  The paper gives no formula,
+mantissa widths (4 for W_q - 2 in the W2A8 setup of Sec. 4.4 -, 8 for X, A_k, B_k).  The paper gives no formula,
 so the reading taken here is:
 
   amax  = max |v_i| over the block
@@ -126,6 +126,37 @@ def unpack_int4(packed: np.ndarray) -> np.ndarray:
     out[..., 1::2] = hi
     out = np.where(out >= 8, out - 16, out)
     return out.astype(np.int8)
+
+
+def pack_int2(codes: np.ndarray) -> np.ndarray:
+    """[..., n] int8 codes in [-1,1] (2-bit mantissas) -> [..., n/4] uint8: element 4i in bits 0-1,
+    4i+1 in bits 2-3, 4i+2 in bits 4-5, 4i+3 in bits 6-7, each as a two's-complement pair of bits."""
+    c = np.asarray(codes).astype(np.int16)
+    if c.shape[-1] % 4:
+        raise ValueError("need a multiple of four 2-bit codes")
+    out = np.zeros(c.shape[:-1] + (c.shape[-1] // 4,), dtype=np.int16)
+    for j in range(4):
+        out |= (c[..., j::4] & 0x3) << (2 * j)
+    return out.astype(np.uint8)
+
+
+def unpack_int2(packed: np.ndarray) -> np.ndarray:
+    """Inverse of pack_int2: [..., n/4] uint8 -> [..., n] int8."""
+    p = np.asarray(packed).astype(np.int16)
+    out = np.empty(p.shape[:-1] + (p.shape[-1] * 4,), dtype=np.int16)
+    for j in range(4):
+        out[..., j::4] = (p >> (2 * j)) & 0x3
+    out = np.where(out >= 2, out - 4, out)
+    return out.astype(np.int8)
+
+
+def pack_codes(codes: np.ndarray, bits: int) -> np.ndarray:
+    """Canonical bytes of `bits`-bit weight codes: nibbles (4) or bit pairs (2)."""
+    return pack_int4(codes) if bits == 4 else pack_int2(codes)
+
+
+def unpack_codes(packed: np.ndarray, bits: int) -> np.ndarray:
+    return unpack_int4(packed) if bits == 4 else unpack_int2(packed)
 
 
 def exp4_bias(exps) -> int:

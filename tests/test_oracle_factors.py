@@ -252,3 +252,30 @@ def test_four_bit_shared_exponents_in_the_offline_step():
     assert np.linalg.norm(W2 - Wh - A @ B) < 0.05 * np.linalg.norm(W2 - Wh)
     # stored size (App. D): 4.25 bits per weight instead of 4.5, 8.25 instead of 8.5 per factor element
     assert mxint.lqer_average_weight_bits(4096, 4096, 32, 4, 8, 4, 4) == pytest.approx(4.25 + 8.25 * 32 * 8192 / 4096 ** 2)
+
+
+def test_two_bit_weights_in_the_offline_step():
+    # the W2A8 setup (Sec. 4.1, Sec. 4.4): W_q has 2-bit mantissas, four per byte; E_q = W - W_q is much larger than
+    # with 4 bits, the split of S E_q still satisfies Eckart-Young, and a high rank recovers most of it
+    rng = np.random.default_rng(21)
+    K, N = 64, 48
+    W = synth.gen_weight(rng, K, N)
+    calib = np.abs(rng.standard_normal((2, 16, K))).astype(np.float32) + 0.1
+    l2 = factors.build_factors(W, calib, 32, 1, w_bits=2)
+    l4 = factors.build_factors(W, calib, 32, 1)
+    assert l2.w_bits == 2 and l2.Wc.shape == (N, K // 4) and l4.Wc.shape == (N, K // 2)
+    codes, exps, W_hat = factors.quantize_weight(W, w_bits=2)
+    assert np.array_equal(mxint.unpack_int2(l2.Wc), codes.T) and np.array_equal(l2.We, exps.T)
+    assert set(np.unique(codes).tolist()) <= {-1, 0, 1}
+    W2, A2, B2 = factors.dequantize_layer(l2)
+    W4, _, _ = factors.dequantize_layer(l4)
+    assert np.array_equal(W2, W_hat)
+    e2, e4 = np.linalg.norm(W - W2), np.linalg.norm(W - W4)
+    assert e2 > 3 * e4
+    s = factors.calibrate_scale(calib)
+    E = W - W2
+    A, B, sig = factors.error_factors(E, s, 32)
+    resid = np.linalg.norm(s[:, None] * (E - A @ B)) ** 2
+    assert abs(resid - (sig[32:] ** 2).sum()) <= 1e-10 * (sig ** 2).sum()
+    # the quantized factors take back most of the weighted error
+    assert np.linalg.norm(s[:, None] * (E - A2 @ B2)) < 0.5 * np.linalg.norm(s[:, None] * E)

@@ -176,3 +176,29 @@ def test_magnitude_sums():
     main, tail, proj = forward.forward_magnitudes(Xp, pos)
     assert np.allclose(main + tail, forward.forward(Xp, pos), rtol=1e-13)
     assert np.allclose(proj, tail, rtol=1e-13)
+
+
+def test_two_bit_weights_in_the_forward_pass():
+    # w_bits = 2 through every form of the forward pass: dense, column subset, integer blocks, magnitudes;
+    # and exact rationals straight from the bytes on one element
+    rng = np.random.default_rng(13)
+    K, N, M = 64, 40, 3
+    W = synth.gen_weight(rng, K, N)
+    calib = np.abs(rng.standard_normal((1, 8, K))).astype(np.float32) + 0.1
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    layer = factors.build_factors(W, calib, 24, 1, w_bits=2)
+    Y = forward.forward(X, layer)
+    cols = np.array([39, 0, 7])
+    assert np.allclose(forward.forward_cols(X, layer, cols), Y[:, cols], rtol=1e-13, atol=1e-18)
+    Xc, Xe = forward.quantize_activations(X)
+    assert np.allclose(forward.forward_int_exact(Xc, Xe, layer), Y, rtol=1e-13, atol=1e-18)
+    main, tail, proj = forward.forward_magnitudes(X, layer)
+    assert np.all(main + tail >= np.abs(Y) * (1 - 1e-12))
+    Wc = mxint.unpack_int2(layer.Wc)
+    two = Fraction(2)
+    t, j = 1, 7
+    xh = [int(Xc[t, i]) * two ** (int(Xe[t, i // 16]) - 133) for i in range(K)]
+    T = [sum(xh[i] * int(layer.Ac[r, i]) * two ** (int(layer.Ae[r, i // 16]) - 133) for i in range(K)) for r in range(layer.kp)]
+    y = sum(xh[i] * int(Wc[j, i]) * two ** (int(layer.We[j, i // 16]) - 127) for i in range(K))       # no fraction bits
+    y += sum(T[r] * int(layer.Bc[j, r]) * two ** (int(layer.Be[j, r // 16]) - 133) for r in range(layer.kp))
+    assert abs(float(y) - Y[t, j]) <= 1e-13 * max(1.0, abs(float(y)))

@@ -68,7 +68,7 @@ def _brute_block(vals, bits):
     return codes, e + 127
 
 
-@pytest.mark.parametrize("bits", [4, 6, 8])
+@pytest.mark.parametrize("bits", [2, 4, 6, 8])
 def test_brute_force_rational(bits):
     rng = np.random.default_rng(7)
     blocks = synth.adversarial_blocks(rng, 96)
@@ -88,7 +88,7 @@ def test_exponent_byte_is_fp32_exponent_field():
     assert np.array_equal(x[:, 0].astype(np.uint32), field)
 
 
-@pytest.mark.parametrize("bits", [4, 6, 8])
+@pytest.mark.parametrize("bits", [2, 4, 6, 8])
 def test_idempotence(bits):
     rng = np.random.default_rng(11)
     v = np.concatenate([synth.adversarial_blocks(rng, 256),
@@ -101,7 +101,7 @@ def test_idempotence(bits):
     assert np.array_equal(x, x2)
 
 
-@pytest.mark.parametrize("bits", [4, 6, 8])
+@pytest.mark.parametrize("bits", [2, 4, 6, 8])
 def test_error_bound(bits):
     rng = np.random.default_rng(5)
     v = (rng.standard_normal((2000, 16)) * np.exp2(rng.integers(-20, 20, (2000, 1)))).astype(np.float32)
@@ -116,7 +116,7 @@ def test_error_bound(bits):
     assert np.all(err < 2 * half_step)           # saturated elements lose at most one step
 
 
-@pytest.mark.parametrize("bits", [4, 6, 8])
+@pytest.mark.parametrize("bits", [2, 4, 6, 8])
 def test_antisymmetry_and_scale_covariance(bits):
     rng = np.random.default_rng(9)
     v = rng.standard_normal((300, 16)).astype(np.float32)
@@ -157,6 +157,32 @@ def test_int4_packing_layout():
     rng = np.random.default_rng(0)
     c = rng.integers(-7, 8, size=(5, 64)).astype(np.int8)
     assert np.array_equal(mxint.unpack_int4(mxint.pack_int4(c)), c)
+
+
+def test_int2_packing_layout():
+    # four 2-bit two's-complement codes per byte, element 4i in bits 0-1
+    codes = np.array([[1, 0, -1, 1, 0, 0, -1, -1]], dtype=np.int8)
+    packed = mxint.pack_int2(codes)
+    assert packed.tolist() == [[0b01_11_00_01, 0b11_11_00_00]]
+    assert np.array_equal(mxint.unpack_int2(packed), codes)
+    rng = np.random.default_rng(4)
+    c = rng.integers(-1, 2, size=(5, 64)).astype(np.int8)
+    assert np.array_equal(mxint.unpack_int2(mxint.pack_int2(c)), c)
+    assert np.array_equal(mxint.unpack_codes(mxint.pack_codes(c, 2), 2), c)
+    assert mxint.pack_codes(c, 2).shape == (5, 16) and mxint.pack_codes(c, 4).shape == (5, 32)
+
+
+def test_two_bit_mantissas_are_ternary_at_the_block_scale():
+    # b = 2: one sign and one integer bit, no fraction: values -2^e, 0, +2^e; an element rounds to
+    # +-2^e from half of it upwards (a tie at exactly half goes to the even code, zero)
+    rng = np.random.default_rng(12)
+    v = (rng.standard_normal((500, 16)) * np.exp2(rng.integers(-10, 10, (500, 1)))).astype(np.float32)
+    c, x = mxint.mx_quantize(v, 2)
+    assert set(np.unique(c).tolist()) <= {-1, 0, 1}
+    step = np.ldexp(1.0, x.astype(np.int64) - 127)
+    assert np.array_equal(c, np.sign(v) * (np.abs(v.astype(np.float64)) > 0.5 * step))
+    assert np.all(np.abs(c).max(axis=1) == 1)                 # the largest element always keeps a code
+    assert mxint.average_bits(2, 4) == 2.25
 
 
 def test_average_bits_closed_forms():
