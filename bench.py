@@ -444,6 +444,47 @@ def run_added_rows(rng):
     return out
 
 
+def run_w2a8(rng, peaks):
+    """The W2A8 setup (2-bit weight mantissas, rank 256: Sec. 4.1, Sec. 4.4) on the LLaMA-7B-shaped q_proj and MLP up
+    layers: decode on a ring of device copies beyond the last-level cache, and prefill at M = 2048.  Bytes per weight
+    of the packed W_q: 2 / 8 + 1 / 16 = 0.3125."""
+    import torch
+    from paper_2402_02446_amd import binding, synth
+    out = []
+    for (name, K, N, k) in (("W2A8 7B q_proj", 4096, 4096, 256), ("W2A8 7B MLP up", 4096, 11008, 256)):
+        kp = k
+        per = K * N * 0.3125
+        d = synth.random_packed_layer(rng, K, N, k, w_bits=2)
+        n = max(1, int(np.ceil(1.25 * LLC_BYTES / per)))
+        layers = [binding.lqer_layer_import_w(2, K, N, k, d["Wc"], d["We"], d["Ac"], d["Ae"], d["Bc"], d["Be"]) for _ in range(n)]
+        for M in (16, 2048):
+            X = torch.randn((M, K), device="cuda", dtype=torch.float32)
+            Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+            for l in layers:
+                l.workspace(M)
+            f = lambda i: binding.lqer_linear_forward(layers[i % n], X, Y=Y)
+            f_main = lambda i: binding.lqer_linear_forward_ex(layers[i % n], X, Y=Y, stages=2)
+            for i in range(n):
+                f(i)
+            torch.cuda.synchronize()
+            steps = 2 * n if M <= 16 else 10
+            ms, ms_main = _graph_ms(f, steps), _graph_ms(f_main, steps)
+            fl = flops_forward(M, K, N, kp)
+            by_main = K * N * 0.3125 + kp * N * 1.0625 + M * K * 1.0625 + 4.0 * M * kp + 4.0 * M * N
+            by_step = K * N * 0.3125 + K * kp * 1.0625 + kp * N * 1.0625 + 4.0 * M * K + 4.0 * M * N
+            path = binding.lqer_linear_path(layers[0], M)
+            rec = {"workload": name, "M": M, "K": K, "N": N, "k": k, "w_bits": 2, "ring_layers": n,
+                   "path": "streaming" if path == 1 else "tiled", "ms_per_step": ms, "ms_main_kernel": ms_main,
+                   "tflops": fl / (ms * 1e-3) / 1e12}
+            rec["roofline"] = (roofline("hbm", "stream_kernel", by_main, ms_main, ms, by_step, peaks) if path == 1
+                               else roofline("mfma", "tiled_kernel", fl, ms_main, ms, fl, peaks))
+            out.append(rec)
+            del X, Y
+        for l in layers:
+            l.free()
+    return out
+
+
 def time_build_factors(rng):
     """Wall time of the offline step per layer shape of cfg5: lqer_build_factors (host fp64 + upload, from host
     arrays) and lqer_build_factors_device (device kernels + small host steps, from device tensors; second call,
@@ -624,6 +665,7 @@ def main():
         extra["crossover"] = run_crossover(rng, peaks)
         extra["cfg5"] = run_cfg5(3, rng, peaks)
         extra["added_rows"] = run_added_rows(rng)
+        extra["w2a8_rank256"] = run_w2a8(rng, peaks)
         extra["build_factors_seconds_per_layer"] = time_build_factors(rng)
     t_gpu = time.perf_counter() - t_start
     cpu = cpu_baseline(ctx, K, N, kp)

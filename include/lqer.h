@@ -44,7 +44,7 @@ typedef enum {
     LQER_OK = 0,
     LQER_ERR_NULL = 1,            /* a required pointer is NULL */
     LQER_ERR_SHAPE = 2,           /* K % 16 != 0, k > min(K,N), ld < cols, negative size ... */
-    LQER_ERR_UNSUPPORTED = 3,     /* mantissa width not in {4,8}, exponent width != 8, block != 16 */
+    LQER_ERR_UNSUPPORTED = 3,     /* a mantissa or exponent width, block size or rank (kp > 256) this build does not take */
     LQER_ERR_SINGULAR_SCALE = 4,  /* a calibrated channel magnitude is <= 0 or not finite (Sec. 3.2 needs S^-1) */
     LQER_ERR_WORKSPACE = 5,       /* workspace NULL, misaligned or too small */
     LQER_ERR_HIP = 6,             /* a HIP runtime call or launch failed */
@@ -54,7 +54,7 @@ typedef enum {
 } lqer_status;
 
 /*
- * Number-format description for lqer_build_factors: {4, 8, 8, 16} or {4, 8, 4, 16}.
+ * Number-format description for lqer_build_factors: {4 or 2, 8, 8 or 4, 16}.
  * exp_bits is the width of the shared exponents of W_q, A_k and B_k (Sec. 4.1 gives them 4 bits;
  * activations always keep 8).  The paper states no bias for the 4-bit field; here each of the
  * three tensors has one bias of its own, chosen so that its largest block keeps its exponent:
@@ -64,7 +64,7 @@ typedef enum {
  * the bytes then span at most 16 consecutive values, so byte - (largest byte - 15) fits a nibble.
  */
 typedef struct {
-    int w_bits;     /* mantissa bits of W_q               (4) */
+    int w_bits;     /* mantissa bits of W_q               (4 or 2) */
     int h_bits;     /* mantissa bits of X, A_k, B_k       (8) */
     int exp_bits;   /* shared exponent bits of W_q, A_k, B_k   (8 or 4) */
     int block;      /* block size                         (16) */
@@ -94,9 +94,10 @@ int lqer_quantize_mx(const float* x_dev, int64_t rows, int64_t cols, int64_t ld,
  * Offline construction (Sec. 3.1 Eq. 1-2; Sec. 3.2 Eq. 4-5; App. A Eq. 7-8).
  *   W_host      [K][N] fp32 row-major, host
  *   calib_host  [n_samples][rows_per_sample][K] fp32, host (ignored when mode == 0; may be NULL then)
- *   k           rank, 0 <= k <= min(K, N)
+ *   k           rank, 0 <= k <= min(K, N), at most 256 (LQER_ERR_UNSUPPORTED above)
  *   mode        0 = LQER (S = I), 1 = L2QER (S from calib_host)
- *   cfg         NULL = {4, 8, 8, 16}; {4, 8, 4, 16} selects 4-bit shared exponents (see lqer_config)
+ *   cfg         NULL = {4, 8, 8, 16}; {4, 8, 4, 16} selects 4-bit shared exponents (see lqer_config);
+ *               w_bits = 2 selects 2-bit weight mantissas (the W2A8 setup, Sec. 4.1 / Sec. 4.4)
  *   out         receives an owning handle; release with lqer_layer_free
  * Computes W_q = q(W), E_q = W - W_q, S, the k leading singular triplets of S E_q,
  * A_k = S^-1 U_k, B_k = Sigma_k V_k^T, quantizes A_k and B_k to MXINT8 and uploads
@@ -126,14 +127,26 @@ int lqer_build_factors_device(const float* W_dev, int64_t K, int64_t N,
 /*
  * Layer from / to canonical packed bytes (host pointers, layouts above).
  * Import copies; the caller keeps its buffers.  Ac/Ae/Bc/Be may be NULL when k == 0.
- * Wc nibbles must not be -8; We bytes must be <= 247; Ae, Be bytes must be <= 254
+ * Wc nibbles must not be -8; We bytes must be <= 245; Ae, Be bytes must be <= 254
  * (LQER_ERR_VALUE otherwise).  Export writes exactly the bytes that were imported
  * (or that lqer_build_factors produced); any output pointer may be NULL to skip it.
+ * The padded rank kp may not exceed 256 (LQER_ERR_UNSUPPORTED): the kernels take up to the
+ * k = 256 that Sec. 4.1 pairs with 2-bit weights.
+ * lqer_layer_import_w: the same with the mantissa width of W_q given, 4 or 2 (the W2A8 setup of
+ * Sec. 4.1 / Sec. 4.4: 1 sign and 1 integer bit, value = code * 2^e, code in {-1, 0, 1}).  For
+ * 2 bits Wc is [N][K/4]: four two's-complement bit pairs per byte, element 4i in bits 0-1; the
+ * pair -2 is excluded (LQER_ERR_VALUE).  lqer_layer_export writes the width the layer has
+ * (lqer_layer_weight_bits; 0 for a NULL handle).
  */
 int lqer_layer_import(int64_t K, int64_t N, int k,
                       const uint8_t* Wc, const uint8_t* We,
                       const int8_t* Ac, const uint8_t* Ae,
                       const int8_t* Bc, const uint8_t* Be, lqer_layer** out);
+int lqer_layer_import_w(int w_bits, int64_t K, int64_t N, int k,
+                        const uint8_t* Wc, const uint8_t* We,
+                        const int8_t* Ac, const uint8_t* Ae,
+                        const int8_t* Bc, const uint8_t* Be, lqer_layer** out);
+int lqer_layer_weight_bits(const lqer_layer* layer);
 int lqer_layer_export(const lqer_layer* layer, uint8_t* Wc, uint8_t* We,
                       int8_t* Ac, uint8_t* Ae, int8_t* Bc, uint8_t* Be);
 int lqer_layer_dims(const lqer_layer* layer, int64_t* K, int64_t* N, int* k, int* kp);

@@ -25,7 +25,7 @@ EXPORTS = ("lqer_status_string", "lqer_quantize_mx", "lqer_build_factors", "lqer
            "lqer_layer_export", "lqer_layer_dims", "lqer_layer_set_activation_bits", "lqer_layer_free", "lqer_linear_workspace_bytes", "lqer_linear_workspace_bytes_ex",
            "lqer_linear_forward", "lqer_linear_forward_q", "lqer_linear_forward_ex", "lqer_linear_forward_requant", "lqer_linear_path",
            "lqer_linear_shared_workspace_bytes", "lqer_linear_forward_shared", "lqer_set_wait_limit",
-           "lqer_linear_forward_static")
+           "lqer_linear_forward_static", "lqer_layer_import_w", "lqer_layer_weight_bits")
 
 
 class LqerError(RuntimeError):
@@ -68,6 +68,10 @@ def lib() -> C.CDLL:
     L.lqer_build_factors_device.argtypes = [vp, i64, i64, vp, i64, i64, i32, i32, vp, vp, C.POINTER(vp)]
     L.lqer_layer_import.restype = i32
     L.lqer_layer_import.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, C.POINTER(vp)]
+    L.lqer_layer_import_w.restype = i32
+    L.lqer_layer_import_w.argtypes = [i32, i64, i64, i32, vp, vp, vp, vp, vp, vp, C.POINTER(vp)]
+    L.lqer_layer_weight_bits.restype = i32
+    L.lqer_layer_weight_bits.argtypes = [vp]
     L.lqer_layer_export.restype = i32
     L.lqer_layer_export.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     L.lqer_layer_dims.restype = i32
@@ -143,6 +147,7 @@ class Layer:
         _check(lib().lqer_layer_dims(self.handle, C.byref(K), C.byref(N), C.byref(k), C.byref(kp)),
                "lqer_layer_dims")
         self.K, self.N, self.k, self.kp = K.value, N.value, k.value, kp.value
+        self.w_bits = int(lib().lqer_layer_weight_bits(self.handle))
         self._ws = None
 
     def set_activation_bits(self, bits: int):
@@ -176,9 +181,19 @@ def lqer_layer_import(K, N, k, Wc, We, Ac=None, Ae=None, Bc=None, Be=None) -> La
     return Layer(out.value)
 
 
+def lqer_layer_import_w(w_bits, K, N, k, Wc, We, Ac=None, Ae=None, Bc=None, Be=None) -> Layer:
+    """Import with the mantissa width of W_q given: 4 (Wc [N][K/2]) or 2 (Wc [N][K/4])."""
+    arrs = [None if a is None else np.ascontiguousarray(a) for a in (Wc, We, Ac, Ae, Bc, Be)]
+    if arrs[0].size != N * K * w_bits // 8:
+        raise ValueError("Wc does not hold N * K codes of that width")
+    out = C.c_void_p()
+    _check(lib().lqer_layer_import_w(int(w_bits), K, N, k, *[_np_ptr(a) for a in arrs], C.byref(out)), "lqer_layer_import_w")
+    return Layer(out.value)
+
+
 def lqer_layer_export(layer: Layer):
     K, N, kp = layer.K, layer.N, layer.kp
-    Wc = np.zeros((N, K // 2), np.uint8)
+    Wc = np.zeros((N, K * layer.w_bits // 8), np.uint8)
     We = np.zeros((N, K // 16), np.uint8)
     Ac = np.zeros((kp, K), np.int8)
     Ae = np.zeros((kp, K // 16), np.uint8)

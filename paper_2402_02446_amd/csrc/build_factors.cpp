@@ -135,7 +135,8 @@ static int truncated_split(const std::vector<double>& G, int64_t K, int64_t N, c
 
 // A (K x k) and B (k x N) -> MXINT8 bytes in the canonical layouts, then the layer handle.
 int pack_factors_and_import(int64_t K, int64_t N, int k, const std::vector<uint8_t>& Wc, const std::vector<uint8_t>& We,
-                            const std::vector<double>& A, const std::vector<double>& B, int exp_bits, lqer_layer** out) {
+                            const std::vector<double>& A, const std::vector<double>& B, int exp_bits, lqer_layer** out,
+                            int w_bits) {
     const int kp = (k + 15) / 16 * 16;
     const int64_t nblk = K / 16;
     std::vector<int8_t> Ac, Bc;
@@ -177,9 +178,9 @@ int pack_factors_and_import(int64_t K, int64_t N, int k, const std::vector<uint8
                 mx_block(colb.data(), 1, 8, &Bc[(size_t)n * kp + rb * 16], &Be[(size_t)n * (kp / 16) + rb], b_floor);
             }
     }
-    return lqer_layer_import(K, N, k, Wc.data(), We.data(), k > 0 ? Ac.data() : nullptr,
-                             k > 0 ? Ae.data() : nullptr, k > 0 ? Bc.data() : nullptr,
-                             k > 0 ? Be.data() : nullptr, out);
+    return lqer_layer_import_w(w_bits, K, N, k, Wc.data(), We.data(), k > 0 ? Ac.data() : nullptr,
+                               k > 0 ? Ae.data() : nullptr, k > 0 ? Bc.data() : nullptr,
+                               k > 0 ? Be.data() : nullptr, out);
 }
 
 // S of App. A from the per-channel magnitudes abar (maximum over samples of the mean |x|): geometric-mean normalisation.
@@ -207,16 +208,17 @@ extern "C" int lqer_build_factors(const float* W_host, int64_t K, int64_t N, con
                                   const lqer_config* cfg, lqer_layer** out) try {
     if (!out) return LQER_ERR_NULL;
     *out = nullptr;
-    if (cfg && (cfg->w_bits != 4 || cfg->h_bits != 8 || (cfg->exp_bits != 8 && cfg->exp_bits != 4) || cfg->block != 16))
+    if (cfg && ((cfg->w_bits != 4 && cfg->w_bits != 2) || cfg->h_bits != 8 || (cfg->exp_bits != 8 && cfg->exp_bits != 4) || cfg->block != 16))
         return LQER_ERR_UNSUPPORTED;
     const int exp_bits = cfg ? cfg->exp_bits : 8;
+    const int w_bits = cfg ? cfg->w_bits : 4;
     if (K <= 0 || N <= 0 || (K & 15) != 0 || k < 0 || k > K || k > N) return LQER_ERR_SHAPE;
     if (mode != 0 && mode != 1) return LQER_ERR_UNSUPPORTED;
     if (!W_host) return LQER_ERR_NULL;
     if (mode == 1 && (!calib_host || n_samples <= 0 || rows_per_sample <= 0))
         return calib_host ? LQER_ERR_SHAPE : LQER_ERR_NULL;
     const int kp = (k + 15) / 16 * 16;
-    if (kp > 64) return LQER_ERR_UNSUPPORTED;
+    if (kp > kMaxRank) return LQER_ERR_UNSUPPORTED;
     const int64_t nblk = K / 16;
 
     // S (App. A): per-sample mean magnitude, maximum over samples, geometric-mean normalisation
@@ -236,7 +238,8 @@ extern "C" int lqer_build_factors(const float* W_host, int64_t K, int64_t N, con
     }
 
     // W_q and G = S (W - W_q)
-    std::vector<uint8_t> Wc((size_t)N * (K / 2)), We((size_t)N * nblk);
+    const int64_t wc_row = w_bits == 4 ? K / 2 : K / 4;      // bytes of one column's codes
+    std::vector<uint8_t> Wc((size_t)N * wc_row), We((size_t)N * nblk);
     std::vector<double> G;
     if (k > 0) G.resize((size_t)K * N);
     for (int64_t i = 0; i < K * N; ++i)
@@ -255,12 +258,18 @@ extern "C" int lqer_build_factors(const float* W_host, int64_t K, int64_t N, con
         for (int64_t kb = 0; kb < nblk; ++kb) {
             for (int i = 0; i < 16; ++i) col[i] = (double)W_host[(kb * 16 + i) * N + n];
             uint8_t eb;
-            mx_block(col, 1, 4, codes, &eb, w_floor);
+            mx_block(col, 1, w_bits, codes, &eb, w_floor);
             We[n * nblk + kb] = eb;
-            for (int i = 0; i < 8; ++i)
-                Wc[n * (K / 2) + kb * 8 + i] = (uint8_t)((codes[2 * i] & 0xF) | ((codes[2 * i + 1] & 0xF) << 4));
+            if (w_bits == 4) {
+                for (int i = 0; i < 8; ++i)
+                    Wc[n * wc_row + kb * 8 + i] = (uint8_t)((codes[2 * i] & 0xF) | ((codes[2 * i + 1] & 0xF) << 4));
+            } else {
+                for (int i = 0; i < 4; ++i)
+                    Wc[n * wc_row + kb * 4 + i] = (uint8_t)((codes[4 * i] & 3) | ((codes[4 * i + 1] & 3) << 2) |
+                                                            ((codes[4 * i + 2] & 3) << 4) | ((codes[4 * i + 3] & 3) << 6));
+            }
             if (k > 0) {
-                const double scale = std::ldexp(1.0, (int)eb - 127 - 2);
+                const double scale = std::ldexp(1.0, (int)eb - 127 - (w_bits - 2));
                 for (int i = 0; i < 16; ++i) {
                     const int64_t row = kb * 16 + i;
                     G[(size_t)row * N + n] = s[row] * (col[i] - codes[i] * scale);
@@ -276,7 +285,7 @@ extern "C" int lqer_build_factors(const float* W_host, int64_t K, int64_t N, con
         G.clear();
         G.shrink_to_fit();
     }
-    return pack_factors_and_import(K, N, k, Wc, We, A, B, exp_bits, out);
+    return pack_factors_and_import(K, N, k, Wc, We, A, B, exp_bits, out, w_bits);
 } catch (...) {                                      // a host allocation failed: nothing may leave through the C ABI
     return LQER_ERR_NO_MEMORY;
 }

@@ -27,7 +27,7 @@ struct PrepArgs {
     int64_t KT;            // K tiles
     int tiles_per_slice;
     int kp, kp16;
-    int groups_per_wg;     // rank groups one workgroup computes (kp16, or 1 when split over grid.z)
+    int groups_per_wg;     // rank groups one plane of grid.z computes: at most 4 (the last plane may have fewer)
     const uint8_t* At;
     uint16_t* Xh; int64_t ldxh;
     int64_t tail_cols;     // columns behind K_pad in Xh (T_hi | T_lo | zero padding)
@@ -67,6 +67,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
     const bool row_ok = row < a.M;
     const int slice = blockIdx.y;
     const int g0 = blockIdx.z * a.groups_per_wg;
+    const int ng = (a.kp16 - g0 < a.groups_per_wg) ? a.kp16 - g0 : a.groups_per_wg;   // rank groups of this plane
     const bool store_x = (blockIdx.z == 0) && SRC != 2;
     const int64_t nblk = a.K / 16;
 
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
         if constexpr (CELLS) {
 #pragma unroll
             for (int g = 0; g < MAXG; ++g) {
-                if (g < a.groups_per_wg) {
+                if (g < ng) {
                     const uint8_t* rec = a.At + ((int64_t)(g0 + g) * a.KT + tile) * kARecordBytes;
 #pragma unroll
                     for (int p = 0; p < 4; ++p) {
@@ -207,7 +208,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
         }
 #pragma unroll
         for (int g = 0; g < MAXG; ++g) {
-            if (g < a.groups_per_wg) {
+            if (g < ng) {
                 const uint8_t* rec = a.At + ((int64_t)(g0 + g) * a.KT + tile) * kARecordBytes;
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
@@ -236,7 +237,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
     for (int g = 0; g < MAXG; ++g)
         *reinterpret_cast<f32x4*>(&red[wave][g][lane][0]) = acc[g];
     __syncthreads();
-    for (int item = threadIdx.x; item < a.groups_per_wg * 64; item += blockDim.x) {
+    for (int item = threadIdx.x; item < ng * 64; item += blockDim.x) {
         const int g = item >> 6, l = item & 63;
         f32x4 s = *reinterpret_cast<const f32x4*>(&red[0][g][l][0]);
         for (int w = 1; w < nwaves; ++w) {
@@ -302,6 +303,9 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     // rows again; 1 us less on the 70B-shaped layer.
     int gz = 1;
     if (ws.cells && L.kp16 > 1) { gz = L.kp16; a.groups_per_wg = 1; }
+    // more than four rank groups (ranks above 64): planes of four groups, each quantizing its rows again
+    // (only the first plane stores them)
+    else if (L.kp16 > 4) { gz = (L.kp16 + 3) / 4; a.groups_per_wg = 4; }
     a.At = L.At; a.Xh = ws.Xh; a.ldxh = ws.ldxh;
     a.tail_cols = ws.ldxh - L.KT * kTileK;
     a.Tpart = ws.Tpart;
@@ -324,7 +328,7 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     const int src = reuse_xh ? 2 : (Xc != nullptr ? 1 : 0);
     const bool fin = (ws.Tpart == nullptr);          // T final (hi/lo behind the row) or partial sums
     if (cells && fin && L.kp > 0) return hipErrorInvalidValue;
-    if (a.groups_per_wg > 4) return hipErrorInvalidValue;      // kp > 64 is rejected at import
+    if (a.groups_per_wg > 4) return hipErrorInvalidValue;
 #define LQER_PREP(FC, FN, MG, CL) hipLaunchKernelGGL((prep_kernel<FC, FN, MG, CL>), grid, block, 0, s, a)
 #define LQER_PREP_G(FC, FN, CL) do { if (a.groups_per_wg <= 1) LQER_PREP(FC, FN, 1, CL); else LQER_PREP(FC, FN, 4, CL); } while (0)
 #define LQER_PREP_C(FN, CL) do { if (src == 1) LQER_PREP_G(1, FN, CL); else LQER_PREP_G(0, FN, CL); } while (0)

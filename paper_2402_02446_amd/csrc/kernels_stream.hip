@@ -37,6 +37,7 @@
 namespace lqer {
 
 constexpr int kStreamTBytes = 9 * 1024;          // 32 rows x (128 + 8) bf16, rounded up to keep what follows 1 KiB aligned
+constexpr int kStreamTBytesBig = 33 * 1024;      // the same for ranks up to 256: 32 rows x (512 + 8) bf16
 
 struct StreamArgs {
     const uint8_t* Wt; const uint8_t* Bt;
@@ -56,8 +57,13 @@ struct StreamArgs {
 //      takes alternate steps of the K range and both add their sums into Y, which the projection
 //      kernel has zeroed, with hardware fp32 atomics.  0 + a + b does not depend on which of the two
 //      arrives first, so the result is the same bits on every run.
-template <int G, int NWC, int NWK, int DT, int LR, bool ONE, int KSP>
+// WB: mantissa bits of W_q, 4 or 2 (half the code bytes per record: two 1 KiB loads per record instead of four).
+// BIGK: padded ranks above 64 (up to 256): the correction's operands are then not fetched ahead of the main
+//      product - there are up to four times as many - but where they are used.
+template <int G, int NWC, int NWK, int DT, int LR, bool ONE, int KSP, int WB, bool BIGK>
 __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
+    static_assert(WB == 4 || WB == 2, "weight mantissas of 4 or 2 bits");
+    constexpr int NC = (WB == 4) ? 4 : 2;            // 1 KiB loads per weight record
     static_assert(KSP == 1 || KSP == 2, "one workgroup per column block, or a pair");
     // 64 token rows are two blocks of 32: every expanded weight operand then feeds two MFMAs
     constexpr int MB = (LR == 6) ? 2 : 1;
@@ -81,7 +87,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     static_assert(XG % 1024 == 0, "a stage is a whole number of wavefront loads");
     // T_hi | T_lo of up to 32 tokens x 64 ranks, bf16; a row is padded by 16 bytes so that the token rows
     // of one operand read fall into different banks
-    constexpr int kTBytes = kStreamTBytes * MB;
+    constexpr int kTBytes = (BIGK ? kStreamTBytesBig : kStreamTBytes) * MB;
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     uint16_t* tlds = reinterpret_cast<uint16_t*>(lds);                 // [32][2 kp + 8] bf16, kept all along
     const int t_ld = 2 * a.kp + 8;                                     // row stride of tlds in elements
@@ -112,7 +118,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     const int es1 = exp4 ? 8 : 16, es0 = exp4 ? 4 : 8;
     const uint32_t emask = exp4 ? 0xFu : 0xFFu, ebias = exp4 ? (uint32_t)a.exp_bias : 0u;
     // from wrec to this lane's exponent word: nibbles in front of the codes at lane * 4, bytes behind them at lane * 8
-    const int e_adj = exp4 ? -(lane * 12) - kWCompactCodeOffset : kWExpOffset - (lane * 8);
+    const int e_adj = exp4 ? -(lane * 12) - kWCompactCodeOffset : w_code_bytes(WB) - (lane * 8);
     int trow[MB];
 #pragma unroll
     for (int b = 0; b < MB; ++b) {
@@ -214,12 +220,27 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     // otherwise T_lo for ranks 16 (jb - kp16)...  Job j = g * nchunks + ch of this wavefront's column
     // groups goes to K slice j % NWK (every slice holds a partial sum of every group).
     const int nb2 = (kh == 0) ? 2 * a.kp16 : 0;      // the correction is added once: by workgroup 0 of a pair
-    const int nchunks = (nb2 + 3) / 4;               // 0, 1 or 2
-    constexpr int NJ = (2 * G + NWK - 1) / NWK;
-    u32x4 tail_cw[NJ][2];
-    uint32_t tail_eb[NJ][2];
+    const int nchunks = (nb2 + 3) / 4;               // 0, 1 or 2; up to 8 with BIGK
+    constexpr int NJ = ((BIGK ? 8 : 2) * G + NWK - 1) / NWK;
+    constexpr int NJP = BIGK ? 1 : NJ;               // jobs whose operands are fetched ahead
+    u32x4 tail_cw[NJP][2];
+    uint32_t tail_eb[NJP][2];
+    auto load_tail = [&](int job, int j, u32x4& cw, uint32_t& eb) {
+        const int g = nchunks ? job / nchunks : 0, ch = nchunks ? job % nchunks : 0;
+        cw = u32x4{0, 0, 0, 0};
+        eb = 0;
+        const int jb = 4 * ch + 2 * hh + j;
+        if (job < G * nchunks && jb < nb2) {
+            const int rb = jb >= a.kp16 ? jb - a.kp16 : jb;
+            int64_t grp = g0 + g;
+            if (grp >= a.N32) grp = a.N32 - 1;
+            const uint8_t* rec = a.Bt + (grp * a.kp16 + rb) * kBRecordBytes;
+            cw = *reinterpret_cast<const u32x4*>(rec + t * 16);
+            eb = rec[512 + t];
+        }
+    };
 #pragma unroll
-    for (int q = 0; q < NJ; ++q) {
+    for (int q = 0; q < (BIGK ? 0 : NJ); ++q) {
         const int job = wk + NWK * q;                // wave-uniform
         const int g = nchunks ? job / nchunks : 0, ch = nchunks ? job % nchunks : 0;
 #pragma unroll
@@ -239,7 +260,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     }
     // T: the workgroup adds the S (<= 8) partial sums of the projection kernel in slice order and
     // leaves T_hi | T_lo as bf16 in LDS.  One item = 4 consecutive ranks of a token.
-    constexpr int TI = (32 * MB * 16 + NW * 64 - 1) / (NW * 64);
+    constexpr int TI = BIGK ? 1 : (32 * MB * 16 + NW * 64 - 1) / (NW * 64);
     constexpr int SMAX = 8;
     const int t_rows = a.M < 32 * MB ? (int)a.M : 32 * MB;
     const int kp4 = a.kp >> 2;
@@ -248,7 +269,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     // their way, so that those do not wait for this round trip.
     f32x4 tpart[TI][SMAX];
 #pragma unroll
-    for (int i = 0; i < TI; ++i) {
+    for (int i = 0; i < (BIGK ? 0 : TI); ++i) {
         const int item = threadIdx.x + i * NW * 64;
 #pragma unroll
         for (int sl = 0; sl < SMAX; ++sl) {
@@ -258,16 +279,27 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
         }
     }
     auto finish_t = [&]() {
+        constexpr int TIL = BIGK ? (32 * MB * 64 + NW * 64 - 1) / (NW * 64) : TI;
 #pragma unroll
-        for (int i = 0; i < TI; ++i) {
+        for (int i = 0; i < TIL; ++i) {
             const int item = threadIdx.x + i * NW * 64;
             if (item >= t_items) continue;
             const int row = item / kp4, r4 = item - row * kp4;
-            f32x4 sum = tpart[i][0];
+            f32x4 sum;
+            if constexpr (BIGK) {
+                // loaded here, one item at a time (slice order as below)
+                sum = *reinterpret_cast<const f32x4*>(a.Tpart + 4 * item);
+                for (int sl = 1; sl < a.S; ++sl) {
+                    const f32x4 o = *reinterpret_cast<const f32x4*>(a.Tpart + (int64_t)sl * a.M * a.kp + 4 * item);
+                    sum[0] += o[0]; sum[1] += o[1]; sum[2] += o[2]; sum[3] += o[3];
+                }
+            } else {
+                sum = tpart[i][0];
 #pragma unroll
-            for (int sl = 1; sl < SMAX; ++sl) {
-                sum[0] += tpart[i][sl][0]; sum[1] += tpart[i][sl][1];
-                sum[2] += tpart[i][sl][2]; sum[3] += tpart[i][sl][3];
+                for (int sl = 1; sl < SMAX; ++sl) {
+                    sum[0] += tpart[i][sl][0]; sum[1] += tpart[i][sl][1];
+                    sum[2] += tpart[i][sl][2]; sum[3] += tpart[i][sl][3];
+                }
             }
             uint32_t hi[4], lo[4];
 #pragma unroll
@@ -286,7 +318,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     // DT register sets hold the weight records of DT consecutive steps; set it % DT serves step it and
     // is refilled chunk by chunk with the tile of step it + DT.
     {
-        u32x4 wcd[DT][G][4];         // packed codes, chunk by chunk
+        u32x4 wcd[DT][G][NC];        // packed codes: one 1 KiB load per chunk (4-bit weights) or per two chunks (2-bit)
         u32x2 wex[DT][G];            // exponent bytes
         {
             XStage st;
@@ -294,7 +326,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
 #pragma unroll
             for (int g = 0; g < G; ++g) wex[0][g] = load_we(g, tile_at(0));
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
+            for (int c = 0; c < NC; ++c)
 #pragma unroll
                 for (int g = 0; g < G; ++g) wcd[0][g][c] = load_wc(g, tile_at(0), c);
             if constexpr (DT == 2) {
@@ -302,7 +334,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
 #pragma unroll
                     for (int g = 0; g < G; ++g) wex[1][g] = load_we(g, tile_at(1));
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
+                    for (int c = 0; c < NC; ++c)
 #pragma unroll
                         for (int g = 0; g < G; ++g) wcd[1][g][c] = load_wc(g, tile_at(1), c);
                 }
@@ -311,7 +343,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
             finish_t();
         }
         // PFX: the step fetches the activations of the next one; PFW: it refills its weight set
-        auto step = [&](u32x4 (&wc_)[G][4], u32x2 (&we_)[G], int64_t it, auto pfx, auto pfw) {
+        auto step = [&](u32x4 (&wc_)[G][NC], u32x2 (&we_)[G], int64_t it, auto pfx, auto pfw) {
             constexpr bool PFX = decltype(pfx)::value, PFW = decltype(pfw)::value;
             __syncthreads();         // stage it % 2 is complete; the other one is free again
             XStage st;
@@ -344,15 +376,24 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
                         for (int s = 0; s < 4; ++s) {
                             // exponent byte of block 2 c + s / 2 of the lane's eight: a byte, or a nibble plus the layer's bias
                             const uint32_t eb = ((we_[g][c >> 1] >> ((c & 1) * es1 + (s >> 1) * es0)) & emask) + ebias;
-                            const bf16x8 wv = unpack_w8(wc_[g][c][s], w_scale(eb));
+                            bf16x8 wv;
+                            if constexpr (WB == 4) wv = unpack_w8(wc_[g][c][s], w_scale(eb));
+                            else wv = unpack_w8_b2(wc_[g][c >> 1][(c & 1) * 2 + (s >> 1)], s & 1, w2_scale(eb));
 #pragma unroll
                             for (int b = 0; b < MB; ++b) acc[g][b] = mfma32(wv, xf[b][s].v, acc[g][b]);
                         }
                     }
                 }
                 if constexpr (PFW) {
+                    // refill what this chunk has just used up: its own 1 KiB, or (2-bit weights) the 1 KiB it shares
+                    // with the chunk before it
+                    if constexpr (WB == 4) {
 #pragma unroll
-                    for (int g = 0; g < G; ++g) wc_[g][c] = load_wc(g, nt, c);
+                        for (int g = 0; g < G; ++g) wc_[g][c] = load_wc(g, nt, c);
+                    } else if (c & 1) {
+#pragma unroll
+                        for (int g = 0; g < G; ++g) wc_[g][c >> 1] = load_wc(g, nt, c >> 1);
+                    }
                 }
             }
             if constexpr (PFX) store_x(st, (int)((it + 1) & 1));    // waits for the activation loads only
@@ -409,7 +450,14 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
                 }
             }
             Frag bf[2];
-            int8x16_to_frags(tail_cw[q][j], h_scale(tail_eb[q][j]), bf[0], bf[1]);
+            if constexpr (BIGK) {
+                u32x4 cw;
+                uint32_t eb;
+                load_tail(job, j, cw, eb);
+                int8x16_to_frags(cw, h_scale(eb), bf[0], bf[1]);
+            } else {
+                int8x16_to_frags(tail_cw[q][j], h_scale(tail_eb[q][j]), bf[0], bf[1]);
+            }
             // g is wave-uniform: pick the accumulator by unrolled comparison so all stay in registers
 #pragma unroll
             for (int gg = 0; gg < G; ++gg) {
@@ -519,16 +567,16 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
 int stream_max_rows() { return 64; }
 int stream_cell_rows_log2(int64_t M) { return M <= 4 ? 2 : (M <= 16 ? 4 : (M <= 32 ? 5 : 6)); }
 
-template <int G, int NWC, int NWK, int DT, int LR, bool ONE, int KSP>
+template <int G, int NWC, int NWK, int DT, int LR, bool ONE, int KSP, int WB, bool BIGK>
 static hipError_t launch_stream_t(const StreamArgs& a, hipStream_t s) {
     constexpr int STAGING = (ONE ? 1 : 2) * NWK * (1 << LR) * 512;
     constexpr int MB = (LR == 6) ? 2 : 1;
     constexpr int REDUCE = NWK * NWC * G * MB * 4096 + (KSP == 2 ? NWC * G * 4096 : 0);
-    constexpr int LDS_BYTES = kStreamTBytes * MB + (STAGING > REDUCE ? STAGING : REDUCE);
+    constexpr int LDS_BYTES = (BIGK ? kStreamTBytesBig : kStreamTBytes) * MB + (STAGING > REDUCE ? STAGING : REDUCE);
     if constexpr (LDS_BYTES > 160 * 1024 || (MB == 2 && KSP == 2)) {
         return hipErrorInvalidValue;                 // this shape does not fit the 160 KB of LDS
     } else {
-        auto kern = stream_kernel<G, NWC, NWK, DT, LR, ONE, KSP>;
+        auto kern = stream_kernel<G, NWC, NWK, DT, LR, ONE, KSP, WB, BIGK>;
         // the dynamic LDS limit of this instance, set once per process (calls may come from several threads)
         static std::once_flag once;
         static hipError_t attr_err = hipSuccess;
@@ -543,23 +591,39 @@ static hipError_t launch_stream_t(const StreamArgs& a, hipStream_t s) {
     }
 }
 
-template <int G, int NWC, int NWK, int DT, int KSP = 1>
+template <int G, int NWC, int NWK, int DT, int KSP, int WB, bool BIGK>
 static hipError_t launch_stream_rows(const StreamArgs& a, hipStream_t s) {
     if constexpr (DT == 1) {
         if (a.KT <= NWK * KSP) {
             switch (stream_cell_rows_log2(a.M)) {
-                case 2: return launch_stream_t<G, NWC, NWK, 1, 2, true, KSP>(a, s);
-                case 4: return launch_stream_t<G, NWC, NWK, 1, 4, true, KSP>(a, s);
-                case 5: return launch_stream_t<G, NWC, NWK, 1, 5, true, KSP>(a, s);
-                default: return launch_stream_t<G, NWC, NWK, 1, 6, true, KSP>(a, s);
+                case 2: return launch_stream_t<G, NWC, NWK, 1, 2, true, KSP, WB, BIGK>(a, s);
+                case 4: return launch_stream_t<G, NWC, NWK, 1, 4, true, KSP, WB, BIGK>(a, s);
+                case 5: return launch_stream_t<G, NWC, NWK, 1, 5, true, KSP, WB, BIGK>(a, s);
+                default: return launch_stream_t<G, NWC, NWK, 1, 6, true, KSP, WB, BIGK>(a, s);
             }
         }
     }
     switch (stream_cell_rows_log2(a.M)) {
-        case 2: return launch_stream_t<G, NWC, NWK, DT, 2, false, KSP>(a, s);
-        case 4: return launch_stream_t<G, NWC, NWK, DT, 4, false, KSP>(a, s);
-        case 5: return launch_stream_t<G, NWC, NWK, DT, 5, false, KSP>(a, s);
-        default: return launch_stream_t<G, NWC, NWK, DT, 6, false, KSP>(a, s);
+        case 2: return launch_stream_t<G, NWC, NWK, DT, 2, false, KSP, WB, BIGK>(a, s);
+        case 4: return launch_stream_t<G, NWC, NWK, DT, 4, false, KSP, WB, BIGK>(a, s);
+        case 5: return launch_stream_t<G, NWC, NWK, DT, 5, false, KSP, WB, BIGK>(a, s);
+        default: return launch_stream_t<G, NWC, NWK, DT, 6, false, KSP, WB, BIGK>(a, s);
+    }
+}
+
+// the shapes the automatic choice uses, for the other number formats: 2-bit weights and / or ranks above 64
+template <int WB, bool BIGK>
+static hipError_t launch_stream_reduced(int v, const StreamArgs& a, hipStream_t s) {
+    switch (v) {
+        case 11421: return launch_stream_rows<1, 4, 2, 1, 1, WB, BIGK>(a, s);
+        case 12241: return launch_stream_rows<2, 2, 4, 1, 1, WB, BIGK>(a, s);
+        case 12181: return launch_stream_rows<2, 1, 8, 1, 1, WB, BIGK>(a, s);
+        case 12141: return launch_stream_rows<2, 1, 4, 1, 1, WB, BIGK>(a, s);
+        case 11181: return launch_stream_rows<1, 1, 8, 1, 1, WB, BIGK>(a, s);
+        case 11241: return launch_stream_rows<1, 2, 4, 1, 1, WB, BIGK>(a, s);
+        case 21181: return launch_stream_rows<1, 1, 8, 1, 2, WB, BIGK>(a, s);
+        case 21141: return launch_stream_rows<1, 1, 4, 1, 2, WB, BIGK>(a, s);
+        default: return hipErrorInvalidValue;
     }
 }
 
@@ -568,15 +632,23 @@ static hipError_t launch_stream_rows(const StreamArgs& a, hipStream_t s) {
 int stream_variant(const Layer& L, int64_t M, int variant) {
     if (variant != 0) return variant;
     if (M > 32) return 11421;                        // 33 to 64 tokens: two blocks of 32 per wavefront, two K slices
+    // With ranks above 64 the T rows take 33 KB of LDS: beside them fit four K slices of up to 16 token rows, or two
+    // of up to 32 (and nothing for more tokens: the dispatcher sends those to the tiled kernel).
+    const bool big = L.kp > 64;
+    if (big && M > 16) return 11421;
     if ((L.N32 + 3) / 4 >= 200) return 12241;        // wide layers
-    if ((L.N32 + 1) / 2 >= 160) return (M <= 16) ? 12181 : 12141;
+    const bool eight = M <= 16 && !big;
+    if ((L.N32 + 1) / 2 >= 160) return eight ? 12181 : 12141;
     // narrow layers: one column group per workgroup, and a pair of workgroups per group when that
     // still leaves half of the compute units idle and the K range is worth sharing
-    if (L.N32 <= 160 && L.KT >= 8) return (M <= 16) ? 21181 : 21141;
-    return (M <= 16) ? 11181 : 11241;
+    if (L.N32 <= 160 && L.KT >= 8) return eight ? 21181 : 21141;
+    return eight ? 11181 : 11241;
 }
 bool stream_variant_adds_into_y(int variant) { return variant / 10000 == 2; }
-int stream_variant_unpaired(int64_t M) { return M <= 16 ? 11181 : 11241; }
+int stream_variant_unpaired(const Layer& L, int64_t M) {
+    if (L.kp > 64) return M <= 16 ? 11241 : 11421;
+    return M <= 16 ? 11181 : 11241;
+}
 bool stream_takes_codes(int variant, int lr) { return lr >= 4 && !stream_variant_adds_into_y(variant); }
 
 hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy, const Requant& rq,
@@ -590,23 +662,26 @@ hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* 
     a.rec_bytes = L.w_rec_bytes; a.exp_bias = L.w_exp_bias;
     const int v = stream_variant(L, M, variant);
     if (rq.codes != nullptr && stream_variant_adds_into_y(v)) return hipErrorInvalidValue;   // a pair's sum is complete only in memory
+    const bool bigk = L.kp > 64;
+    if (L.w_bits == 2) return bigk ? launch_stream_reduced<2, true>(v, a, s) : launch_stream_reduced<2, false>(v, a, s);
+    if (bigk) return launch_stream_reduced<4, true>(v, a, s);
     switch (v) {
-        case 11441: return launch_stream_rows<1, 4, 4, 1>(a, s);
-        case 11421: return launch_stream_rows<1, 4, 2, 1>(a, s);
-        case 12241: return launch_stream_rows<2, 2, 4, 1>(a, s);
-        case 12242: return launch_stream_rows<2, 2, 4, 2>(a, s);
-        case 12181: return launch_stream_rows<2, 1, 8, 1>(a, s);
-        case 12141: return launch_stream_rows<2, 1, 4, 1>(a, s);
-        case 11181: return launch_stream_rows<1, 1, 8, 1>(a, s);
-        case 11101: return launch_stream_rows<1, 1, 16, 1>(a, s);
-        case 11281: return launch_stream_rows<1, 2, 8, 1>(a, s);
-        case 11241: return launch_stream_rows<1, 2, 4, 1>(a, s);
-        case 21181: return launch_stream_rows<1, 1, 8, 1, 2>(a, s);
-        case 21141: return launch_stream_rows<1, 1, 4, 1, 2>(a, s);
-        case 22181: return launch_stream_rows<2, 1, 8, 1, 2>(a, s);
-        case 22421: return launch_stream_rows<2, 4, 2, 1, 2>(a, s);
-        case 21441: return launch_stream_rows<1, 4, 4, 1, 2>(a, s);
-        case 21101: return launch_stream_rows<1, 1, 16, 1, 2>(a, s);
+        case 11441: return launch_stream_rows<1, 4, 4, 1, 1, 4, false>(a, s);
+        case 11421: return launch_stream_rows<1, 4, 2, 1, 1, 4, false>(a, s);
+        case 12241: return launch_stream_rows<2, 2, 4, 1, 1, 4, false>(a, s);
+        case 12242: return launch_stream_rows<2, 2, 4, 2, 1, 4, false>(a, s);
+        case 12181: return launch_stream_rows<2, 1, 8, 1, 1, 4, false>(a, s);
+        case 12141: return launch_stream_rows<2, 1, 4, 1, 1, 4, false>(a, s);
+        case 11181: return launch_stream_rows<1, 1, 8, 1, 1, 4, false>(a, s);
+        case 11101: return launch_stream_rows<1, 1, 16, 1, 1, 4, false>(a, s);
+        case 11281: return launch_stream_rows<1, 2, 8, 1, 1, 4, false>(a, s);
+        case 11241: return launch_stream_rows<1, 2, 4, 1, 1, 4, false>(a, s);
+        case 21181: return launch_stream_rows<1, 1, 8, 1, 2, 4, false>(a, s);
+        case 21141: return launch_stream_rows<1, 1, 4, 1, 2, 4, false>(a, s);
+        case 22181: return launch_stream_rows<2, 1, 8, 1, 2, 4, false>(a, s);
+        case 22421: return launch_stream_rows<2, 4, 2, 1, 2, 4, false>(a, s);
+        case 21441: return launch_stream_rows<1, 4, 4, 1, 2, 4, false>(a, s);
+        case 21101: return launch_stream_rows<1, 1, 16, 1, 2, 4, false>(a, s);
         default: return hipErrorInvalidValue;
     }
 }

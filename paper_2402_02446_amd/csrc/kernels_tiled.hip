@@ -29,6 +29,7 @@
 // another wait.  The sum order is fixed by the split, so the result has the same bits every run.
 #include <atomic>
 #include <mutex>
+#include <type_traits>
 
 #include "lqer_internal.h"
 #include "mx_device.h"
@@ -61,8 +62,10 @@ struct TiledArgs {
 // MINW = wavefronts per SIMD the register allocation must allow (2 lets two four-wavefront workgroups share a compute unit)
 // SPLIT = the workgroup walks a list of pieces (work split); otherwise it computes output tile blockIdx.x
 // whole, as straight-line code (the loop over pieces costs the main product a few percent)
-template <int TM, int TN, int WR, int WC, int NS, int MINW, bool SPLIT>
+// WB = mantissa bits of W_q: 4, or 2 (half the code bytes per record, one 32-bit word per block)
+template <int TM, int TN, int WR, int WC, int NS, int MINW, bool SPLIT, int WB>
 __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) {
+    static_assert(WB == 4 || WB == 2, "weight mantissas of 4 or 2 bits");
     constexpr int BM = 32 * TM * WR;
     constexpr int NW = WR * WC;
     constexpr int STAGE = BM * 128;                // bytes: BM rows x 64 bf16
@@ -111,7 +114,7 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     const int es1 = exp4 ? 8 : 16, es0 = exp4 ? 4 : 8;
     const uint32_t emask = exp4 ? 0xFu : 0xFFu, ebias = exp4 ? (uint32_t)a.exp_bias : 0u;
     // nibbles sit in front of the codes (lane * 4), bytes behind them (lane * 8)
-    const int code_off = exp4 ? kWCompactCodeOffset : 0, exp_off = exp4 ? lane16 >> 2 : kWExpOffset + (lane16 >> 1);
+    const int code_off = exp4 ? kWCompactCodeOffset : 0, exp_off = exp4 ? lane16 >> 2 : w_code_bytes(WB) + (lane16 >> 1);
 
     int64_t dp_next = lin;                                     // next whole tile of this workgroup
     int64_t u = a.sk_share * lin;                              // its range of the shared K tiles
@@ -180,8 +183,9 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
 
+    typedef typename std::conditional<WB == 4, u32x4, u32x2>::type WVec;   // a lane's two blocks of one chunk
     struct WSet {                // packed codes of one chunk for this wavefront's TN column groups
-        u32x4 c[TN];
+        WVec c[TN];
     };
     struct ESet {                // exponent bytes of one K tile (four chunks) for the same groups
         u32x2 e[TN];
@@ -192,7 +196,8 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
             const uint8_t* rec = a.Wt + (tile * a.N32 + group_of(tn)) * a.rec_bytes;   // wave-uniform
-            w.c[tn] = *reinterpret_cast<const u32x4*>(rec + code_off + cc * 1024 + lane16);
+            if constexpr (WB == 4) w.c[tn] = *reinterpret_cast<const u32x4*>(rec + code_off + cc * 1024 + lane16);
+            else w.c[tn] = *reinterpret_cast<const u32x2*>(rec + code_off + (cc >> 1) * 1024 + lane16 + (cc & 1) * 8);
         }
     };
     auto load_eset = [&](ESet& x, int tile_i) {
@@ -264,8 +269,8 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
             const uint32_t ew = x.e[tn][c >> 1] >> ((c & 1) * es1);
-            sc[tn][0] = w_scale((ew & emask) + ebias);
-            sc[tn][1] = w_scale(((ew >> es0) & emask) + ebias);
+            sc[tn][0] = (WB == 4) ? w_scale((ew & emask) + ebias) : w2_scale((ew & emask) + ebias);
+            sc[tn][1] = (WB == 4) ? w_scale(((ew >> es0) & emask) + ebias) : w2_scale(((ew >> es0) & emask) + ebias);
         }
 #pragma unroll
         for (int s4 = 0; s4 < 4; ++s4) {
@@ -274,7 +279,9 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
             else read_xa(xn, (c + 1) & 3, 0);
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
-                const bf16x8 wv = unpack_w8(w.c[tn][s4], sc[tn][s4 >> 1]);
+                bf16x8 wv;
+                if constexpr (WB == 4) wv = unpack_w8(w.c[tn][s4], sc[tn][s4 >> 1]);
+                else wv = unpack_w8_b2(w.c[tn][s4 >> 1], s4 & 1, sc[tn][s4 >> 1]);
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm) acc[tm][tn] = mfma32(wv, xa[tm].v, acc[tm][tn]);
             }
@@ -346,7 +353,7 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     }
 
     // ---- rank-kp correction: [T_hi | T_lo | 0] against B_k ---------------------------------------
-    // The (at most two) correction chunks are fetched here rather than ahead from the main loop: B_k's
+    // The correction chunks are fetched here rather than ahead from the main loop: B_k's
     // records are needed at the same moment and cost the same memory round trip.  Stages 0 and 1 are
     // free: every wavefront is past the barrier of the last main chunk, which reads stage 3.
     // lane half hh owns rank blocks jb = 4 cc + 2 hh + {0, 1} of tail chunk cc
@@ -356,43 +363,47 @@ __global__ __launch_bounds__(64 * WR * WC, MINW) void tiled_kernel(TiledArgs a) 
     int t_e = t, hh_e = hh, lane_e = lane;
     if constexpr (SPLIT) asm volatile("" : "+v"(t_e), "+v"(hh_e), "+v"(lane_e));
     const int my_tail = owner ? tail_chunks : 0;              // the piece that stores the tile adds the correction
-    if (my_tail > 0) {
-        u32x4 tst[2][LPT];
-        fetch_any(tst[0], main_chunks);
-        if (tail_chunks > 1) fetch_any(tst[1], main_chunks + 1);
-        store_x(tst[0], 0);
-        if (tail_chunks > 1) store_x(tst[1], 1);
-        __syncthreads();
-    }
-    for (int cc = 0; cc < my_tail; ++cc) {
-        const uint8_t* stage = lds + (cc & 3) * STAGE;
+    // two correction chunks at a time through stages 0 and 1 (ranks up to 64 need one round, 256 four)
+    for (int cc0 = 0; cc0 < my_tail; cc0 += 2) {
+        {
+            u32x4 tst[2][LPT];
+            if (cc0 > 0) __syncthreads();                      // every wavefront has read the previous pair of chunks
+            fetch_any(tst[0], main_chunks + cc0);
+            if (cc0 + 1 < tail_chunks) fetch_any(tst[1], main_chunks + cc0 + 1);
+            store_x(tst[0], 0);
+            if (cc0 + 1 < tail_chunks) store_x(tst[1], 1);
+            __syncthreads();
+        }
+        for (int cc = cc0; cc < cc0 + 2 && cc < my_tail; ++cc) {
+            const uint8_t* stage = lds + (cc & 1) * STAGE;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int jb = 4 * cc + 2 * hh_e + j;
-            const bool live = jb < nb2;
-            const int rb = live ? (jb < a.kp16 ? jb : jb - a.kp16) : 0;
-            Frag bf[TN][2];
+            for (int j = 0; j < 2; ++j) {
+                const int jb = 4 * cc + 2 * hh_e + j;
+                const bool live = jb < nb2;
+                const int rb = live ? (jb < a.kp16 ? jb : jb - a.kp16) : 0;
+                Frag bf[TN][2];
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                u32x4 cw = u32x4{0, 0, 0, 0};
-                uint32_t eb = 0;
-                if (live) {
-                    const uint8_t* rec = a.Bt + (group_of(tn) * a.kp16 + rb) * kBRecordBytes;
-                    cw = *reinterpret_cast<const u32x4*>(rec + t_e * 16);
-                    eb = rec[512 + t_e];
+                for (int tn = 0; tn < TN; ++tn) {
+                    u32x4 cw = u32x4{0, 0, 0, 0};
+                    uint32_t eb = 0;
+                    if (live) {
+                        const uint8_t* rec = a.Bt + (group_of(tn) * a.kp16 + rb) * kBRecordBytes;
+                        cw = *reinterpret_cast<const u32x4*>(rec + t_e * 16);
+                        eb = rec[512 + t_e];
+                    }
+                    int8x16_to_frags(cw, h_scale(eb), bf[tn][0], bf[tn][1]);
                 }
-                int8x16_to_frags(cw, h_scale(eb), bf[tn][0], bf[tn][1]);
-            }
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                Frag xa[TM];
+                for (int h = 0; h < 2; ++h) {
+                    Frag xa[TM];
 #pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
-                    xa[tm].u = *reinterpret_cast<const u32x4*>(stage + rd_off[2 * j + h] + tm * 4096);
+                    for (int tm = 0; tm < TM; ++tm)
+                        xa[tm].u = *reinterpret_cast<const u32x4*>(stage + rd_off[2 * j + h] + tm * 4096);
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
+                    for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-                    for (int tm = 0; tm < TM; ++tm) acc[tm][tn] = mfma32(bf[tn][h].v, xa[tm].v, acc[tm][tn]);
+                        for (int tm = 0; tm < TM; ++tm) acc[tm][tn] = mfma32(bf[tn][h].v, xa[tm].v, acc[tm][tn]);
+                }
             }
         }
     }
@@ -630,7 +641,7 @@ static hipError_t launch_kernel(Kern kern, KernelSetup& ks, int lds_bytes, int64
 }
 
 // CAN_SPLIT: the shape also exists in the form that walks a list of pieces
-template <int TM, int TN, int WR, int WC, int NS, int MINW = 1, bool CAN_SPLIT = false>
+template <int WB, int TM, int TN, int WR, int WC, int NS, int MINW = 1, bool CAN_SPLIT = false>
 static hipError_t launch_tiled_t(TiledArgs a, int64_t M, int mode, int cus, hipStream_t s) {
     constexpr int BM = 32 * TM * WR, BN = 32 * TN * WC;
     constexpr int LDS_BYTES = NS * BM * 128;
@@ -647,7 +658,7 @@ static hipError_t launch_tiled_t(TiledArgs a, int64_t M, int mode, int cus, hipS
     // bounds; should it ever be lower than the shape assumes, tiles are not cut.
     bool can_split = CAN_SPLIT;
     if constexpr (CAN_SPLIT) {
-        const hipError_t e = prepare_kernel(tiled_kernel<TM, TN, WR, WC, NS, MINW, true>, setup_split, LDS_BYTES, 64 * WR * WC);
+        const hipError_t e = prepare_kernel(tiled_kernel<TM, TN, WR, WC, NS, MINW, true, WB>, setup_split, LDS_BYTES, 64 * WR * WC);
         if (e != hipSuccess) return e;
         if (setup_split.resident < MINW) can_split = false;
     }
@@ -664,9 +675,9 @@ static hipError_t launch_tiled_t(TiledArgs a, int64_t M, int mode, int cus, hipS
     a.dp_tiles = sp.dp_tiles; a.sk_units = sp.sk_units; a.sk_share = sp.sk_share; a.sk_tile_units = sp.sk_tile_units;
     if constexpr (CAN_SPLIT) {
         if (sp.sk_units > 0)
-            return launch_kernel(tiled_kernel<TM, TN, WR, WC, NS, MINW, true>, setup_split, LDS_BYTES, sp.grid, 64 * WR * WC, a, s);
+            return launch_kernel(tiled_kernel<TM, TN, WR, WC, NS, MINW, true, WB>, setup_split, LDS_BYTES, sp.grid, 64 * WR * WC, a, s);
     }
-    return launch_kernel(tiled_kernel<TM, TN, WR, WC, NS, MINW, false>, setup_whole, LDS_BYTES, tiles, 64 * WR * WC, a, s);
+    return launch_kernel(tiled_kernel<TM, TN, WR, WC, NS, MINW, false, WB>, setup_whole, LDS_BYTES, tiles, 64 * WR * WC, a, s);
 }
 
 __global__ void clear_flags_kernel(uint32_t* flags, int n) {
@@ -726,15 +737,24 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
             if (variant == 0 || t < best) { best = t; variant = sh.id; }
         }
     }
+    if (L.w_bits == 2) {
+        // 2-bit weights: the three shapes the automatic choice uses
+        switch (variant) {
+            case 4: return launch_tiled_t<2, 2, 2, 2, 2, 4, 2, true>(a, M, mode, cus, s);
+            case 11: return launch_tiled_t<2, 4, 2, 1, 8, 4, 1, true>(a, M, mode, cus, s);
+            case 12: return launch_tiled_t<2, 4, 2, 1, 4, 4, 2, true>(a, M, mode, cus, s);
+            default: return hipErrorInvalidValue;
+        }
+    }
     switch (variant) {
-        case 1: return launch_tiled_t<4, 4, 2, 2, 4>(a, M, mode, cus, s);      // 256 x 256
-        case 3: return launch_tiled_t<2, 4, 2, 2, 4>(a, M, mode, cus, s);      // 128 x 256
-        case 4: return launch_tiled_t<2, 2, 2, 2, 4, 2, true>(a, M, mode, cus, s);   // 128 x 128, two workgroups per compute unit
-        case 7: return launch_tiled_t<2, 4, 2, 4, 4>(a, M, mode, cus, s);      // 128 x 512, eight wavefronts
-        case 8: return launch_tiled_t<2, 4, 2, 2, 4, 2>(a, M, mode, cus, s);   // 128 x 256, two workgroups per compute unit
-        case 11: return launch_tiled_t<4, 2, 1, 8, 4, 1, true>(a, M, mode, cus, s);     // 128 x 512, eight wavefronts, each 128 x 64
-        case 12: return launch_tiled_t<4, 2, 1, 4, 4, 2, true>(a, M, mode, cus, s);  // 128 x 256, four wavefronts each 128 x 64, two workgroups per compute unit
-        case 13: return launch_tiled_t<4, 2, 1, 4, 4>(a, M, mode, cus, s);     // 128 x 256, four wavefronts each 128 x 64
+        case 1: return launch_tiled_t<4, 4, 4, 2, 2, 4>(a, M, mode, cus, s);      // 256 x 256
+        case 3: return launch_tiled_t<4, 2, 4, 2, 2, 4>(a, M, mode, cus, s);      // 128 x 256
+        case 4: return launch_tiled_t<4, 2, 2, 2, 2, 4, 2, true>(a, M, mode, cus, s);   // 128 x 128, two workgroups per compute unit
+        case 7: return launch_tiled_t<4, 2, 4, 2, 4, 4>(a, M, mode, cus, s);      // 128 x 512, eight wavefronts
+        case 8: return launch_tiled_t<4, 2, 4, 2, 2, 4, 2>(a, M, mode, cus, s);   // 128 x 256, two workgroups per compute unit
+        case 11: return launch_tiled_t<4, 4, 2, 1, 8, 4, 1, true>(a, M, mode, cus, s);     // 128 x 512, eight wavefronts, each 128 x 64
+        case 12: return launch_tiled_t<4, 4, 2, 1, 4, 4, 2, true>(a, M, mode, cus, s);  // 128 x 256, four wavefronts each 128 x 64, two workgroups per compute unit
+        case 13: return launch_tiled_t<4, 4, 2, 1, 4, 4>(a, M, mode, cus, s);     // 128 x 256, four wavefronts each 128 x 64
         default: return hipErrorInvalidValue;
     }
 }

@@ -46,6 +46,61 @@ static void decode_word(uint32_t w, int8_t* c) {
 
 static inline int nibble_to_code(uint32_t v) { return v < 8 ? (int)v : (int)v - 16; }
 
+// 16 codes (-1, 0, 1) of one block -> one 32-bit word, layout documented in lqer_internal.h
+static uint32_t encode_word2(const int8_t* c) {
+    uint32_t w = 0;
+    for (int x = 0; x < 4; ++x)
+        for (int i = 0; i < 4; ++i) {
+            const int v = c[4 * x + i];
+            if (v != 0) w |= 1u << (8 * i + 2 * x);
+            if (v < 0) w |= 1u << ((8 * i + 2 * x + 7) & 31);
+        }
+    return w;
+}
+
+static void decode_word2(uint32_t w, int8_t* c) {
+    for (int x = 0; x < 4; ++x)
+        for (int i = 0; i < 4; ++i) {
+            const int mag = (w >> (8 * i + 2 * x)) & 1, sg = (w >> ((8 * i + 2 * x + 7) & 31)) & 1;
+            c[4 * x + i] = (int8_t)(sg ? -mag : mag);
+        }
+}
+
+// the 16 codes of block kb of column n from the canonical bytes (4 bits: nibbles, 2 bits: bit pairs); false on an
+// excluded value (nibble -8, bit pair -2)
+static bool canonical_block(const uint8_t* Wc, int bits, int64_t K, int64_t n, int64_t kb, int8_t* codes) {
+    bool ok = true;
+    if (bits == 4) {
+        const uint8_t* src = Wc + n * (K / 2) + kb * 8;
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t lo = src[e] & 0xF, hi = src[e] >> 4;
+            if (lo == 8 || hi == 8) ok = false;
+            codes[2 * e] = (int8_t)nibble_to_code(lo);
+            codes[2 * e + 1] = (int8_t)nibble_to_code(hi);
+        }
+    } else {
+        const uint8_t* src = Wc + n * (K / 4) + kb * 4;
+        for (int e = 0; e < 16; ++e) {
+            const uint32_t v = (src[e >> 2] >> (2 * (e & 3))) & 3;
+            if (v == 2) ok = false;
+            codes[e] = (int8_t)(v == 3 ? -1 : (int)v);
+        }
+    }
+    return ok;
+}
+
+static void store_canonical_block(uint8_t* Wc, int bits, int64_t K, int64_t n, int64_t kb, const int8_t* codes) {
+    if (bits == 4) {
+        uint8_t* dst = Wc + n * (K / 2) + kb * 8;
+        for (int e = 0; e < 8; ++e) dst[e] = (uint8_t)((codes[2 * e] & 0xF) | ((codes[2 * e + 1] & 0xF) << 4));
+    } else {
+        uint8_t* dst = Wc + n * (K / 4) + kb * 4;
+        for (int e = 0; e < 4; ++e)
+            dst[e] = (uint8_t)((codes[4 * e] & 3) | ((codes[4 * e + 1] & 3) << 2) | ((codes[4 * e + 2] & 3) << 4) |
+                               ((codes[4 * e + 3] & 3) << 6));
+    }
+}
+
 // canonical Wc/We -> tiled records.  Returns LQER_ERR_VALUE on a -8 nibble or an exponent byte > 247.
 // Chooses the record form: exponent nibbles when the layer's exponent bytes span at most 16 values.
 static int tile_weights(Layer& L, const uint8_t* Wc, const uint8_t* We, std::vector<uint8_t>& out) {
@@ -59,10 +114,11 @@ static int tile_weights(Layer& L, const uint8_t* Wc, const uint8_t* We, std::vec
             hi = e > hi ? e : hi;
         }
     const bool compact = hi - lo <= 15;
+    const int bits = L.w_bits;
     L.w_exp_bias = compact ? lo : -1;
-    L.w_rec_bytes = compact ? kWRecordBytesCompact : kWRecordBytes;
+    L.w_rec_bytes = w_record_bytes(bits, compact);
     const int kRec = L.w_rec_bytes, bias = L.w_exp_bias;
-    const int code_off = compact ? kWCompactCodeOffset : 0;
+    const int code_off = compact ? kWCompactCodeOffset : 0, exp_off = w_code_bytes(bits);
     out.assign((size_t)(L.N32 * L.KT) * kRec + kWTailPad, 0);
     std::atomic<int> bad{0};
     parallel_for(L.N32, [&](int64_t g) {
@@ -77,24 +133,23 @@ static int tile_weights(Layer& L, const uint8_t* Wc, const uint8_t* We, std::vec
                         int8_t codes[16] = {0};
                         uint8_t eb = (uint8_t)(bias >= 0 ? bias : 0);       // padding blocks: zero codes, any exponent
                         if (n < L.N && kb < nblk) {
-                            const uint8_t* src = Wc + n * (L.K / 2) + kb * 8;
-                            for (int e = 0; e < 8; ++e) {
-                                const uint32_t lo = src[e] & 0xF, hi = src[e] >> 4;
-                                if (lo == 8 || hi == 8) bad.store(1, std::memory_order_relaxed);
-                                codes[2 * e] = (int8_t)nibble_to_code(lo);
-                                codes[2 * e + 1] = (int8_t)nibble_to_code(hi);
-                            }
+                            if (!canonical_block(Wc, bits, L.K, n, kb, codes)) bad.store(1, std::memory_order_relaxed);
                             eb = We[n * nblk + kb];
                         }
-                        const uint32_t w0 = encode_word(codes), w1 = encode_word(codes + 8);
-                        uint8_t* dst = rec + code_off + c * 1024 + lane * 16 + j * 8;
-                        memcpy(dst, &w0, 4);
-                        memcpy(dst + 4, &w1, 4);
+                        if (bits == 4) {
+                            const uint32_t w0 = encode_word(codes), w1 = encode_word(codes + 8);
+                            uint8_t* dst = rec + code_off + c * 1024 + lane * 16 + j * 8;
+                            memcpy(dst, &w0, 4);
+                            memcpy(dst + 4, &w1, 4);
+                        } else {
+                            const uint32_t w = encode_word2(codes);
+                            memcpy(rec + code_off + (c >> 1) * 1024 + lane * 16 + ((c & 1) * 2 + j) * 4, &w, 4);
+                        }
                         if (bias >= 0) {
                             uint8_t& b2 = rec[lane * 4 + c];                            // nibble 2c + j of the lane's word
                             b2 = (uint8_t)(b2 | ((eb - bias) << (4 * j)));
                         } else {
-                            rec[kWExpOffset + lane * 8 + 2 * c + j] = eb;
+                            rec[exp_off + lane * 8 + 2 * c + j] = eb;
                         }
                     }
             }
@@ -105,6 +160,8 @@ static int tile_weights(Layer& L, const uint8_t* Wc, const uint8_t* We, std::vec
 
 static void untile_weights(const Layer& L, const std::vector<uint8_t>& in, uint8_t* Wc, uint8_t* We) {
     const int64_t nblk = L.K / 16;
+    const int bits = L.w_bits;
+    const int code_off = L.w_exp_bias >= 0 ? kWCompactCodeOffset : 0, exp_off = w_code_bytes(bits);
     parallel_for(L.N32, [&](int64_t g) {
         for (int64_t tile = 0; tile < L.KT; ++tile) {
             const uint8_t* rec = in.data() + (size_t)(tile * L.N32 + g) * L.w_rec_bytes;
@@ -116,21 +173,23 @@ static void untile_weights(const Layer& L, const std::vector<uint8_t>& in, uint8
                     for (int j = 0; j < 2; ++j) {
                         const int64_t kb = tile * 16 + 4 * c + 2 * hh + j;
                         if (kb >= nblk) continue;
-                        uint32_t w0, w1;
-                        const uint8_t* src = rec + (L.w_exp_bias >= 0 ? kWCompactCodeOffset : 0) + c * 1024 + lane * 16 + j * 8;
-                        memcpy(&w0, src, 4);
-                        memcpy(&w1, src + 4, 4);
                         int8_t codes[16];
-                        decode_word(w0, codes);
-                        decode_word(w1, codes + 8);
-                        if (Wc) {
-                            uint8_t* dst = Wc + n * (L.K / 2) + kb * 8;
-                            for (int e = 0; e < 8; ++e)
-                                dst[e] = (uint8_t)((codes[2 * e] & 0xF) | ((codes[2 * e + 1] & 0xF) << 4));
+                        if (bits == 4) {
+                            uint32_t w0, w1;
+                            const uint8_t* src = rec + code_off + c * 1024 + lane * 16 + j * 8;
+                            memcpy(&w0, src, 4);
+                            memcpy(&w1, src + 4, 4);
+                            decode_word(w0, codes);
+                            decode_word(w1, codes + 8);
+                        } else {
+                            uint32_t w;
+                            memcpy(&w, rec + code_off + (c >> 1) * 1024 + lane * 16 + ((c & 1) * 2 + j) * 4, 4);
+                            decode_word2(w, codes);
                         }
+                        if (Wc) store_canonical_block(Wc, bits, L.K, n, kb, codes);
                         if (We) We[n * nblk + kb] = L.w_exp_bias >= 0
                                 ? (uint8_t)(((rec[lane * 4 + c] >> (4 * j)) & 0xF) + L.w_exp_bias)
-                                : rec[kWExpOffset + lane * 8 + 2 * c + j];
+                                : rec[exp_off + lane * 8 + 2 * c + j];
                     }
             }
         }
@@ -293,7 +352,8 @@ static int pick_path(const Layer& L, int64_t M) {
     // The streaming kernel takes up to 32 tokens for any layer, and up to 64 (two blocks of 32 per
     // wavefront) for layers wide enough to fill the chip with four column groups per workgroup.
     if (M <= 32) return 1;
-    if (M <= stream_max_rows() && L.N32 >= 512) return 1;
+    // (with ranks above 64 the T rows of 64 tokens do not fit the streaming kernel's LDS)
+    if (M <= stream_max_rows() && L.N32 >= 512 && L.kp <= 64) return 1;
     return 2;
 }
 
@@ -330,7 +390,7 @@ static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, co
     if (path == 1 && M > stream_max_rows()) return LQER_ERR_SHAPE;
     // a pair of workgroups completes its sum only in memory: with MXINT8 output take the unpaired shape
     if (requant && path == 1 && variant == 0 && stream_variant_adds_into_y(stream_variant(L, M, 0)))
-        variant = stream_variant_unpaired(M);
+        variant = stream_variant_unpaired(L, M);
     if (stages == 0) stages = 3;
     if (!wsp || ((uintptr_t)wsp & 255) != 0) return LQER_ERR_WORKSPACE;
     Workspace ws = plan_workspace(L, M, path, wsp, with_slots);
@@ -419,13 +479,21 @@ int lqer_quantize_mx(const float* x_dev, int64_t rows, int64_t cols, int64_t ld,
 
 int lqer_layer_import(int64_t K, int64_t N, int k, const uint8_t* Wc, const uint8_t* We, const int8_t* Ac,
                       const uint8_t* Ae, const int8_t* Bc, const uint8_t* Be, lqer_layer** out) {
+    return lqer_layer_import_w(4, K, N, k, Wc, We, Ac, Ae, Bc, Be, out);
+}
+
+int lqer_layer_weight_bits(const lqer_layer* layer) { return layer ? layer->L.w_bits : 0; }
+
+int lqer_layer_import_w(int w_bits, int64_t K, int64_t N, int k, const uint8_t* Wc, const uint8_t* We, const int8_t* Ac,
+                        const uint8_t* Ae, const int8_t* Bc, const uint8_t* Be, lqer_layer** out) {
     if (!out) return LQER_ERR_NULL;
     *out = nullptr;
+    if (w_bits != 4 && w_bits != 2) return LQER_ERR_UNSUPPORTED;
     if (K <= 0 || N <= 0 || (K & 15) != 0 || k < 0 || k > K || k > N) return LQER_ERR_SHAPE;
     if (!Wc || !We) return LQER_ERR_NULL;
     if (k > 0 && (!Ac || !Ae || !Bc || !Be)) return LQER_ERR_NULL;
     const int kp = (k + 15) / 16 * 16;
-    if (kp > 64) return LQER_ERR_UNSUPPORTED;
+    if (kp > kMaxRank) return LQER_ERR_UNSUPPORTED;
     lqer_layer* h = new (std::nothrow) lqer_layer;
     if (!h) return LQER_ERR_NO_MEMORY;
     Layer& L = h->L;
@@ -434,7 +502,8 @@ int lqer_layer_import(int64_t K, int64_t N, int k, const uint8_t* Wc, const uint
     L.N32 = (N + 31) / 32;
     L.kp16 = kp / 16;
     L.act_bits = 8;
-    L.w_rec_bytes = kWRecordBytes;
+    L.w_bits = w_bits;
+    L.w_rec_bytes = w_record_bytes(w_bits, false);
     L.w_exp_bias = -1;
     L.Wt = L.At = L.Bt = nullptr;
     if (hipGetDevice(&L.device) != hipSuccess) { delete h; return LQER_ERR_HIP; }

@@ -46,15 +46,29 @@ namespace lqer {
 // B_k: records of [32 columns] x [16 ranks] (one MXINT block per column): codes[32 columns][16 B]
 //      + exps[32 columns][1 B]; ordered [column group][rank block].
 
+// 2-bit weights (the W2A8 setup of Sec. 4.1 / Sec. 4.4): the same record with half the code bytes,
+//   codes[2 halves][64 lanes][16 B]   lane's 16 B of half h = its blocks of chunks 2h and 2h+1, one 32-bit word per
+//                                     block: words (chunk 2h: block 2hh, 2hh+1; chunk 2h+1: block 2hh, 2hh+1)
+//   and the exponents as above (512 B of bytes behind the codes, or 256 B of nibbles in front): 2560 / 2304 B.
+// A word holds the block's 16 codes e0..e15 (-1, 0, 1) as sign and magnitude bits placed so that a rotation and
+// one mask yield four fp8 (E4M3) subnormal bytes s0000001 = +-2^-9:
+//   magnitude of e[4x + i] at bit 8 i + 2 x, its sign at bit (8 i + 2 x + 7) mod 32        (x, i = 0..3)
+//   rotr(w, 2 x) & 0x81818181  -> bytes e[4x], e[4x+1], e[4x+2], e[4x+3]
+// MFMA step s of a chunk uses elements 8 (s % 2) .. + 7 of block s / 2: extractions x = 2 (s % 2) and x + 1.
+
 constexpr int kTileK = 256;          // K covered by one W / A record
 constexpr int kWRecordBytes = 4608;  // with one exponent byte per block
 constexpr int kWRecordBytesCompact = 4352;   // with exponent nibbles (below)
 constexpr int kWExpOffset = 4096;     // exponent bytes sit behind the codes; exponent nibbles (256 B) in front of them:
 constexpr int kWCompactCodeOffset = 256;   // their 8-byte reads then run over into a line the wavefront needs anyway
+// bytes of a record's codes, its size with exponent bytes / nibbles, for b-bit weights (b = 4 or 2)
+constexpr int w_code_bytes(int bits) { return bits == 4 ? 4096 : 2048; }
+constexpr int w_record_bytes(int bits, bool compact) { return w_code_bytes(bits) + (compact ? 256 : 512); }
+constexpr int kMaxRank = 256;        // padded rank kp the kernels take (Sec. 4.1 runs W2A8 with k = 256)
 constexpr int kWTailPad = 16;        // bytes behind the last record: exponent words are read 8 bytes wide in both forms
 constexpr int kARecordBytes = 8192;
 constexpr int kBRecordBytes = 544;
-constexpr int kMaxWExpByte = 247;    // (byte + 7) must stay a finite fp32 exponent field
+constexpr int kMaxWExpByte = 245;    // (byte + 7), for 2-bit weights (byte + 9), must stay a finite fp32 exponent field
 
 struct Layer {
     int64_t K, N;
@@ -63,7 +77,8 @@ struct Layer {
     int64_t N32;       // column groups of 32
     int kp16;          // rank groups (= MXINT blocks along k) of 16
     int device;
-    int w_rec_bytes;   // kWRecordBytes or kWRecordBytesCompact
+    int w_bits;        // mantissa width of W_q: 4 or 2
+    int w_rec_bytes;   // w_record_bytes(w_bits, compact)
     int w_exp_bias;    // compact records: exponent byte = nibble + this; -1: one byte per block
     int act_bits;      // width of the activation codes: 8 or 6
     uint8_t* Wt;       // device, N32*KT records
@@ -115,7 +130,7 @@ struct Requant {
 // Streaming (small M) main kernel.  variant 0 = automatic.
 hipError_t launch_stream(const Layer& L, int64_t M, const Workspace& ws, float* Y, int64_t ldy, const Requant& rq,
                          int variant, hipStream_t s);
-int stream_variant_unpaired(int64_t M);                          // the shape used when pairs of workgroups are ruled out
+int stream_variant_unpaired(const Layer& L, int64_t M);                          // the shape used when pairs of workgroups are ruled out
 int stream_max_rows();
 int stream_variant(const Layer& L, int64_t M, int variant);      // resolves 0 = automatic
 bool stream_variant_adds_into_y(int variant);                    // Y must be zero before the launch
@@ -133,7 +148,8 @@ void set_tiled_wait_limit(int polls);
 // ---- offline construction, shared host steps (build_factors.cpp) ---------------------------
 // exp_bits: width of A_k's and B_k's shared exponents (8, or 4 with one bias per tensor)
 int pack_factors_and_import(int64_t K, int64_t N, int k, const std::vector<uint8_t>& Wc, const std::vector<uint8_t>& We,
-                            const std::vector<double>& A, const std::vector<double>& B, int exp_bits, lqer_layer** out);
+                            const std::vector<double>& A, const std::vector<double>& B, int exp_bits, lqer_layer** out,
+                            int w_bits = 4);
 int scale_from_magnitudes(const std::vector<double>& abar, std::vector<double>& s);
 
 int prep_slices(const Layer& L, int64_t M, int path);

@@ -40,6 +40,23 @@ __device__ __forceinline__ bf16x8 unpack_w8(uint32_t w, float scale) {
     return f.v;
 }
 
+// 2-bit weights: fp32 scale 2^(eb - 127 + 9) for a block with exponent byte eb (no fraction bits; the +9 undoes the
+// 2^-9 of the fp8 subnormal encoding).  eb <= 245 is checked at import.
+__device__ __forceinline__ float w2_scale(uint32_t eb) { return f32_from_bits((eb + 9u) << 23); }
+
+// Eight of the 16 sign-and-magnitude 2-bit codes of a block word (layout in lqer_internal.h) -> 8 bf16 values
+// code * 2^e: elements 8 half .. 8 half + 7.
+__device__ __forceinline__ bf16x8 unpack_w8_b2(uint32_t w, int half, float scale) {
+    const uint32_t r0 = (half ? __builtin_amdgcn_alignbit(w, w, 4) : w) & 0x81818181u;
+    const uint32_t r1 = __builtin_amdgcn_alignbit(w, w, half ? 6 : 2) & 0x81818181u;
+    Frag f;
+    f.h[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r0, scale, false);
+    f.h[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r0, scale, true);
+    f.h[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r1, scale, false);
+    f.h[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r1, scale, true);
+    return f.v;
+}
+
 // Two fp32 values that are exactly representable in bf16 -> packed pair (a low, b high).
 __device__ __forceinline__ uint32_t pack_bf16_exact(float a, float b) {
     return __builtin_amdgcn_perm(f32_bits(b), f32_bits(a), 0x07060302u);

@@ -141,15 +141,21 @@ def adversarial_blocks(rng: np.random.Generator, n_blocks: int) -> np.ndarray:
     return out
 
 
-def random_packed_layer(rng: np.random.Generator, K: int, N: int, k: int):
+def random_packed_layer(rng: np.random.Generator, K: int, N: int, k: int, w_bits: int = 4):
     """Random canonical bytes with the statistics of a quantized Gaussian layer, for timing runs
     at sizes where quantizing real draws on the host would dominate the run: 4-bit codes drawn
-    uniformly from [-7, 7] with exponent bytes near 2^-6, int8 factor codes with exponents near
-    2^-8 (A_k) and 2^-10 (B_k).  Returns a dict of the six canonical arrays plus kp."""
+    uniformly from [-7, 7] (2-bit: from {-1, 0, 1}, four per byte) with exponent bytes near 2^-6, int8 factor
+    codes with exponents near 2^-8 (A_k) and 2^-10 (B_k).  Returns a dict of the six canonical arrays plus kp
+    (and w_bits when it is not 4)."""
     kp = ((k + 15) // 16) * 16
-    nib = rng.integers(0, 15, size=(N, K), dtype=np.uint8)            # 15 values: the codes -7 .. 7
-    nib[nib >= 8] += 1                                                # 8..14 -> 9..15 (codes -7..-1); nibble 8 (-8) never occurs
-    Wc = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+    if w_bits == 4:
+        nib = rng.integers(0, 15, size=(N, K), dtype=np.uint8)        # 15 values: the codes -7 .. 7
+        nib[nib >= 8] += 1                                            # 8..14 -> 9..15 (codes -7..-1); nibble 8 (-8) never occurs
+        Wc = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+    else:
+        pair = rng.integers(0, 3, size=(N, K), dtype=np.uint8)        # 0, 1, 2 -> bit pairs 00, 01, 11 (codes 0, 1, -1)
+        pair[pair == 2] = 3
+        Wc = (pair[:, 0::4] | (pair[:, 1::4] << 2) | (pair[:, 2::4] << 4) | (pair[:, 3::4] << 6)).astype(np.uint8)
     We = rng.integers(119, 123, size=(N, K // 16), dtype=np.uint8)
     Ac = rng.integers(-127, 128, size=(kp, K)).astype(np.int8)
     Ae = rng.integers(117, 121, size=(kp, K // 16), dtype=np.uint8)
@@ -159,4 +165,7 @@ def random_packed_layer(rng: np.random.Generator, K: int, N: int, k: int):
         Ac[k:] = 0
         Ae[k:] = 0
         Bc[:, k:] = 0
-    return dict(K=K, N=N, k=k, kp=kp, Wc=Wc, We=We, Ac=Ac, Ae=Ae, Bc=Bc, Be=Be)
+    d = dict(K=K, N=N, k=k, kp=kp, Wc=Wc, We=We, Ac=Ac, Ae=Ae, Bc=Bc, Be=Be)
+    if w_bits != 4:
+        d["w_bits"] = w_bits
+    return d

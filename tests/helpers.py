@@ -17,19 +17,20 @@ def oracle_layer_small(K, N, k, seed=0, mode=1, outliers=4, gain=30.0, calib_row
     return factors.build_factors(W, calib, k, mode), ch
 
 
-def oracle_layer_big(K, N, k, seed=0, n_outlier=None, gain=50.0, chunk=512):
+def oracle_layer_big(K, N, k, seed=0, n_outlier=None, gain=50.0, chunk=512, w_bits=None):
     """W_q by the oracle quantizer, A_k/B_k from random stand-ins quantized by the oracle.
     Used where an exact SVD would take minutes; the forward pass only needs the bytes."""
     rng = np.random.default_rng(seed)
     n_outlier = max(1, round(0.01 * K)) if n_outlier is None else n_outlier
     ch = synth.gen_outlier_channels(rng, K, n_outlier)
-    Wc = np.empty((N, K // 2), np.uint8)
+    w_bits = factors.W_BITS if w_bits is None else w_bits
+    Wc = np.empty((N, K * w_bits // 8), np.uint8)
     We = np.empty((N, K // 16), np.uint8)
     for n0 in range(0, N, chunk):
         n1 = min(N, n0 + chunk)
         W = synth.gen_weight(rng, K, n1 - n0)
-        c, e = mxint.mx_quantize(W, factors.W_BITS, axis=0)
-        Wc[n0:n1] = mxint.pack_int4(np.ascontiguousarray(c.T))
+        c, e = mxint.mx_quantize(W, w_bits, axis=0)
+        Wc[n0:n1] = mxint.pack_codes(np.ascontiguousarray(c.T), w_bits)
         We[n0:n1] = e.T
     kp = factors.padded_rank(k)
     A, B = synth.gen_factor_standins(rng, K, N, k, ch, gain)
@@ -37,7 +38,7 @@ def oracle_layer_big(K, N, k, seed=0, n_outlier=None, gain=50.0, chunk=512):
     Bp = np.zeros((kp, N)); Bp[:k] = B
     ac, ae = mxint.mx_quantize(Ap, factors.H_BITS, axis=0)
     bc, be = mxint.mx_quantize(Bp, factors.H_BITS, axis=0)
-    layer = factors.PackedLayer(K=K, N=N, k=k, kp=kp, Wc=Wc, We=We,
+    layer = factors.PackedLayer(K=K, N=N, k=k, kp=kp, w_bits=w_bits, Wc=Wc, We=We,
                                 Ac=np.ascontiguousarray(ac.T), Ae=np.ascontiguousarray(ae.T),
                                 Bc=np.ascontiguousarray(bc.T), Be=np.ascontiguousarray(be.T))
     return layer, ch
@@ -45,10 +46,10 @@ def oracle_layer_big(K, N, k, seed=0, n_outlier=None, gain=50.0, chunk=512):
 
 def upload(layer):
     from paper_2402_02446_amd import binding
-    if layer.k == 0:
-        return binding.lqer_layer_import(layer.K, layer.N, 0, layer.Wc, layer.We)
-    return binding.lqer_layer_import(layer.K, layer.N, layer.k, layer.Wc, layer.We,
-                                     layer.Ac, layer.Ae, layer.Bc, layer.Be)
+    fac = (layer.Ac, layer.Ae, layer.Bc, layer.Be) if layer.k > 0 else ()
+    if getattr(layer, "w_bits", 4) != 4:
+        return binding.lqer_layer_import_w(layer.w_bits, layer.K, layer.N, layer.k, layer.Wc, layer.We, *fac)
+    return binding.lqer_layer_import(layer.K, layer.N, layer.k, layer.Wc, layer.We, *fac)
 
 
 # Elementwise bar beside the norm.  Every product that enters an accumulator is exact; what rounds is the fp32

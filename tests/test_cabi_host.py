@@ -57,7 +57,7 @@ def test_import_argument_errors(L):
     assert imp(16, 16, 0, None, p(We), None, None, None, None, C.byref(out)) == 1
     assert imp(16, 16, 4, p(Wc), p(We), None, None, None, None, C.byref(out)) == 1      # factors missing
     assert imp(16, 16, 0, p(Wc), p(We), None, None, None, None, None) == 1
-    assert imp(4096, 4096, 80, p(Wc), p(We), p(Wc), p(We), p(Wc), p(We), C.byref(out)) == 3   # rank > 64
+    assert imp(4096, 4096, 257, p(Wc), p(We), p(Wc), p(We), p(Wc), p(We), C.byref(out)) == 3  # padded rank > 256
 
 
 def test_build_factors_argument_errors(L):
