@@ -54,7 +54,8 @@ typedef enum {
 } lqer_status;
 
 /*
- * Number-format description for lqer_build_factors: {4 or 2, 8, 8 or 4, 16}.
+ * Number-format description for lqer_build_factors: {4 or 2, 8, 8 or 4, 16}, or {4, 8, 16, 128} for the
+ * scaled-integer variant (see lqer_int_layer_import).
  * exp_bits is the width of the shared exponents of W_q, A_k and B_k (Sec. 4.1 gives them 4 bits;
  * activations always keep 8).  The paper states no bias for the 4-bit field; here each of the
  * three tensors has one bias of its own, chosen so that its largest block keeps its exponent:
@@ -260,6 +261,36 @@ int lqer_linear_forward_shared(const lqer_layer* const* layers, int n_layers, co
 int lqer_set_wait_limit(int polls);
 
 /*
+ * The scaled-integer variant of the layer (Table 2, rows "L2QER-INT": INT4 weights in groups of 128, "g128", and 8-bit
+ * activations; Sec. 2.1 for the form of such formats: a scale factor per weight group, per-token scalars for the
+ * activations, an inner product = a fixed-point inner product times an FP16 product of scalars).  The paper prints no
+ * formula; the reading here is the plain symmetric one:
+ *   weights, A_k, B_k: groups of 128 along the contraction axis (B_k: its kp <= 128 ranks are one group per column),
+ *       s = fp16(amax / qmax) rounded to nearest even (1 for an all-zero group), code = clamp(rne(v / s), -qmax, qmax),
+ *       qmax = 7 for W_q (4 bits), 127 for A_k, B_k (8 bits);
+ *   activations: s_t = fp16(amax_t / 127) and code = clamp(rne(x / s_t), -127, 127), both divisions in fp32.
+ * Canonical arrays (host, contraction axis contiguous; scales are FP16 bit patterns):
+ *   Wc[N][K/2] nibbles as above, Ws[N][K/128];  Ac[kp][K] int8, As[kp][K/128];  Bc[N][kp] int8, Bs[N].
+ * K must be a multiple of 128 and kp at most 128 (LQER_ERR_SHAPE / LQER_ERR_UNSUPPORTED); nibble -8, and scales that
+ * are zero, negative or not finite, are excluded (LQER_ERR_VALUE).
+ * lqer_build_factors with cfg = {4, 8, 16, 128} builds such a layer (same steps, Sec. 3.1-3.2 and App. A).
+ * An INT layer runs through lqer_linear_forward, lqer_linear_forward_static and lqer_linear_workspace_bytes
+ * (lqer_linear_path reports 3: one kernel, int8 matrix cores, for every token count); the entry points that take
+ * MXINT codes, launch options, MXINT8 output or layer groups return LQER_ERR_UNSUPPORTED for it, and
+ * lqer_layer_export does too (lqer_int_layer_export is its counterpart).
+ * lqer_quantize_int8_token is the stand-alone per-token quantizer: x_dev [rows][ld] fp32 (16-byte aligned, ld and
+ * cols multiples of 4), codes_dev int8 [rows][cols], scales_dev FP16 bit patterns [rows].
+ */
+int lqer_int_layer_import(int64_t K, int64_t N, int k,
+                          const uint8_t* Wc, const uint16_t* Ws,
+                          const int8_t* Ac, const uint16_t* As,
+                          const int8_t* Bc, const uint16_t* Bs, lqer_layer** out);
+int lqer_int_layer_export(const lqer_layer* layer, uint8_t* Wc, uint16_t* Ws,
+                          int8_t* Ac, uint16_t* As, int8_t* Bc, uint16_t* Bs);
+int lqer_quantize_int8_token(const float* x_dev, int64_t rows, int64_t cols, int64_t ld,
+                             int8_t* codes_dev, uint16_t* scales_dev, void* hip_stream);
+
+/*
  * lqer_linear_forward for callers that cannot allocate device memory or hand over a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments,
  * same kernels and the same bits in Y as lqer_linear_forward with an automatic launch whose tiles
@@ -278,7 +309,7 @@ int lqer_set_wait_limit(int polls);
 int lqer_linear_forward_static(const lqer_layer* layer, const float* X_dev, int64_t M, int64_t ldx,
                                float* Y_dev, int64_t ldy, void* hip_stream);
 
-/* Which path the dispatcher picks for this layer at M tokens: 1 = streaming, 2 = tiled MFMA. */
+/* Which path the dispatcher picks for this layer at M tokens: 1 = streaming, 2 = tiled MFMA, 3 = the INT variant's kernel. */
 int lqer_linear_path(const lqer_layer* layer, int64_t M);
 
 #ifdef __cplusplus

@@ -25,7 +25,8 @@ EXPORTS = ("lqer_status_string", "lqer_quantize_mx", "lqer_build_factors", "lqer
            "lqer_layer_export", "lqer_layer_dims", "lqer_layer_set_activation_bits", "lqer_layer_free", "lqer_linear_workspace_bytes", "lqer_linear_workspace_bytes_ex",
            "lqer_linear_forward", "lqer_linear_forward_q", "lqer_linear_forward_ex", "lqer_linear_forward_requant", "lqer_linear_path",
            "lqer_linear_shared_workspace_bytes", "lqer_linear_forward_shared", "lqer_set_wait_limit",
-           "lqer_linear_forward_static", "lqer_layer_import_w", "lqer_layer_weight_bits")
+           "lqer_linear_forward_static", "lqer_layer_import_w", "lqer_layer_weight_bits",
+           "lqer_int_layer_import", "lqer_int_layer_export", "lqer_quantize_int8_token")
 
 
 class LqerError(RuntimeError):
@@ -72,6 +73,12 @@ def lib() -> C.CDLL:
     L.lqer_layer_import_w.argtypes = [i32, i64, i64, i32, vp, vp, vp, vp, vp, vp, C.POINTER(vp)]
     L.lqer_layer_weight_bits.restype = i32
     L.lqer_layer_weight_bits.argtypes = [vp]
+    L.lqer_int_layer_import.restype = i32
+    L.lqer_int_layer_import.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, C.POINTER(vp)]
+    L.lqer_int_layer_export.restype = i32
+    L.lqer_int_layer_export.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    L.lqer_quantize_int8_token.restype = i32
+    L.lqer_quantize_int8_token.argtypes = [vp, i64, i64, i64, vp, vp, vp]
     L.lqer_layer_export.restype = i32
     L.lqer_layer_export.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     L.lqer_layer_dims.restype = i32
@@ -189,6 +196,38 @@ def lqer_layer_import_w(w_bits, K, N, k, Wc, We, Ac=None, Ae=None, Bc=None, Be=N
     out = C.c_void_p()
     _check(lib().lqer_layer_import_w(int(w_bits), K, N, k, *[_np_ptr(a) for a in arrs], C.byref(out)), "lqer_layer_import_w")
     return Layer(out.value)
+
+
+def lqer_int_layer_import(K, N, k, Wc, Ws, Ac=None, As=None, Bc=None, Bs=None) -> Layer:
+    """INT layer from canonical arrays; scales are float16 arrays."""
+    arrs = [np.ascontiguousarray(Wc, dtype=np.uint8), np.ascontiguousarray(Ws, dtype=np.float16)]
+    for a, dt in ((Ac, np.int8), (As, np.float16), (Bc, np.int8), (Bs, np.float16)):
+        arrs.append(None if (a is None or k == 0) else np.ascontiguousarray(a, dtype=dt))
+    out = C.c_void_p()
+    _check(lib().lqer_int_layer_import(K, N, k, *[_np_ptr(a) for a in arrs], C.byref(out)), "lqer_int_layer_import")
+    return Layer(out.value)
+
+
+def lqer_int_layer_export(layer: Layer):
+    K, N, kp = layer.K, layer.N, layer.kp
+    Wc, Ws = np.zeros((N, K // 2), np.uint8), np.zeros((N, K // 128), np.float16)
+    Ac, As = np.zeros((kp, K), np.int8), np.zeros((kp, K // 128), np.float16)
+    Bc, Bs = np.zeros((N, kp), np.int8), np.zeros((N,), np.float16)
+    ptrs = [_np_ptr(a) for a in ((Wc, Ws, Ac, As, Bc, Bs) if kp else (Wc, Ws))] + ([] if kp else [None] * 4)
+    _check(lib().lqer_int_layer_export(layer.handle, *ptrs), "lqer_int_layer_export")
+    return dict(Wc=Wc, Ws=Ws, Ac=Ac, As=As, Bc=Bc, Bs=Bs)
+
+
+def lqer_quantize_int8_token(x):
+    """x: CUDA fp32 [rows][cols].  Returns (codes int8 [rows][cols], scales float16 [rows]) CUDA tensors."""
+    import torch
+    rows, cols = x.shape
+    ld = x.stride(0) if rows > 1 else max(cols, x.stride(0))
+    codes = torch.empty((rows, cols), dtype=torch.int8, device=x.device)
+    scales = torch.empty((rows,), dtype=torch.float16, device=x.device)
+    _check(lib().lqer_quantize_int8_token(C.c_void_p(x.data_ptr()), rows, cols, ld, C.c_void_p(codes.data_ptr()),
+                                          C.c_void_p(scales.data_ptr()), _stream()), "lqer_quantize_int8_token")
+    return codes, scales
 
 
 def lqer_layer_export(layer: Layer):

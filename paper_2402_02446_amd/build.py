@@ -24,7 +24,7 @@ PROBES_LIB = os.path.join(PKG, "liblqer_probes.so")
 PROBES_SOURCES = ["bench_probes.hip"]
 
 SOURCES = ["lqer_host.cpp", "build_factors.cpp", "kernels_quant.hip", "kernels_prep.hip",
-           "kernels_stream.hip", "kernels_tiled.hip", "kernels_build.hip", "static_entry.hip"]
+           "kernels_stream.hip", "kernels_tiled.hip", "kernels_build.hip", "static_entry.hip", "kernels_int.hip", "int_host.cpp"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

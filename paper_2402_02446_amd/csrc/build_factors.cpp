@@ -72,7 +72,7 @@ static void gemm_tn(const std::vector<double>& G, int64_t K, int64_t N, const st
 }
 
 // Leading-k split of G = S E (K x N): A = S^-1 U_k (K x k), B = Sigma_k V_k^T (k x N).
-static int truncated_split(const std::vector<double>& G, int64_t K, int64_t N, const std::vector<double>& s,
+int truncated_split(const std::vector<double>& G, int64_t K, int64_t N, const std::vector<double>& s,
                            int k, std::vector<double>& A, std::vector<double>& B) {
     const int64_t mn = std::min(K, N);
     int l = k + 16;
@@ -208,7 +208,10 @@ extern "C" int lqer_build_factors(const float* W_host, int64_t K, int64_t N, con
                                   const lqer_config* cfg, lqer_layer** out) try {
     if (!out) return LQER_ERR_NULL;
     *out = nullptr;
-    if (cfg && ((cfg->w_bits != 4 && cfg->w_bits != 2) || cfg->h_bits != 8 || (cfg->exp_bits != 8 && cfg->exp_bits != 4) || cfg->block != 16))
+    // {4, 8, 16, 128}: the scaled-integer variant (Table 2 "L2QER-INT": INT4 weights in groups of 128 with FP16 scales)
+    const bool int_format = cfg && cfg->w_bits == 4 && cfg->h_bits == 8 && cfg->exp_bits == 16 && cfg->block == 128;
+    if (cfg && !int_format &&
+        ((cfg->w_bits != 4 && cfg->w_bits != 2) || cfg->h_bits != 8 || (cfg->exp_bits != 8 && cfg->exp_bits != 4) || cfg->block != 16))
         return LQER_ERR_UNSUPPORTED;
     const int exp_bits = cfg ? cfg->exp_bits : 8;
     const int w_bits = cfg ? cfg->w_bits : 4;
@@ -236,6 +239,8 @@ extern "C" int lqer_build_factors(const float* W_host, int64_t K, int64_t N, con
         const int st = scale_from_magnitudes(abar, s);
         if (st != LQER_OK) return st;
     }
+
+    if (int_format) return build_factors_int(W_host, K, N, s, k, out);
 
     // W_q and G = S (W - W_q)
     const int64_t wc_row = w_bits == 4 ? K / 2 : K / 4;      // bytes of one column's codes

@@ -10,11 +10,6 @@
 #include "lqer_internal.h"
 #include "host_parallel.h"
 
-struct lqer_layer {
-    lqer::Layer L;
-    std::vector<uint8_t> Ae_host;     // A_k's exponent bytes [kp][K/16], needed again only by export
-};
-
 namespace lqer {
 
 static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
@@ -263,9 +258,9 @@ static void untile_a(const Layer& L, const std::vector<uint8_t>& in, const std::
         }
 }
 
-static int tile_b(const Layer& L, const int8_t* Bc, const uint8_t* Be, std::vector<uint8_t>& out) {
+int tile_b(const Layer& L, const int8_t* Bc, const uint8_t* Be, std::vector<uint8_t>& out) {
     out.assign((size_t)(L.N32 * L.kp16) * kBRecordBytes, 0);
-    for (int64_t i = 0; i < L.N * L.kp16; ++i)
+    for (int64_t i = 0; Be && i < L.N * L.kp16; ++i)
         if (Be[i] == 255) return LQER_ERR_VALUE;
     for (int64_t g = 0; g < L.N32; ++g)
         for (int rb = 0; rb < L.kp16; ++rb) {
@@ -274,7 +269,7 @@ static int tile_b(const Layer& L, const int8_t* Bc, const uint8_t* Be, std::vect
                 const int64_t n = g * 32 + c;
                 if (n >= L.N) continue;
                 memcpy(rec + c * 16, Bc + n * L.kp + rb * 16, 16);
-                rec[512 + c] = Be[n * L.kp16 + rb];
+                rec[512 + c] = Be ? Be[n * L.kp16 + rb] : 0;
             }
         }
     return LQER_OK;
@@ -293,14 +288,18 @@ static void untile_b(const Layer& L, const std::vector<uint8_t>& in, int8_t* Bc,
         }
 }
 
-static void free_device(Layer& L) {
+void free_device(Layer& L) {
     if (L.Wt) (void)hipFree(L.Wt);
     if (L.At) (void)hipFree(L.At);
     if (L.Bt) (void)hipFree(L.Bt);
+    if (L.Wsc) (void)hipFree(L.Wsc);
+    if (L.Asc) (void)hipFree(L.Asc);
+    if (L.Bsc) (void)hipFree(L.Bsc);
     L.Wt = L.At = L.Bt = nullptr;
+    L.Wsc = L.Asc = L.Bsc = nullptr;
 }
 
-static int upload(const std::vector<uint8_t>& host, uint8_t** dev) {
+int upload(const std::vector<uint8_t>& host, uint8_t** dev) {
     *dev = nullptr;
     if (host.empty()) return LQER_OK;
     if (hipMalloc((void**)dev, host.size()) != hipSuccess) return LQER_ERR_HIP;
@@ -349,6 +348,7 @@ static Workspace plan_workspace(const Layer& L, int64_t M, int path, void* base,
 }
 
 static int pick_path(const Layer& L, int64_t M) {
+    if (L.format == 1) return 3;                     // the scaled-integer variant has one kernel for every token count
     // The streaming kernel takes up to 32 tokens for any layer, and up to 64 (two blocks of 32 per
     // wavefront) for layers wide enough to fill the chip with four column groups per workgroup.
     if (M <= 32) return 1;
@@ -364,6 +364,16 @@ static int forward_impl(const lqer_layer* layer, const float* X, int64_t ldx, co
     if (!layer) return LQER_ERR_NULL;
     const Layer& L = layer->L;
     if (M < 0) return LQER_ERR_SHAPE;
+    if (L.format == 1) {
+        // the scaled-integer variant: fp32 in, fp32 out, one launch shape
+        if (Xc || rq.codes || (opts && (opts->path != 0 || opts->variant != 0 || opts->stages != 0))) return LQER_ERR_UNSUPPORTED;
+        if (M == 0) return LQER_OK;
+        if (!X || !Y) return LQER_ERR_NULL;
+        if (ldx < L.K || (ldx & 3) != 0 || ((uintptr_t)X & 15) != 0) return LQER_ERR_SHAPE;
+        if (ldy < L.N || (ldy & 3) != 0 || ((uintptr_t)Y & 15) != 0) return LQER_ERR_SHAPE;
+        if (!wsp || ((uintptr_t)wsp & 255) != 0) return LQER_ERR_WORKSPACE;
+        return forward_int(L, X, ldx, M, Y, ldy, wsp, ws_bytes, (hipStream_t)stream);
+    }
     if (M == 0) return LQER_OK;
     const bool requant = rq.codes != nullptr;
     if (requant) {
@@ -423,7 +433,7 @@ static Layer shared_plan_layer(const lqer_layer* const* layers, int n) {
 static bool shared_group_ok(const lqer_layer* const* layers, int n) {
     if (!layers || n < 1) return false;
     for (int i = 0; i < n; ++i) {
-        if (!layers[i]) return false;
+        if (!layers[i] || layers[i]->L.format != 0) return false;
         if (layers[i]->L.K != layers[0]->L.K || layers[i]->L.act_bits != layers[0]->L.act_bits) return false;
     }
     return true;
@@ -502,6 +512,8 @@ int lqer_layer_import_w(int w_bits, int64_t K, int64_t N, int k, const uint8_t* 
     L.N32 = (N + 31) / 32;
     L.kp16 = kp / 16;
     L.act_bits = 8;
+    L.format = 0; L.kp32 = 0;
+    L.Wsc = L.Asc = L.Bsc = nullptr;
     L.w_bits = w_bits;
     L.w_rec_bytes = w_record_bytes(w_bits, false);
     L.w_exp_bias = -1;
@@ -541,6 +553,7 @@ int lqer_layer_export(const lqer_layer* layer, uint8_t* Wc, uint8_t* We, int8_t*
                       uint8_t* Be) {
     if (!layer) return LQER_ERR_NULL;
     const Layer& L = layer->L;
+    if (L.format != 0) return LQER_ERR_UNSUPPORTED;  // lqer_int_layer_export is the call for that format
     try {
     std::vector<uint8_t> buf;
     int st;
@@ -576,7 +589,7 @@ int lqer_layer_dims(const lqer_layer* layer, int64_t* K, int64_t* N, int* k, int
 
 int lqer_layer_set_activation_bits(lqer_layer* layer, int bits) {
     if (!layer) return LQER_ERR_NULL;
-    if (bits != 8 && bits != 6) return LQER_ERR_UNSUPPORTED;
+    if ((bits != 8 && bits != 6) || layer->L.format != 0) return LQER_ERR_UNSUPPORTED;
     layer->L.act_bits = bits;
     return LQER_OK;
 }
@@ -591,6 +604,7 @@ int lqer_layer_free(lqer_layer* layer) {
 size_t lqer_linear_workspace_bytes_ex(const lqer_layer* layer, int64_t M, int path) {
     if (!layer || M <= 0 || path < 0 || path > 2) return 0;
     const Layer& L = layer->L;
+    if (L.format == 1) return path == 0 ? int_workspace_bytes(L, M) : 0;
     if (path == 0) path = pick_path(L, M);
     if (path == 1 && M > stream_max_rows()) return 0;
     return plan_workspace(L, M, path, nullptr).bytes;

@@ -6,6 +6,8 @@
 #include <vector>
 #include "lqer.h"
 
+namespace lqer { struct Layer; }
+
 namespace lqer {
 
 // ---- internal device layout of one layer ------------------------------------------------
@@ -84,6 +86,14 @@ struct Layer {
     uint8_t* Wt;       // device, N32*KT records
     uint8_t* At;       // device, kp16*KT records
     uint8_t* Bt;       // device, N32*kp16 records
+    // The scaled-integer variant (Table 2 "L2QER-INT"; kernels_int.hip): format 1.  Wt then holds [N32][K/128] records of
+    // canonical nibbles ([2 spans of 64 K][64 lanes][16 B]), At [kp32][K/128] records of int8 codes ([4][64 lanes][16 B],
+    // K permuted like the activations), Bt the B_k records above (exponent bytes unused), and the scale tables are fp32:
+    int format;        // 0 = MXINT, 1 = INT (INT4 g128 weights, INT8 g128 factors, INT8 per-token activations)
+    int kp32;          // INT: rank groups of 32 (the projection's output columns)
+    float* Wsc;        // INT: [N32][K/128][32], W_q's FP16 scales divided by 16 (the kernel multiplies codes by 16)
+    float* Asc;        // INT: [kp32][K/128][32]
+    float* Bsc;        // INT: [N32 * 32]
 };
 
 // Workspace layout for one forward call.
@@ -106,6 +116,19 @@ struct Workspace {
 // shape (128 x 512 with one workgroup per compute unit, 128 x 256 with two).
 constexpr int64_t kTiledPartBytesPerCu = 256 * 1024;
 constexpr int kTiledFlags = 1024;
+
+}  // namespace lqer
+
+struct lqer_layer {
+    lqer::Layer L;
+    std::vector<uint8_t> Ae_host;     // A_k's exponent bytes [kp][K/16], needed again only by export
+    // INT layers keep their canonical arrays for export
+    std::vector<uint8_t> iWc;
+    std::vector<int8_t> iAc, iBc;
+    std::vector<uint16_t> iWs, iAs, iBs;
+};
+
+namespace lqer {
 
 // ---- kernel launchers (each returns the hipError_t of its launch) ------------------------
 hipError_t launch_quantize_mx(const float* x, int64_t rows, int64_t cols, int64_t ld, int bits,
@@ -151,6 +174,21 @@ int pack_factors_and_import(int64_t K, int64_t N, int k, const std::vector<uint8
                             const std::vector<double>& A, const std::vector<double>& B, int exp_bits, lqer_layer** out,
                             int w_bits = 4);
 int scale_from_magnitudes(const std::vector<double>& abar, std::vector<double>& s);
+
+// ---- the scaled-integer variant (int_host.cpp, kernels_int.hip) ------------------------------------------------------
+hipError_t launch_quant_token(const float* X, int64_t rows, int64_t K, int64_t ldx, int8_t* codes, int64_t ldc,
+                              float* scale_f32, uint16_t* scale_f16, bool perm, hipStream_t s);
+size_t int_workspace_bytes(const Layer& L, int64_t M);
+int forward_int(const Layer& L, const float* X, int64_t ldx, int64_t M, float* Y, int64_t ldy, void* ws, size_t ws_bytes,
+                hipStream_t s);
+void free_device(Layer& L);
+int upload(const std::vector<uint8_t>& host, uint8_t** dev);
+// canonical B_k codes -> the records both formats use (exponent bytes from Be, or zero when Be is null)
+int tile_b(const Layer& L, const int8_t* Bc, const uint8_t* Be, std::vector<uint8_t>& out);
+// rank-k split of G = S E_q (K x N, fp64): A = S^-1 U_k (K x k), B = Sigma_k V_k^T (k x N)
+int truncated_split(const std::vector<double>& G, int64_t K, int64_t N, const std::vector<double>& s, int k,
+                    std::vector<double>& A, std::vector<double>& B);
+int build_factors_int(const float* W_host, int64_t K, int64_t N, const std::vector<double>& s, int k, lqer_layer** out);
 
 int prep_slices(const Layer& L, int64_t M, int path);
 // lqer_linear_forward with the given scratch as its workspace, planned without the slots of the tiled kernel's

@@ -23,7 +23,7 @@ def L():
 def test_every_declared_symbol_is_exported(L):
     header = open(os.path.join(ROOT, "include", "lqer.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(lqer_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(lqer_[a-z0-9_]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(L, name) is not None
