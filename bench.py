@@ -44,6 +44,7 @@ sys.path.insert(0, ROOT)
 METRIC = "LQER W4A8 linear: TFLOP/s + % roofline (HBM GB/s M<=16, MFMA util M>=2048)"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, vendor figure
+MFMA_INT8_PEAK_TOPS = 5000.0    # dense int8 MFMA, vendor figure
 LLC_BYTES = 256 << 20
 
 
@@ -485,6 +486,52 @@ def run_w2a8(rng, peaks):
     return out
 
 
+def run_int_variant(rng, peaks):
+    """The scaled-integer variant (Table 2 "L2QER-INT": INT4 g128 weights, INT8 per-token activations, k = 32) on the
+    LLaMA-7B-shaped layers: decode on a ring of device copies beyond the last-level cache, prefill at M = 2048 and the
+    4096 x 4096 linear at 65536 tokens.  One step = per-token quantizer + projection + main product (three launches);
+    the fractions are of the whole step: against HBM for M = 16 (0.515625 B per weight), against the dense int8
+    matrix-core peak (5.0 POP/s) for prefill."""
+    import torch
+    from paper_2402_02446_amd import binding, synth
+    out = []
+    for (name, K, N, k, Ms) in (("INT 7B q_proj", 4096, 4096, 32, (16, 65536)), ("INT 7B MLP up", 4096, 11008, 32, (2048,)),
+                                ("INT 7B MLP down", 11008, 4096, 32, (2048,))):
+        d = synth.random_int_layer(rng, K, N, k)
+        kp = d["kp"]
+        per = K * N * 0.515625
+        n = max(1, int(np.ceil(1.25 * LLC_BYTES / per))) if 16 in Ms else 1
+        layers = [binding.lqer_int_layer_import(K, N, k, d["Wc"], d["Ws"], d["Ac"], d["As"], d["Bc"], d["Bs"]) for _ in range(n)]
+        for M in Ms:
+            X = torch.randn((M, K), device="cuda", dtype=torch.float32)
+            Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+            for l in layers:
+                l.workspace(M)
+            f = lambda i: binding.lqer_linear_forward(layers[i % n], X, Y=Y)
+            for i in range(n):
+                f(i)
+            torch.cuda.synchronize()
+            steps = 2 * n if M <= 16 else (10 if M <= 2048 else 3)
+            ms = _graph_ms(f, steps)
+            ops = flops_forward(M, K, N, kp)
+            by = K * N * 0.515625 + K * kp * 1.015625 + kp * N * 1.0 + 4.0 * M * K + 4.0 * M * N
+            rec = {"workload": name, "M": M, "K": K, "N": N, "k": k, "format": "INT4 g128 / INT8 per token",
+                   "ring_layers": n, "ms_per_step": ms, "tops": ops / (ms * 1e-3) / 1e12}
+            if M <= 16:
+                ach = by / (ms * 1e-3) / 1e9
+                rec["roofline"] = {"bound": "hbm", "kernel": "whole step (quant_token_kernel + 2 x int_gemm_kernel)", "achieved": ach,
+                                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
+            else:
+                ach = ops / (ms * 1e-3) / 1e12
+                rec["roofline"] = {"bound": "mfma", "kernel": "whole step (quant_token_kernel + 2 x int_gemm_kernel)", "achieved": ach,
+                                   "peak": MFMA_INT8_PEAK_TOPS, "unit": "TOP/s", "frac": ach / MFMA_INT8_PEAK_TOPS, "traffic": None}
+            out.append(rec)
+            del X, Y
+        for l in layers:
+            l.free()
+    return out
+
+
 def time_build_factors(rng):
     """Wall time of the offline step per layer shape of cfg5: lqer_build_factors (host fp64 + upload, from host
     arrays) and lqer_build_factors_device (device kernels + small host steps, from device tensors; second call,
@@ -666,6 +713,7 @@ def main():
         extra["cfg5"] = run_cfg5(3, rng, peaks)
         extra["added_rows"] = run_added_rows(rng)
         extra["w2a8_rank256"] = run_w2a8(rng, peaks)
+        extra["int_variant"] = run_int_variant(rng, peaks)
         extra["build_factors_seconds_per_layer"] = time_build_factors(rng)
     t_gpu = time.perf_counter() - t_start
     cpu = cpu_baseline(ctx, K, N, kp)

@@ -309,6 +309,13 @@ int lqer_quantize_int8_token(const float* x_dev, int64_t rows, int64_t cols, int
 int lqer_linear_forward_static(const lqer_layer* layer, const float* X_dev, int64_t M, int64_t ldx,
                                float* Y_dev, int64_t ldy, void* hip_stream);
 
+/*
+ * Diagnostic, host only (no device call, runs without a GPU): tiles pseudo-random canonical bytes into the device
+ * record layouts of Sec. 4.1's formats (4- and 2-bit weights, both exponent forms, ragged sizes, ranks to 256) and back,
+ * and compares.  LQER_OK, or LQER_ERR_VALUE at the first difference.  Meant for builds with host sanitizers.
+ */
+int lqer_selftest_layouts(void);
+
 /* Which path the dispatcher picks for this layer at M tokens: 1 = streaming, 2 = tiled MFMA, 3 = the INT variant's kernel. */
 int lqer_linear_path(const lqer_layer* layer, int64_t M);
 

@@ -26,7 +26,7 @@ EXPORTS = ("lqer_status_string", "lqer_quantize_mx", "lqer_build_factors", "lqer
            "lqer_linear_forward", "lqer_linear_forward_q", "lqer_linear_forward_ex", "lqer_linear_forward_requant", "lqer_linear_path",
            "lqer_linear_shared_workspace_bytes", "lqer_linear_forward_shared", "lqer_set_wait_limit",
            "lqer_linear_forward_static", "lqer_layer_import_w", "lqer_layer_weight_bits",
-           "lqer_int_layer_import", "lqer_int_layer_export", "lqer_quantize_int8_token")
+           "lqer_int_layer_import", "lqer_int_layer_export", "lqer_quantize_int8_token", "lqer_selftest_layouts")
 
 
 class LqerError(RuntimeError):

@@ -66,5 +66,30 @@ def build(extra_flags=(), verbose: bool = True) -> str:
     return LIB
 
 
+HOST_SOURCES = ["lqer_host.cpp", "build_factors.cpp", "int_host.cpp"]
+ASAN_EXE = os.path.join(BUILD, "host_selftest_asan")
+
+
+def build_host_asan() -> str:
+    """The library's host sources and csrc/selftest_main.cpp compiled with AddressSanitizer and UBSan (host code only;
+    the kernel objects of the normal build are linked in unchanged): _build/host_selftest_asan.  Needs build() first."""
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    objs = []
+    for src in HOST_SOURCES + ["selftest_main.cpp"]:
+        obj = os.path.join(BUILD, os.path.splitext(src)[0] + ".asan.o")
+        cmd = [_hipcc(), *COMMON, *san, "-c", os.path.join(CSRC, src), "-o", obj]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError(f"hipcc (sanitizers) failed on {src}:\n{res.stderr}")
+        objs.append(obj)
+    kern = [os.path.join(BUILD, os.path.splitext(s)[0] + ".o") for s in SOURCES if s not in HOST_SOURCES]
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
+           "-o", ASAN_EXE, *objs, *kern, "-lpthread"]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("link (sanitizers) failed:\n" + res.stderr)
+    return ASAN_EXE
+
+
 if __name__ == "__main__":
     build(extra_flags=sys.argv[1:])

@@ -1,5 +1,6 @@
 // Host side of liblqer: the C ABI, layer import/export (canonical bytes <-> tiled device layout),
 // workspace planning and the dispatch between the streaming and the tiled main kernel.
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdlib>
@@ -675,6 +676,55 @@ int lqer_linear_forward_shared(const lqer_layer* const* layers, int n_layers, co
         if (e != hipSuccess) return LQER_ERR_HIP;
     }
     return LQER_OK;
+}
+
+// Host-only check of the layout transforms (no device call): pseudo-random canonical bytes are tiled into the device
+// records and untiled again for 4- and 2-bit weights, both exponent forms, ragged K, N and ranks; meant to be run in a
+// build with host sanitizers.  Returns LQER_OK, or LQER_ERR_VALUE at the first difference.
+int lqer_selftest_layouts(void) {
+    try {
+        uint64_t state = 0x243F6A8885A308D3ull;
+        auto rnd = [&state]() { state = state * 6364136223846793005ull + 1442695040888963407ull; return (uint32_t)(state >> 33); };
+        const int64_t shapes[][3] = {{16, 1, 0}, {48, 40, 8}, {272, 100, 33}, {1040, 65, 256}, {2304, 31, 64}};
+        for (int bits = 2; bits <= 4; bits += 2)
+            for (int wide = 0; wide < 2; ++wide)
+                for (const auto& sh : shapes) {
+                    Layer L{};
+                    L.K = sh[0]; L.N = sh[1]; L.k = (int)std::min<int64_t>(sh[2], std::min(sh[0], sh[1]));
+                    L.kp = (L.k + 15) / 16 * 16; L.kp16 = L.kp / 16;
+                    L.KT = (L.K + kTileK - 1) / kTileK; L.N32 = (L.N + 31) / 32;
+                    L.w_bits = bits;
+                    const int64_t nblk = L.K / 16, wrow = L.K * bits / 8;
+                    std::vector<uint8_t> Wc((size_t)L.N * wrow), We((size_t)L.N * nblk), Ae((size_t)L.kp * nblk), Be((size_t)L.N * L.kp16);
+                    std::vector<int8_t> Ac((size_t)L.kp * L.K), Bc((size_t)L.N * L.kp);
+                    for (auto& b : Wc) {
+                        if (bits == 4) { const uint32_t lo = rnd() % 15, hi = rnd() % 15; b = (uint8_t)((lo >= 8 ? lo + 1 : lo) | ((hi >= 8 ? hi + 1 : hi) << 4)); }
+                        else { b = 0; for (int j = 0; j < 4; ++j) { const uint32_t v = rnd() % 3; b = (uint8_t)(b | ((v == 2 ? 3u : v) << (2 * j))); } }
+                    }
+                    for (auto& e : We) e = (uint8_t)(wide ? rnd() % 246 : 110 + rnd() % 16);
+                    for (auto& e : Ae) e = (uint8_t)(30 + rnd() % 220);    // (code * 2^(e-6) must be a normal bf16 number)
+                    for (auto& e : Be) e = (uint8_t)(rnd() % 255);
+                    for (auto& c : Ac) c = (int8_t)((int)(rnd() % 255) - 127);
+                    for (auto& c : Bc) c = (int8_t)((int)(rnd() % 255) - 127);
+                    std::vector<uint8_t> rec, Wc2(Wc.size()), We2(We.size());
+                    if (tile_weights(L, Wc.data(), We.data(), rec) != LQER_OK) return LQER_ERR_VALUE;
+                    if (L.N * nblk >= 256 && (L.w_exp_bias >= 0) != (wide == 0)) return LQER_ERR_VALUE;   // both exponent forms are exercised
+                    rec.resize(rec.size() - kWTailPad);
+                    untile_weights(L, rec, Wc2.data(), We2.data());
+                    if (Wc2 != Wc || We2 != We) return LQER_ERR_VALUE;
+                    if (L.kp > 0) {
+                        std::vector<uint8_t> ra, rb, Ae2(Ae.size()), Be2(Be.size());
+                        std::vector<int8_t> Ac2(Ac.size()), Bc2(Bc.size());
+                        if (tile_a(L, Ac.data(), Ae.data(), ra) != LQER_OK || tile_b(L, Bc.data(), Be.data(), rb) != LQER_OK) return LQER_ERR_VALUE;
+                        untile_a(L, ra, Ae, Ac2.data(), Ae2.data());
+                        untile_b(L, rb, Bc2.data(), Be2.data());
+                        if (Ac2 != Ac || Ae2 != Ae || Bc2 != Bc || Be2 != Be) return LQER_ERR_VALUE;
+                    }
+                }
+        return LQER_OK;
+    } catch (...) {
+        return LQER_ERR_NO_MEMORY;
+    }
 }
 
 int lqer_set_wait_limit(int polls) {

@@ -169,3 +169,22 @@ def random_packed_layer(rng: np.random.Generator, K: int, N: int, k: int, w_bits
     if w_bits != 4:
         d["w_bits"] = w_bits
     return d
+
+
+def random_int_layer(rng: np.random.Generator, K: int, N: int, k: int):
+    """Random canonical arrays of the scaled-integer variant (INT4 codes in groups of 128 with FP16 scales, INT8
+    factors) with the statistics of a quantized Gaussian layer, for timing runs: codes uniform in [-7, 7], weight
+    scales near 0.06 / 7, factor scales near 2^-8 / 127 (A_k) and 2^-4 / 127 (B_k).  Returns a dict of the six arrays plus kp."""
+    kp = ((k + 15) // 16) * 16
+    nib = rng.integers(0, 15, size=(N, K), dtype=np.uint8)
+    nib[nib >= 8] += 1
+    Wc = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+    Ws = (rng.uniform(0.05, 0.07, size=(N, K // 128)) / 7.0).astype(np.float16)
+    Ac = rng.integers(-127, 128, size=(kp, K)).astype(np.int8)
+    As = (rng.uniform(0.8, 1.2, size=(kp, K // 128)) * 2.0 ** -8 / 127.0).astype(np.float16)
+    Bc = rng.integers(-127, 128, size=(N, kp)).astype(np.int8)
+    Bs = (rng.uniform(0.8, 1.2, size=(N,)) * 2.0 ** -4 / 127.0).astype(np.float16)
+    if kp > k:
+        Ac[k:] = 0
+        Bc[:, k:] = 0
+    return dict(K=K, N=N, k=k, kp=kp, Wc=Wc, Ws=Ws, Ac=Ac, As=As, Bc=Bc, Bs=Bs)
