@@ -21,7 +21,10 @@ struct IntGemmArgs {
     const float* Wsc;
     int64_t M, N, N32, G;
     float* Out; int64_t ldo;
+    int64_t g_per_z;
+    int64_t out_z_stride;
     const float* T; int64_t ldt;
+    int S; int64_t t_stride;
     const uint8_t* Bt; const float* Bsc;
     int kp16;
 };
@@ -73,10 +76,20 @@ static int upload_floats(const std::vector<float>& host, float** dev) {
 // every run of 32 as its 16 even elements followed by its 16 odd ones
 static inline int perm_pos(int e) { return (e & ~31) + ((e & 1) << 4) + ((e & 31) >> 1); }
 
+// K planes of the projection: it has few output columns, so with few token tiles its K groups are spread over
+// workgroups (each keeps at least four groups); the main kernel adds the planes' partial T in plane order.
+static int projection_planes(const Layer& L, int64_t M) {
+    const int64_t tiles = (M + 127) / 128, G = L.K / 128;
+    int64_t s = 1;
+    while (tiles * s < 256 && s < 8 && G / (2 * s) >= 4) s *= 2;
+    return (int)s;
+}
+
 size_t int_workspace_bytes(const Layer& L, int64_t M) {
     if (M <= 0) return 0;
     const int64_t mp = round_up(M, 128);
-    return (size_t)(round_up(mp * L.K, 256) + round_up(mp * 4, 256) + mp * (int64_t)L.kp32 * 32 * 4);
+    return (size_t)(round_up(mp * L.K, 256) + round_up(mp * 4, 256) +
+                    (int64_t)projection_planes(L, M) * mp * (int64_t)L.kp32 * 32 * 4);
 }
 
 int forward_int(const Layer& L, const float* X, int64_t ldx, int64_t M, float* Y, int64_t ldy, void* ws, size_t ws_bytes,
@@ -90,12 +103,17 @@ int forward_int(const Layer& L, const float* X, int64_t ldx, int64_t M, float* Y
     if (launch_quant_token(X, M, L.K, ldx, Xc, L.K, Xs, nullptr, true, s) != hipSuccess) return LQER_ERR_HIP;
     IntGemmArgs a;
     a.Xc = Xc; a.ldxc = L.K; a.Xs = Xs; a.G = L.K / 128; a.M = M;
+    const int S = projection_planes(L, M);
     a.T = nullptr; a.ldt = ldt; a.Bt = nullptr; a.Bsc = nullptr; a.kp16 = 0;
+    a.S = S; a.t_stride = mp * ldt;
     if (L.kp > 0) {
         a.Wt = L.At; a.Wsc = L.Asc; a.N = ldt; a.N32 = L.kp32; a.Out = T; a.ldo = ldt;
+        a.g_per_z = (a.G + S - 1) / S; a.out_z_stride = mp * ldt;
         if (launch_int_gemm(true, a, s) != hipSuccess) return LQER_ERR_HIP;
+        a.S = (int)((a.G + a.g_per_z - 1) / a.g_per_z);         // planes that exist
     }
     a.Wt = L.Wt; a.Wsc = L.Wsc; a.N = L.N; a.N32 = L.N32; a.Out = Y; a.ldo = ldy;
+    a.g_per_z = a.G; a.out_z_stride = 0;
     a.T = T; a.Bt = L.Bt; a.Bsc = L.Bsc; a.kp16 = L.kp16;
     if (launch_int_gemm(false, a, s) != hipSuccess) return LQER_ERR_HIP;
     return LQER_OK;

@@ -91,9 +91,12 @@ struct IntGemmArgs {
     const uint8_t* Wt;                   // weight records [N32][G][rec]: 4 bits: [2 spans][64 lanes][16 B]; 8 bits: [4 steps][64 lanes][16 B]
     const float* Wsc;                    // scales [N32][G][32] (4 bits: already divided by 16)
     int64_t M, N, N32, G;
-    float* Out; int64_t ldo;             // Y [M][ldo], or T [rows padded][ldo] for the projection
+    float* Out; int64_t ldo;             // Y [M][ldo], or T [S][rows padded][ldo] for the projection
+    int64_t g_per_z;                     // K groups per plane of grid.z (the projection splits K over S planes; G otherwise)
+    int64_t out_z_stride;                // floats between the planes' outputs
     // rank-k correction (TAIL)
-    const float* T; int64_t ldt;         // [rows padded][ldt] fp32
+    const float* T; int64_t ldt;         // [S][rows padded][ldt] fp32 partial sums of T, added in plane order
+    int S; int64_t t_stride;
     const uint8_t* Bt; const float* Bsc; // B_k records [N32][kp16][kBRecordBytes], scales [N32 * 32]
     int kp16;
 };
@@ -153,16 +156,19 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
 
+    // this workgroup's K groups [gb, ge)
+    const int64_t gb = (int64_t)blockIdx.z * a.g_per_z;
+    const int64_t ge = gb + a.g_per_z < a.G ? gb + a.g_per_z : a.G;
     WSet w0, w1;
     u32x4 stx[4];
-    fetch_x(stx, 0);
-    load_w(w0, 0);
+    fetch_x(stx, gb);
+    load_w(w0, gb);
     store_x(stx, 0);
 
     auto step = [&](const WSet& cur, WSet& nxt, int64_t g) {
         __syncthreads();                             // tile g is complete; the other buffer is free again
-        const int buf = (int)(g & 1);
-        const int64_t gn = g + 1 < a.G ? g + 1 : g;  // clamped: loads stay unconditional
+        const int buf = (int)((g - gb) & 1);
+        const int64_t gn = g + 1 < ge ? g + 1 : g;   // clamped: loads stay unconditional
         fetch_x(stx, gn);
         load_w(nxt, gn);
         // this group's scales: needed only after its MFMAs, which hide the round trip
@@ -213,9 +219,9 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
                 for (int r = 0; r < 16; ++r) acc[tm][tn][r] += (float)ia[tm][tn][r] * sc[tn][r >> 2][r & 3];
         store_x(stx, buf ^ 1);                       // last read two barriers ago (a clamped re-write of the last tile is harmless)
     };
-    for (int64_t g = 0; g < a.G; g += 2) {
+    for (int64_t g = gb; g < ge; g += 2) {
         step(w0, w1, g);
-        if (g + 1 < a.G) step(w1, w0, g + 1);
+        if (g + 1 < ge) step(w1, w0, g + 1);
     }
 
     // ---- epilogue: token scale, rank-k correction, store ----------------------------------------------------------
@@ -251,7 +257,13 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm) {
                     const float* src = a.T + (m0 + wr * 64 + tm * 32 + t) * a.ldt + rb * 16 + 8 * hh;
-                    const f32x4 p0 = *reinterpret_cast<const f32x4*>(src), p1 = *reinterpret_cast<const f32x4*>(src + 4);
+                    f32x4 p0 = *reinterpret_cast<const f32x4*>(src), p1 = *reinterpret_cast<const f32x4*>(src + 4);
+                    for (int z = 1; z < a.S; ++z) {                      // the projection's K planes, in plane order
+                        const f32x4 q0 = *reinterpret_cast<const f32x4*>(src + z * a.t_stride);
+                        const f32x4 q1 = *reinterpret_cast<const f32x4*>(src + z * a.t_stride + 4);
+                        p0 += q0;
+                        p1 += q1;
+                    }
                     const float v[8] = {p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
                     Frag hi, lo;
 #pragma unroll
@@ -298,7 +310,7 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
                 const int64_t n = cg * 32 + 8 * r4 + 4 * hh;
-                float* dst = a.Out + row * a.ldo + n;
+                float* dst = a.Out + (int64_t)blockIdx.z * a.out_z_stride + row * a.ldo + n;
                 const f32x4 v = f32x4{acc[tm][tn][4 * r4], acc[tm][tn][4 * r4 + 1], acc[tm][tn][4 * r4 + 2], acc[tm][tn][4 * r4 + 3]};
                 if (n + 3 < a.N) {
                     *reinterpret_cast<f32x4*>(dst) = v;
@@ -315,7 +327,8 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
 // Projection T = X_q A_k (Out = T, N = padded rank) or main product with the correction.
 hipError_t launch_int_gemm(bool projection, const IntGemmArgs& a, hipStream_t s) {
     if (a.M == 0) return hipSuccess;
-    const dim3 grid((unsigned)((a.N + 127) / 128), (unsigned)((a.M + 127) / 128)), block(256);
+    const unsigned planes = (unsigned)((a.G + a.g_per_z - 1) / a.g_per_z);
+    const dim3 grid((unsigned)((a.N + 127) / 128), (unsigned)((a.M + 127) / 128), planes), block(256);
     if (projection) hipLaunchKernelGGL((int_gemm_kernel<8, false>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((int_gemm_kernel<4, true>), grid, block, 0, s, a);
     return hipGetLastError();

@@ -55,9 +55,27 @@ constexpr int kPrepWaves = 8;
 // SRC: where the activations come from: 0 = fp32 X (quantized here), 1 = MXINT codes and exponent bytes,
 // 2 = the bf16 matrix an earlier launch on the same X left in the workspace (nothing is stored again: only T
 // is computed, for another layer applied to the same activations).
-template <int SRC, bool FINAL, int MAXG, bool CELLS>
-__global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
-    __shared__ float red[kPrepWaves][MAXG][64][4];
+template <int CTRL>
+__device__ __forceinline__ float dpp_quad(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+template <int SRC, bool FINAL, int MAXG, bool CELLS, bool RW = false>
+__global__ __launch_bounds__(64 * kPrepWaves, RW ? 4 : 1) void prep_kernel(PrepArgs a) {
+    static_assert(!RW || (SRC == 0 && !CELLS), "the row-wise form reads fp32 rows and writes row-major bf16");
+    // ROWWISE (fp32 X in, row-major bf16 out: the prefill case, bound by HBM): a wavefront reads and writes whole rows
+    // of its 16 x 256 tile - 1 KiB per load, 512 B per store, every cache line touched by one instruction - with the
+    // four lanes of a quad sharing a block, and turns the tile into the MFMA operand order (lane = token, 16-byte
+    // runs of one block) through 8 KB of LDS of its own; the sums of T go through the same memory afterwards.
+    // Chosen by the launcher for launches of many workgroups; with few (prefill calls of a few thousand tokens, where K
+    // is split over workgroups) the longer chain load - quantize - LDS - MFMA per tile and the two workgroups per
+    // compute unit cost more than the coalescing gains (measured: 8192 wide, 4096 tokens 46 -> 52 us; 65536 tokens of
+    // 4096 channels 373 -> 308 us), and the lane-per-block form below is used.
+    constexpr bool ROWWISE = RW;
+    constexpr int RED_BYTES = kPrepWaves * MAXG * 64 * 16;
+    constexpr int SMEM_BYTES = ROWWISE ? (kPrepWaves * 8192 > RED_BYTES ? kPrepWaves * 8192 : RED_BYTES) : RED_BYTES;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM_BYTES];
+    float (*red)[MAXG][64][4] = reinterpret_cast<float (*)[MAXG][64][4]>(smem);
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -119,8 +137,71 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
                 }
             }
         }
+        if constexpr (ROWWISE) {
+            uint8_t* tl = smem + wave * 8192;                 // [16 rows][32 cells of 16 B], cell index XOR row
+            const int64_t col = tile * kTileK + 4 * lane;     // this lane's four columns (K is a multiple of 16: all in or all out)
+            const bool col_ok = col < a.K;
+            // four batches of four rows: the next batch's loads are on their way while one is quantized.  Rows past M
+            // repeat the last one (their stores are skipped); columns past K are zeroed after the load.
+            const int64_t row0 = (int64_t)blockIdx.x * 16;
+            const int64_t last = a.M - 1 - row0;              // >= 0: the grid covers M
+            const int64_t ccol = col_ok ? col : 0;
+            const float* xsrc = a.X + row0 * a.ldx + ccol;
+            uint16_t* xdst = a.Xh + row0 * a.ldxh + col;
+            const float keep = col_ok ? 1.0f : 0.0f;
+            auto load_rows = [&](f32x4 (&v)[4], int i0) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
+                for (int i = 0; i < 4; ++i) {
+                    const int64_t r = (i0 + i) <= last ? (i0 + i) : last;
+                    v[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(xsrc + r * a.ldx));
+                }
+            };
+            const float lim = (float)((2 << a.act_frac) - 1);
+            auto quantize_rows = [&](const f32x4 (&v)[4], int i0) {
+#pragma unroll
+                for (int ii = 0; ii < 4; ++ii) {
+                    const int i = i0 + ii;
+                    const f32x4 x = v[ii] * keep;
+                    float m = __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(x[0]), __builtin_fabsf(x[1])),
+                                              __builtin_fmaxf(__builtin_fabsf(x[2]), __builtin_fabsf(x[3])));
+                    m = __builtin_fmaxf(m, dpp_quad<0xB1>(m));    // quad_perm [1,0,3,2]
+                    m = __builtin_fmaxf(m, dpp_quad<0x4E>(m));    // quad_perm [2,3,0,1]
+                    const uint32_t eb = (f32_bits(m) >> 23) & 0xFFu;
+                    const int sh = a.act_frac - ((int)eb - 127);
+                    const float scale = x_scale(eb, a.act_frac);
+                    float c[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float r = __builtin_rintf(__builtin_amdgcn_ldexpf(x[j], sh));
+                        c[j] = __builtin_fminf(__builtin_fmaxf(r, -lim), lim) * scale;
+                    }
+                    const u32x2 w = u32x2{pack_bf16_exact(c[0], c[1]), pack_bf16_exact(c[2], c[3])};
+                    // columns between K and the end of the last tile are written as zeros: the main kernel reads whole tiles
+                    if (store_x && i <= last) *reinterpret_cast<u32x2*>(xdst + i * a.ldxh) = w;
+                    *reinterpret_cast<u32x2*>(tl + i * 512 + (((lane >> 1) ^ i) << 4) + (lane & 1) * 8) = w;
+                }
+            };
+            f32x4 va[4], vb[4];
+            load_rows(va, 0);
+            load_rows(vb, 4);
+            __builtin_amdgcn_wave_barrier();                  // the previous tile's operand reads are issued before these writes
+            quantize_rows(va, 0);
+            load_rows(va, 8);
+            quantize_rows(vb, 4);
+            load_rows(vb, 12);
+            quantize_rows(va, 8);
+            quantize_rows(vb, 12);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int p = 0; p < 4; ++p)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    xf[p][h].u = *reinterpret_cast<const u32x4*>(tl + t * 512 + (((2 * (q + 4 * p) + h) ^ t) << 4));
+        }
+#pragma unroll
+        for (int p = 0; p < (ROWWISE ? 0 : 4); ++p) {
             const int64_t kb = tile * 16 + q + 4 * p;        // block index along K
             const bool ok = row_ok && kb < nblk;
             float scale = 0.f;
@@ -223,6 +304,8 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
                     acc[g] = mfma16(af[0].v, xf[p][0].v, acc[g]);
                     acc[g] = mfma16(af[1].v, xf[p][1].v, acc[g]);
                 }
+                // one rank group's eight loads in flight at a time: all of them at once cost the registers of a second workgroup
+                if constexpr (ROWWISE) __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
@@ -233,6 +316,7 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
     }
 
     // add the wavefronts' partial T in a fixed order
+    if constexpr (ROWWISE) __syncthreads();          // the sums reuse the tiles' memory: every wavefront is done with its tile
 #pragma unroll
     for (int g = 0; g < MAXG; ++g)
         *reinterpret_cast<f32x4*>(&red[wave][g][lane][0]) = acc[g];
@@ -269,6 +353,17 @@ __global__ __launch_bounds__(64 * kPrepWaves) void prep_kernel(PrepArgs a) {
             if (orow < a.M) a.Xh[orow * a.ldxh + a.KT * kTileK + 2 * a.kp + item % pad] = 0;
         }
     }
+}
+
+template <int SRC, bool FINAL, int MAXG, bool CELLS>
+static void launch_prep_t(dim3 grid, dim3 block, hipStream_t s, const PrepArgs& a, bool rowwise) {
+    if constexpr (SRC == 0 && !CELLS) {
+        if (rowwise) {
+            hipLaunchKernelGGL((prep_kernel<SRC, FINAL, MAXG, CELLS, true>), grid, block, 0, s, a);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((prep_kernel<SRC, FINAL, MAXG, CELLS, false>), grid, block, 0, s, a);
 }
 
 int prep_slices(const Layer& L, int64_t M, int path) {
@@ -329,7 +424,9 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     const bool fin = (ws.Tpart == nullptr);          // T final (hi/lo behind the row) or partial sums
     if (cells && fin && L.kp > 0) return hipErrorInvalidValue;
     if (a.groups_per_wg > 4) return hipErrorInvalidValue;
-#define LQER_PREP(FC, FN, MG, CL) hipLaunchKernelGGL((prep_kernel<FC, FN, MG, CL>), grid, block, 0, s, a)
+    // the row-wise form for fp32 input in row-major layout when the launch has workgroups to spare
+    const bool rowwise = !cells && src == 0 && (int64_t)grid.x * ws.S * gz >= 2048;
+#define LQER_PREP(FC, FN, MG, CL) launch_prep_t<FC, FN, MG, CL>(grid, block, s, a, rowwise)
 #define LQER_PREP_G(FC, FN, CL) do { if (a.groups_per_wg <= 1) LQER_PREP(FC, FN, 1, CL); else LQER_PREP(FC, FN, 4, CL); } while (0)
 #define LQER_PREP_C(FN, CL) do { if (src == 1) LQER_PREP_G(1, FN, CL); else LQER_PREP_G(0, FN, CL); } while (0)
     if (cells) LQER_PREP_C(false, true);

@@ -277,6 +277,26 @@ def test_six_bit_activations(M, K, N, k):
     h.free()
 
 
+@pytest.mark.parametrize("M,K,N,k,bits", [(33000, 272, 64, 33, 8), (32776, 528, 40, 0, 8), (40000, 1040, 112, 100, 6)])
+def test_many_tokens_ragged_rows_and_columns(M, K, N, k, bits):
+    # launches of 2048 workgroups and more take the row-wise form of the projection kernel (whole rows per wavefront,
+    # block maxima across the four lanes of a quad, operands turned through LDS): ragged last row group, K that ends
+    # inside a 256-wide tile, ranks in more than four groups, 6-bit activations; the whole output against the oracle
+    import torch
+    from paper_2402_02446_amd import binding
+    layer, ch = oracle_layer_small(K, N, k, seed=M)
+    h = upload(layer)
+    if bits == 6:
+        h.set_activation_bits(6)
+    X = synth.gen_activations(np.random.default_rng(M), M, K, ch, 30.0)
+    Xd = torch.from_numpy(X).cuda()
+    Y = binding.lqer_linear_forward(h, Xd)
+    assert_forward_matches(Y.cpu().numpy(), X, layer, act_bits=bits)
+    Xc, Xe = binding.lqer_quantize_mx(Xd, bits)
+    assert torch.equal(binding.lqer_linear_forward_q(h, Xc, Xe), Y)           # the lane-per-block form gives the same bits
+    h.free()
+
+
 @pytest.mark.parametrize("M,K,N,k,path,variant", [
     (1, 1024, 272, 32, 1, 11181), (16, 4096, 64, 16, 1, 11181), (20, 2304, 528, 33, 1, 11241), (5, 1024, 4096, 8, 1, 12241),
     (40, 512, 16384, 8, 1, 11421), (300, 1024, 528, 64, 2, 111), (300, 1024, 528, 64, 2, 112), (513, 4352, 1104, 16, 2, 211),
