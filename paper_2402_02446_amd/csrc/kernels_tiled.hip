@@ -544,7 +544,7 @@ static const TileShape kShapes[] = {
     {11, 128, 512, 1, 1372.0, 1372.0, 1372.0}, {12, 128, 256, 2, 1300.0, 1000.0, 1150.0}, {4, 128, 128, 2, 1058.0, 800.0, 1058.0},
 };
 constexpr double kPieceUs = 4.0;       // filling the pipeline and storing the tile, per piece
-constexpr double kSplitFixedUs = 30.0; // what a split launch was measured to take beyond this, per workgroup sharing a compute unit: the
+constexpr double kSplitFixedUs = 38.0; // what a split launch was measured to take beyond this, per workgroup sharing a compute unit: the
                                        // pieces' drain and refill, not the slots' way through memory (the time is the same without them)
 
 struct Split { int64_t grid, dp_tiles, sk_units, sk_share, sk_tile_units; bool aligned; };
