@@ -609,7 +609,8 @@ def pmc_probe(rng, which):
     WRITE_SIZE in the same run.  `headline` / `cfg4_prefill`: the 70B-shaped layer at M = 4096;
     `cfg4_decode`: the same layer at M = 16 on a ring of device copies; `cfg2_decode`: the 7B-shaped
     q_proj at M = 16 on its ring; `cfg3`: the two 7B-shaped MLP layers at M = 2048; `cfg5_prep`: the 7B block's
-    4096- and 11008-wide linears at M = 65536 (projection kernel and main kernel)."""
+    4096- and 11008-wide linears at M = 65536 (projection kernel and main kernel); `int_prefill`: the INT variant's
+    three kernels on a 4096 x 4096 layer at 16384 tokens."""
     import torch
     from paper_2402_02446_amd import binding, synth
     if which == "build":
@@ -629,6 +630,17 @@ def pmc_probe(rng, which):
         "cfg3": [(2048, 4096, 11008, 32, 0, 10), (2048, 11008, 4096, 32, 0, 10)],
         "cfg5_prep": [(65536, 4096, 4096, 32, 0, 4), (65536, 11008, 4096, 32, 0, 4)],
     }
+    if which == "int_prefill":
+        # the scaled-integer variant: 4096 x 4096, k = 32 at 16384 tokens (quantizer, projection, main product)
+        d = synth.random_int_layer(rng, 4096, 4096, 32)
+        layer = binding.lqer_int_layer_import(4096, 4096, 32, d["Wc"], d["Ws"], d["Ac"], d["As"], d["Bc"], d["Bs"])
+        X = torch.randn((16384, 4096), device="cuda", dtype=torch.float32)
+        Y = torch.empty((16384, 4096), dtype=torch.float32, device="cuda")
+        for _ in range(4):
+            binding.lqer_linear_forward(layer, X, Y=Y)
+        torch.cuda.synchronize()
+        print("pmc-probe int_prefill done")
+        return
     for (M, K, N, k, ring, reps) in plans[which]:
         layers, _ = make_ring(rng, K, N, k, ring)
         if M >= 65536:
@@ -669,7 +681,7 @@ def main():
     ap.add_argument("--cases", default="all", choices=["headline", "all"],
                     help="headline: the 70B-shaped layer at M = 4096 only; all (default): every workload")
     ap.add_argument("--pmc-probe", nargs="?", const="headline", default=None,
-                    choices=["headline", "cfg4_decode", "cfg4_prefill", "cfg2_decode", "cfg3", "cfg5_prep", "build"],
+                    choices=["headline", "cfg4_decode", "cfg4_prefill", "cfg2_decode", "cfg3", "cfg5_prep", "int_prefill", "build"],
                     help="run one workload a few times and exit, for rocprofv3 runs (each after plain 1 GiB "
                          "copies that calibrate the byte counters; build: the offline step per layer shape "
                          "of cfg5, host and device path, timings printed as JSON)")
