@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
     // activation loader: thread -> four 16-byte cells of a 128 x 128 byte tile
     const int ld_row = tid >> 3, ld_cell = tid & 7;
     const int8_t* ld_src = a.Xc + (m0 + ld_row) * a.ldxc + ld_cell * 16;
-    const int ld_dst = ld_row * 128 + ((ld_cell ^ (ld_row & 7)) << 4);          // rows 32 apart share the swizzle term
+    const int ld_dst = ld_row * 128 + ((ld_cell ^ ((ld_row >> 1) & 7)) << 4);   // rows 32 apart share the swizzle term
     auto fetch_x = [&](u32x4 (&st)[4], int64_t g) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) st[j] = *reinterpret_cast<const u32x4*>(ld_src + (int64_t)j * 32 * a.ldxc + g * 128);
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
     const int rd_row = wr * 64 + t;
     auto read_x = [&](int buf, int tm, int sp, int p) {
         const int row = rd_row + tm * 32;
-        const int cell = (4 * sp + 2 * hh + p) ^ (row & 7);
+        const int cell = (4 * sp + 2 * hh + p) ^ ((row >> 1) & 7);   // rows are 128 B = half of the banks: 16 rows of a read hit 16 different bank groups
         return *reinterpret_cast<const i32x4*>(&xs[buf][row * 128 + (cell << 4)]);
     };
 
