@@ -28,6 +28,7 @@ struct PrepArgs {
     int tiles_per_slice;
     int kp, kp16;
     int groups_per_wg;     // rank groups one plane of grid.z computes: at most 4 (the last plane may have fewer)
+    int g_first;           // first rank group of plane 0
     const uint8_t* At;
     uint16_t* Xh; int64_t ldxh;
     int64_t tail_cols;     // columns behind K_pad in Xh (T_hi | T_lo | zero padding)
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(64 * kPrepWaves, RW ? 4 : 1) void prep_kernel(PrepA
     const int64_t row = (int64_t)blockIdx.x * 16 + t;
     const bool row_ok = row < a.M;
     const int slice = blockIdx.y;
-    const int g0 = blockIdx.z * a.groups_per_wg;
+    const int g0 = a.g_first + blockIdx.z * a.groups_per_wg;
     const int ng = (a.kp16 - g0 < a.groups_per_wg) ? a.kp16 - g0 : a.groups_per_wg;   // rank groups of this plane
     const bool store_x = (blockIdx.z == 0) && SRC != 2;
     const int64_t nblk = a.K / 16;
@@ -398,9 +399,12 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     // rows again; 1 us less on the 70B-shaped layer.
     int gz = 1;
     if (ws.cells && L.kp16 > 1) { gz = L.kp16; a.groups_per_wg = 1; }
-    // more than four rank groups (ranks above 64): planes of four groups, each quantizing its rows again
-    // (only the first plane stores them)
-    else if (L.kp16 > 4) { gz = (L.kp16 + 3) / 4; a.groups_per_wg = 4; }
+    // More than four rank groups (ranks above 64), row-major layout: this launch does the first four; the others
+    // follow in a second launch that reads the bf16 activations this one stores (half the bytes, nothing to
+    // quantize), in planes of four groups.  (An input that is already the stored matrix takes planes at once.)
+    const bool two_launches = !ws.cells && L.kp16 > 4 && !reuse_xh;
+    if (!ws.cells && L.kp16 > 4) { gz = reuse_xh ? (L.kp16 + 3) / 4 : 1; a.groups_per_wg = 4; }
+    a.g_first = 0;
     a.At = L.At; a.Xh = ws.Xh; a.ldxh = ws.ldxh;
     a.tail_cols = ws.ldxh - L.KT * kTileK;
     a.Tpart = ws.Tpart;
@@ -433,6 +437,14 @@ hipError_t launch_prep(const Layer& L, const float* X, int64_t ldx, const int8_t
     else if (src == 2) { if (fin) LQER_PREP_G(2, true, false); else LQER_PREP_G(2, false, false); }
     else if (fin) LQER_PREP_C(true, false);
     else LQER_PREP_C(false, false);
+    if (two_launches) {
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        a.g_first = 4;
+        grid.z = (unsigned)((L.kp16 - 4 + 3) / 4);
+        grid.y = (unsigned)ws.S;
+        if (fin) LQER_PREP_G(2, true, false); else LQER_PREP_G(2, false, false);
+    }
 #undef LQER_PREP_C
 #undef LQER_PREP_G
 #undef LQER_PREP
