@@ -55,3 +55,34 @@ def test_static_scratch_refuses_sizes_beyond_it():
     Y = binding.lqer_linear_forward_static(h, X[:0])           # no tokens: nothing to do
     assert Y.shape == (0, 64)
     h.free()
+
+
+def test_static_scratch_under_graph_capture():
+    # the callers the entry point is for: after one call outside any capture (which looks up the scratch's address),
+    # the call is captured in a HIP graph and every replay - with eager work and synchronisations in between -
+    # reproduces the eager result
+    import torch
+    from paper_2402_02446_amd import binding
+    layer, ch = oracle_layer_big(1024, 528, 24, seed=33)
+    h = upload(layer)
+    for M in (7, 200):
+        X = torch.from_numpy(synth.gen_activations(np.random.default_rng(M), M, 1024, ch, 50.0)).cuda()
+        X2 = torch.from_numpy(synth.gen_activations(np.random.default_rng(M + 1), M, 1024, ch, 50.0)).cuda()
+        want = binding.lqer_linear_forward_static(h, X).clone()
+        want2 = binding.lqer_linear_forward_static(h, X2).clone()
+        torch.cuda.synchronize()
+        Xg, Yg = X.clone(), torch.empty_like(want)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            binding.lqer_linear_forward_static(h, Xg, Y=Yg)
+        for rep, (src, w) in enumerate([(X, want), (X2, want2), (X, want)]):
+            Xg.copy_(src)
+            Yg.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(Yg, w), f"replay {rep} differs (M={M})"
+            _ = binding.lqer_linear_forward_static(h, X2)          # eager work on the same scratch between replays
+            torch.cuda.synchronize()
+        del g
+    h.free()
