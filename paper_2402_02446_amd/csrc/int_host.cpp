@@ -27,8 +27,11 @@ struct IntGemmArgs {
     int S; int64_t t_stride;
     const uint8_t* Bt; const float* Bsc;
     int kp16;
+    int tail_plane;
 };
 hipError_t launch_int_gemm(bool projection, const IntGemmArgs& a, hipStream_t s);
+hipError_t launch_int_reduce_planes(const float* P, int planes, int64_t plane_stride, int64_t M, int64_t N, int64_t ldp,
+                                    float* Y, int64_t ldy, hipStream_t s);
 
 static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 
@@ -77,19 +80,35 @@ static int upload_floats(const std::vector<float>& host, float** dev) {
 static inline int perm_pos(int e) { return (e & ~31) + ((e & 1) << 4) + ((e & 31) >> 1); }
 
 // K planes of the projection: it has few output columns, so with few token tiles its K groups are spread over
-// workgroups (each keeps at least four groups); the main kernel adds the planes' partial T in plane order.
+// workgroups (each keeps at least two groups: a workgroup's groups are a chain of dependent memory round trips, which
+// is what a few-token call waits for); the main kernel adds the planes' partial T in plane order.
 static int projection_planes(const Layer& L, int64_t M) {
     const int64_t tiles = (M + 127) / 128, G = L.K / 128;
     int64_t s = 1;
-    while (tiles * s < 256 && s < 8 && G / (2 * s) >= 4) s *= 2;
+    while (tiles * s < 256 && s < 16 && G / (2 * s) >= 2) s *= 2;
     return (int)s;
+}
+
+// K planes of the main product: with few output tiles (few tokens) its K groups are spread over workgroups as well,
+// each plane leaving partial sums of Y in the workspace for a small kernel to add up; the rank-k correction then gets a
+// plane of its own.  Two workgroups fit a compute unit: the fewest groups per plane (at least two) that keep the launch
+// within 512 workgroups.
+static int main_planes(const Layer& L, int64_t M) {
+    const int64_t tiles = ((M + 127) / 128) * ((L.N + 127) / 128), G = L.K / 128, cap = 512;
+    const int64_t extra = L.kp > 0 ? 1 : 0;
+    if (tiles * (2 + extra) > cap) return 1;
+    int64_t g = 2;                                     // K groups per plane
+    while (g < G && tiles * ((G + g - 1) / g + extra) > cap) ++g;
+    return (int)((G + g - 1) / g);
 }
 
 size_t int_workspace_bytes(const Layer& L, int64_t M) {
     if (M <= 0) return 0;
     const int64_t mp = round_up(M, 128);
+    const int sm = main_planes(L, M);
     return (size_t)(round_up(mp * L.K, 256) + round_up(mp * 4, 256) +
-                    (int64_t)projection_planes(L, M) * mp * (int64_t)L.kp32 * 32 * 4);
+                    round_up((int64_t)projection_planes(L, M) * mp * (int64_t)L.kp32 * 32 * 4, 256) +
+                    (sm > 1 ? (int64_t)(sm + 1) * mp * round_up(L.N, 4) * 4 : 0));
 }
 
 int forward_int(const Layer& L, const float* X, int64_t ldx, int64_t M, float* Y, int64_t ldy, void* ws, size_t ws_bytes,
@@ -105,16 +124,31 @@ int forward_int(const Layer& L, const float* X, int64_t ldx, int64_t M, float* Y
     a.Xc = Xc; a.ldxc = L.K; a.Xs = Xs; a.G = L.K / 128; a.M = M;
     const int S = projection_planes(L, M);
     a.T = nullptr; a.ldt = ldt; a.Bt = nullptr; a.Bsc = nullptr; a.kp16 = 0;
-    a.S = S; a.t_stride = mp * ldt;
+    a.S = S; a.t_stride = mp * ldt; a.tail_plane = 0;
     if (L.kp > 0) {
         a.Wt = L.At; a.Wsc = L.Asc; a.N = ldt; a.N32 = L.kp32; a.Out = T; a.ldo = ldt;
         a.g_per_z = (a.G + S - 1) / S; a.out_z_stride = mp * ldt;
         if (launch_int_gemm(true, a, s) != hipSuccess) return LQER_ERR_HIP;
-        a.S = (int)((a.G + a.g_per_z - 1) / a.g_per_z);         // planes that exist
+        const int planes = (int)((a.G + a.g_per_z - 1) / a.g_per_z);
+        // the planes' partial T are added up (in plane order, into the first) before the main kernel reads them: inside
+        // it that sum would be a chain of dependent loads in front of every rank block
+        if (planes > 1 && launch_int_reduce_planes(T, planes, mp * ldt, mp, ldt, ldt, T, ldt, s) != hipSuccess) return LQER_ERR_HIP;
+        a.S = 1;
     }
     a.Wt = L.Wt; a.Wsc = L.Wsc; a.N = L.N; a.N32 = L.N32; a.Out = Y; a.ldo = ldy;
     a.g_per_z = a.G; a.out_z_stride = 0;
     a.T = T; a.Bt = L.Bt; a.Bsc = L.Bsc; a.kp16 = L.kp16;
+    const int sm = main_planes(L, M);
+    if (sm > 1) {
+        float* P = (float*)((uint8_t*)T + round_up((int64_t)S * mp * ldt * 4, 256));
+        const int64_t ldp = round_up(L.N, 4);
+        a.Out = P; a.ldo = ldp; a.g_per_z = (a.G + sm - 1) / sm; a.out_z_stride = mp * ldp;
+        a.tail_plane = L.kp > 0 ? 1 : 0;
+        if (launch_int_gemm(false, a, s) != hipSuccess) return LQER_ERR_HIP;
+        const int planes = (int)((a.G + a.g_per_z - 1) / a.g_per_z) + a.tail_plane;
+        if (launch_int_reduce_planes(P, planes, mp * ldp, M, L.N, ldp, Y, ldy, s) != hipSuccess) return LQER_ERR_HIP;
+        return LQER_OK;
+    }
     if (launch_int_gemm(false, a, s) != hipSuccess) return LQER_ERR_HIP;
     return LQER_OK;
 }

@@ -99,6 +99,7 @@ struct IntGemmArgs {
     int S; int64_t t_stride;
     const uint8_t* Bt; const float* Bsc; // B_k records [N32][kp16][kBRecordBytes], scales [N32 * 32]
     int kp16;
+    int tail_plane;                      // 1: grid.z has one more plane than K planes, which computes only the correction
 };
 
 template <int WB, bool TAIL>
@@ -156,9 +157,14 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
 
+    float st[TM];                                    // token scales (for the epilogue; asked for here, ahead of the loop)
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) st[tm] = a.Xs[m0 + wr * 64 + tm * 32 + t];
+
     // this workgroup's K groups [gb, ge)
-    const int64_t gb = (int64_t)blockIdx.z * a.g_per_z;
-    const int64_t ge = gb + a.g_per_z < a.G ? gb + a.g_per_z : a.G;
+    const bool tail_only = TAIL && a.tail_plane && blockIdx.z + 1 == gridDim.z;    // (its range is empty: acc stays zero)
+    const int64_t gb = tail_only ? 0 : (int64_t)blockIdx.z * a.g_per_z;
+    const int64_t ge = tail_only ? 0 : (gb + a.g_per_z < a.G ? gb + a.g_per_z : a.G);
     WSet w0, w1;
     u32x4 stx[4];
     fetch_x(stx, gb);
@@ -225,9 +231,6 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
     }
 
     // ---- epilogue: token scale, rank-k correction, store ----------------------------------------------------------
-    float st[TM];
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) st[tm] = a.Xs[m0 + wr * 64 + tm * 32 + t];
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -235,7 +238,7 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tm][tn][r] *= st[tm];
     if constexpr (TAIL) {
-        if (a.kp16 > 0) {
+        if (a.kp16 > 0 && (a.tail_plane ? tail_only : blockIdx.z == 0)) {
             f32x16 ta[TM][TN];
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
@@ -258,11 +261,20 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
                 for (int tm = 0; tm < TM; ++tm) {
                     const float* src = a.T + (m0 + wr * 64 + tm * 32 + t) * a.ldt + rb * 16 + 8 * hh;
                     f32x4 p0 = *reinterpret_cast<const f32x4*>(src), p1 = *reinterpret_cast<const f32x4*>(src + 4);
-                    for (int z = 1; z < a.S; ++z) {                      // the projection's K planes, in plane order
-                        const f32x4 q0 = *reinterpret_cast<const f32x4*>(src + z * a.t_stride);
-                        const f32x4 q1 = *reinterpret_cast<const f32x4*>(src + z * a.t_stride + 4);
-                        p0 += q0;
-                        p1 += q1;
+                    for (int z0 = 1; z0 < a.S; z0 += 8) {                // the projection's K planes, in plane order;
+                        f32x4 q[8][2];                                   // eight planes' loads in flight at a time
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const int z = z0 + j < a.S ? z0 + j : a.S - 1;
+                            q[j][0] = *reinterpret_cast<const f32x4*>(src + z * a.t_stride);
+                            q[j][1] = *reinterpret_cast<const f32x4*>(src + z * a.t_stride + 4);
+                        }
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            if (z0 + j < a.S) {
+                                p0 += q[j][0];
+                                p1 += q[j][1];
+                            }
                     }
                     const float v[8] = {p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
                     Frag hi, lo;
@@ -324,10 +336,44 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
     }
 }
 
+// Few-token calls split the K groups of the projection and of the main product over planes of workgroups, each leaving
+// its share of T or Y in the workspace; this adds the planes in plane order (the same bits on every run).
+// Y may be the first plane itself (a thread reads all of its elements before it writes them).
+__global__ __launch_bounds__(256) void int_reduce_planes_kernel(const float* P, int planes, int64_t plane_stride,
+                                                                int64_t M, int64_t N, int64_t ldp, float* Y, int64_t ldy) {
+    const int64_t n4 = (N + 3) / 4;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M * n4) return;
+    const int64_t r = i / n4, c = 4 * (i - r * n4);
+    const float* src = P + r * ldp + c;
+    f32x4 v = *reinterpret_cast<const f32x4*>(src);
+    for (int z0 = 1; z0 < planes; z0 += 8) {         // eight loads in flight, added in plane order
+        f32x4 q[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) q[j] = *reinterpret_cast<const f32x4*>(src + (z0 + j < planes ? z0 + j : planes - 1) * plane_stride);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (z0 + j < planes) v += q[j];
+    }
+    float* dst = Y + r * ldy + c;
+    if (c + 3 < N) {
+        *reinterpret_cast<f32x4*>(dst) = v;
+    } else {
+        for (int j = 0; c + j < N; ++j) dst[j] = v[j];
+    }
+}
+
+hipError_t launch_int_reduce_planes(const float* P, int planes, int64_t plane_stride, int64_t M, int64_t N, int64_t ldp,
+                                    float* Y, int64_t ldy, hipStream_t s) {
+    const int64_t items = M * ((N + 3) / 4);
+    hipLaunchKernelGGL(int_reduce_planes_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, s, P, planes, plane_stride, M, N, ldp, Y, ldy);
+    return hipGetLastError();
+}
+
 // Projection T = X_q A_k (Out = T, N = padded rank) or main product with the correction.
 hipError_t launch_int_gemm(bool projection, const IntGemmArgs& a, hipStream_t s) {
     if (a.M == 0) return hipSuccess;
-    const unsigned planes = (unsigned)((a.G + a.g_per_z - 1) / a.g_per_z);
+    const unsigned planes = (unsigned)((a.G + a.g_per_z - 1) / a.g_per_z) + (projection ? 0u : (unsigned)a.tail_plane);
     const dim3 grid((unsigned)((a.N + 127) / 128), (unsigned)((a.M + 127) / 128), planes), block(256);
     if (projection) hipLaunchKernelGGL((int_gemm_kernel<8, false>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((int_gemm_kernel<4, true>), grid, block, 0, s, a);

@@ -174,7 +174,27 @@ def test_offline_step(K, N, k, mode):
     h.free()
 
 
-@pytest.mark.parametrize("K,N,k,M", [(4096, 4096, 32, 16), (4096, 11008, 32, 2048), (11008, 4096, 32, 2048)])
+@pytest.mark.parametrize("K,N,k,M", [(1024, 272, 64, 5), (2304, 528, 33, 100), (4096, 640, 128, 16), (4096, 1100, 0, 129)])
+def test_few_tokens_split_over_k_same_bits_every_run(K, N, k, M):
+    # with few output tiles the projection and the main product split K over planes of workgroups that a small kernel adds
+    # in plane order: the result has the same bits on every run, also through the static-scratch entry
+    import torch
+    from paper_2402_02446_amd import binding
+    layer, ch = _standin_layer(K, N, k, seed=3 * K + N)
+    h = _upload(layer)
+    X = torch.from_numpy(synth.gen_activations(np.random.default_rng(K + M), M, K, ch, 40.0)).cuda()
+    Y0 = binding.lqer_linear_forward(h, X)
+    _check(Y0.cpu().numpy(), X.cpu().numpy(), layer)
+    for _ in range(3):
+        assert torch.equal(binding.lqer_linear_forward(h, X), Y0)
+    Ys = torch.full_like(Y0, float("nan"))
+    binding.lqer_linear_forward_static(h, X, Y=Ys)
+    assert torch.equal(Ys, Y0)
+    h.free()
+
+
+@pytest.mark.parametrize("K,N,k,M", [(4096, 4096, 32, 16), (4096, 11008, 32, 16), (11008, 4096, 32, 16),
+                                     (4096, 11008, 32, 2048), (11008, 4096, 32, 2048)])
 def test_7b_shaped_layers_every_tile(K, N, k, M):
     # the LLaMA-7B-shaped layers with Table 2's k = 32, decode and prefill: every token row (M = 16) or one of every band
     # of 32 against one column of every group of 32 - every output tile, wavefront part and MFMA tile is touched
