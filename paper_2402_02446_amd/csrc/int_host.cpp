@@ -108,7 +108,7 @@ size_t int_workspace_bytes(const Layer& L, int64_t M) {
     const int sm = main_planes(L, M);
     return (size_t)(round_up(mp * L.K, 256) + round_up(mp * 4, 256) +
                     round_up((int64_t)projection_planes(L, M) * mp * (int64_t)L.kp32 * 32 * 4, 256) +
-                    (sm > 1 ? (int64_t)(sm + 1) * mp * round_up(L.N, 4) * 4 : 0));
+                    (sm > 1 ? (int64_t)(sm + 1) * M * round_up(L.N, 4) * 4 : 0));       // (the planes of Y hold the M real rows only)
 }
 
 int forward_int(const Layer& L, const float* X, int64_t ldx, int64_t M, float* Y, int64_t ldy, void* ws, size_t ws_bytes,
@@ -142,11 +142,11 @@ int forward_int(const Layer& L, const float* X, int64_t ldx, int64_t M, float* Y
     if (sm > 1) {
         float* P = (float*)((uint8_t*)T + round_up((int64_t)S * mp * ldt * 4, 256));
         const int64_t ldp = round_up(L.N, 4);
-        a.Out = P; a.ldo = ldp; a.g_per_z = (a.G + sm - 1) / sm; a.out_z_stride = mp * ldp;
+        a.Out = P; a.ldo = ldp; a.g_per_z = (a.G + sm - 1) / sm; a.out_z_stride = M * ldp;
         a.tail_plane = L.kp > 0 ? 1 : 0;
         if (launch_int_gemm(false, a, s) != hipSuccess) return LQER_ERR_HIP;
         const int planes = (int)((a.G + a.g_per_z - 1) / a.g_per_z) + a.tail_plane;
-        if (launch_int_reduce_planes(P, planes, mp * ldp, M, L.N, ldp, Y, ldy, s) != hipSuccess) return LQER_ERR_HIP;
+        if (launch_int_reduce_planes(P, planes, M * ldp, M, L.N, ldp, Y, ldy, s) != hipSuccess) return LQER_ERR_HIP;
         return LQER_OK;
     }
     if (launch_int_gemm(false, a, s) != hipSuccess) return LQER_ERR_HIP;
