@@ -7,8 +7,8 @@
 //
 //   quant_token_kernel   per-token INT8 quantizer (one workgroup per token row: row maximum, then codes)
 //   int_gemm_kernel      128 tokens x 128 columns per workgroup, four wavefronts of 64 x 64; one K group per step:
-//                        activation codes through a double-buffered, XOR-swizzled LDS tile, packed weights straight
-//                        into registers one group ahead.  <4, true>: the main product with the rank-k correction
+//                        activation codes and the group's 128 scales through double-buffered LDS (the tile XOR-swizzled),
+//                        packed weights straight into registers, all asked for one group ahead at the top of the step.  <4, true>: the main product with the rank-k correction
 //                        (T_hi | T_lo against B_k's codes on the bf16 matrix cores, one scale per column) in the
 //                        epilogue; <8, false>: the projection T = X_q A_k, A_k as 8-bit "weights".
 //
@@ -108,6 +108,7 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
     constexpr int NL = (WB == 4) ? 2 : 4;            // 16-byte loads per lane, column group and K group
     constexpr int REC = NL * 1024;
     __shared__ __attribute__((aligned(1024))) uint8_t xs[2][128 * 128];
+    __shared__ __attribute__((aligned(16))) float ss[2][128];      // the K group's scales of the tile's 128 columns
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -116,21 +117,25 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
     const int t = lane & 31, hh = lane >> 5;
     const int64_t m0 = (int64_t)blockIdx.y * 128;
     const int64_t g0 = ((int64_t)blockIdx.x * 2 + wc) * TN;        // first column group of this wavefront
-    auto group_of = [&](int tn) {
-        const int64_t g = g0 + tn;
-        return g < a.N32 ? g : a.N32 - 1;                          // clamp; the store is masked
-    };
+    auto clamp_group = [&](int64_t g) { return g < a.N32 ? g : a.N32 - 1; };   // (the store is masked)
+    auto group_of = [&](int tn) { return clamp_group(g0 + tn); };
     // activation loader: thread -> four 16-byte cells of a 128 x 128 byte tile
     const int ld_row = tid >> 3, ld_cell = tid & 7;
     const int8_t* ld_src = a.Xc + (m0 + ld_row) * a.ldxc + ld_cell * 16;
     const int ld_dst = ld_row * 128 + ((ld_cell ^ ((ld_row >> 1) & 7)) << 4);   // rows 32 apart share the swizzle term
-    auto fetch_x = [&](u32x4 (&st)[4], int64_t g) {
+    // scale loader: the first 32 threads bring the 4 x 32 scales of the tile's column groups (four floats each)
+    const float* sc_src = a.Wsc + clamp_group((int64_t)blockIdx.x * 4 + ((tid >> 3) & 3)) * a.G * 32 + (tid & 7) * 4;
+    const int sc_dst = ((tid >> 3) & 3) * 32 + (tid & 7) * 4;
+    struct XStage { u32x4 x[4]; f32x4 s; };
+    auto fetch_x = [&](XStage& st, int64_t g) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) st[j] = *reinterpret_cast<const u32x4*>(ld_src + (int64_t)j * 32 * a.ldxc + g * 128);
+        for (int j = 0; j < 4; ++j) st.x[j] = *reinterpret_cast<const u32x4*>(ld_src + (int64_t)j * 32 * a.ldxc + g * 128);
+        st.s = *reinterpret_cast<const f32x4*>(sc_src + g * 32);     // (every thread: the wavefronts beyond the first ask for the same lines again)
     };
-    auto store_x = [&](const u32x4 (&st)[4], int buf) {
+    auto store_x = [&](const XStage& st, int buf) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4*>(&xs[buf][ld_dst + j * 32 * 128]) = st[j];
+        for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4*>(&xs[buf][ld_dst + j * 32 * 128]) = st.x[j];
+        if (tid < 32) *reinterpret_cast<f32x4*>(&ss[buf][sc_dst]) = st.s;
     };
     struct WSet { u32x4 c[TN][NL]; };
     auto load_w = [&](WSet& w, int64_t g) {
@@ -166,35 +171,33 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
     const int64_t gb = tail_only ? 0 : (int64_t)blockIdx.z * a.g_per_z;
     const int64_t ge = tail_only ? 0 : (gb + a.g_per_z < a.G ? gb + a.g_per_z : a.G);
     WSet w0, w1;
-    u32x4 stx[4];
+    XStage stx;
     fetch_x(stx, gb);
     load_w(w0, gb);
     store_x(stx, 0);
 
+    // One K group.  The next group's activations, scales and weights are asked for first and stay in flight through the
+    // step (they land in LDS / become `cur` at its end); the column groups are worked one after the other, so that the
+    // conversion and scaling of one's sums can run beside the MFMAs of the other.
     auto step = [&](const WSet& cur, WSet& nxt, int64_t g) {
         __syncthreads();                             // tile g is complete; the other buffer is free again
         const int buf = (int)((g - gb) & 1);
         const int64_t gn = g + 1 < ge ? g + 1 : g;   // clamped: loads stay unconditional
         fetch_x(stx, gn);
         load_w(nxt, gn);
-        // this group's scales: needed only after its MFMAs, which hide the round trip
-        f32x4 sc[TN][4];
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
-            const float* s = a.Wsc + (group_of(tn) * a.G + g) * 32 + 4 * hh;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) sc[tn][q] = *reinterpret_cast<const f32x4*>(s + 8 * q);
-        }
-        i32x16 ia[TM][TN];
+        __builtin_amdgcn_sched_barrier(0);           // (not to be sunk towards their uses: that would put the round trip on the step's path)
+        i32x4 xb[2][2][TM];
 #pragma unroll
         for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                i32x4 xb[TM];
+            for (int p = 0; p < 2; ++p)
 #pragma unroll
-                for (int tm = 0; tm < TM; ++tm) xb[tm] = read_x(buf, tm, sp, p);
+                for (int tm = 0; tm < TM; ++tm) xb[sp][p][tm] = read_x(buf, tm, sp, p);
+        auto products = [&](i32x16 (&ia)[TM], int tn) {
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn) {
+            for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+                for (int p = 0; p < 2; ++p) {
                     i32x4 wv;
                     if constexpr (WB == 4) {
                         const u32x4 c = cur.c[tn][sp];
@@ -209,20 +212,37 @@ __global__ __launch_bounds__(256, 2) void int_gemm_kernel(IntGemmArgs a) {
                             i32x16 z;
 #pragma unroll
                             for (int r = 0; r < 16; ++r) z[r] = 0;
-                            ia[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv, xb[tm], z, 0, 0, 0);
+                            ia[tm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv, xb[sp][p][tm], z, 0, 0, 0);
                         } else {
-                            ia[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv, xb[tm], ia[tm][tn], 0, 0, 0);
+                            ia[tm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv, xb[sp][p][tm], ia[tm], 0, 0, 0);
                         }
                     }
                 }
-            }
+        };
         // the group's exact integer sums, scaled once: register r of a lane is column 8 (r / 4) + 4 hh + r % 4
+        auto fold = [&](const i32x16 (&ia)[TM], int tn) {
+            f32x4 sc[4];
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
+            for (int q = 0; q < 4; ++q) sc[q] = *reinterpret_cast<const f32x4*>(&ss[buf][(wc * 2 + tn) * 32 + 8 * q + 4 * hh]);
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
+            for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[tm][tn][r] += (float)ia[tm][tn][r] * sc[tn][r >> 2][r & 3];
+                for (int r = 0; r < 16; ++r) acc[tm][tn][r] += (float)ia[tm][r] * sc[r >> 2][r & 3];
+        };
+        // (the empty asm statements keep the arithmetic where it is written: nothing else orders pure instructions
+        // against the scheduling barriers, and left alone they all sink to the end of the step)
+        i32x16 ia0[TM], ia1[TM];
+        products(ia0, 0);
+        asm volatile("" : "+v"(ia0[0]), "+v"(ia0[1]));
+        __builtin_amdgcn_sched_barrier(0);
+        // the second column group's MFMAs run while the first one's sums are converted and scaled
+        products(ia1, 1);
+        fold(ia0, 0);
+        asm volatile("" : "+v"(ia1[0]), "+v"(ia1[1]), "+v"(acc[0][0]), "+v"(acc[1][0]));
+        __builtin_amdgcn_sched_barrier(0);
+        fold(ia1, 1);
+        asm volatile("" : "+v"(acc[0][1]), "+v"(acc[1][1]));
+        __builtin_amdgcn_sched_barrier(0);
         store_x(stx, buf ^ 1);                       // last read two barriers ago (a clamped re-write of the last tile is harmless)
     };
     for (int64_t g = gb; g < ge; g += 2) {
