@@ -729,11 +729,21 @@ hipError_t launch_tiled(const Layer& L, int64_t M, const Workspace& ws, float* Y
     if (variant == 0) {
         // pick the tile shape (and the split) with the lowest estimated time
         double best = 0.0;
-        for (const TileShape& sh : kShapes) {
+        for (const TileShape& entry : kShapes) {
+            TileShape sh = entry;
+            int64_t KT = L.KT;
+            if (L.w_bits == 2) {
+                // the 2-bit instances against the table's 4-bit rates, and the correction's extra K columns, which at the
+                // ranks such layers come with are no longer small (measured on 4096 x 4096 at 2048 tokens and rank 256:
+                // 128 x 512 cut along K 103 us, 128 x 256 114 us, 128 x 128 113 us)
+                const double f = sh.id == 11 ? 0.85 : 0.7;
+                sh.pair *= f; sh.single *= f; sh.cut *= f;
+                KT += (2 * L.kp + kTileK - 1) / kTileK;
+            }
             const int64_t tiles = ((M + sh.bm - 1) / sh.bm) * ((L.N + sh.bn - 1) / sh.bn);
-            double t = time_whole(sh, tiles, L.KT, cus);
-            if (mode >= 2 && ws.Part != nullptr) t = time_split(sh, tiles, L.KT, cus);
-            else if (mode == 0 && ws.Part != nullptr && split_pays(sh, tiles, L.KT, cus)) t = time_split(sh, tiles, L.KT, cus);
+            double t = time_whole(sh, tiles, KT, cus);
+            if (mode >= 2 && ws.Part != nullptr) t = time_split(sh, tiles, KT, cus);
+            else if (mode == 0 && ws.Part != nullptr && split_pays(sh, tiles, KT, cus)) t = time_split(sh, tiles, KT, cus);
             if (variant == 0 || t < best) { best = t; variant = sh.id; }
         }
     }
