@@ -287,12 +287,15 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
             const int row = item / kp4, r4 = item - row * kp4;
             f32x4 sum;
             if constexpr (BIGK) {
-                // loaded here, one item at a time (slice order as below)
-                sum = *reinterpret_cast<const f32x4*>(a.Tpart + 4 * item);
-                for (int sl = 1; sl < a.S; ++sl) {
-                    const f32x4 o = *reinterpret_cast<const f32x4*>(a.Tpart + (int64_t)sl * a.M * a.kp + 4 * item);
-                    sum[0] += o[0]; sum[1] += o[1]; sum[2] += o[2]; sum[3] += o[3];
-                }
+                // loaded here, one item at a time, its slices' loads in flight together (slice order as below)
+                f32x4 o[SMAX];
+#pragma unroll
+                for (int sl = 0; sl < SMAX; ++sl)
+                    o[sl] = *reinterpret_cast<const f32x4*>(a.Tpart + (int64_t)(sl < a.S ? sl : a.S - 1) * a.M * a.kp + 4 * item);
+                sum = o[0];
+#pragma unroll
+                for (int sl = 1; sl < SMAX; ++sl)
+                    if (sl < a.S) { sum[0] += o[sl][0]; sum[1] += o[sl][1]; sum[2] += o[sl][2]; sum[3] += o[sl][3]; }
             } else {
                 sum = tpart[i][0];
 #pragma unroll
@@ -430,6 +433,17 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     }
 
     // ---- rank-kp correction, part 2: the arithmetic ---------------------------------------------------
+    // (ranks above 64: the operands of all of this wavefront's jobs are asked for here, in the registers the weight sets
+    // have left, instead of one round trip per job)
+    constexpr int NJB = BIGK ? NJ : 1;
+    u32x4 big_cw[NJB][2];
+    uint32_t big_eb[NJB][2];
+    if constexpr (BIGK) {
+#pragma unroll
+        for (int q = 0; q < NJ; ++q)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) load_tail(wk + NWK * q, j, big_cw[q][j], big_eb[q][j]);
+    }
 #pragma unroll
     for (int q = 0; q < NJ; ++q) {
         const int job = wk + NWK * q;
@@ -451,10 +465,7 @@ __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
             }
             Frag bf[2];
             if constexpr (BIGK) {
-                u32x4 cw;
-                uint32_t eb;
-                load_tail(job, j, cw, eb);
-                int8x16_to_frags(cw, h_scale(eb), bf[0], bf[1]);
+                int8x16_to_frags(big_cw[q][j], h_scale(big_eb[q][j]), bf[0], bf[1]);
             } else {
                 int8x16_to_frags(tail_cw[q][j], h_scale(tail_eb[q][j]), bf[0], bf[1]);
             }
