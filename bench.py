@@ -124,6 +124,7 @@ def probes():
         L.lqer_probe_stream_read.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         L.lqer_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
         L.lqer_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.lqer_probe_mfma_valu.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         _probes = L
     return _probes
 
@@ -178,6 +179,17 @@ def measure_peaks():
         ms = min(_event_ms(f, 3) for _ in range(3))
         out[key] = wgs * 4 * iters * chains * 32768.0 / (ms * 1e-3) / 1e12
     out["mfma_bf16_tflops"] = max(out["mfma_bf16_tflops_1wave_per_simd"], out["mfma_bf16_tflops_2waves_per_simd"])
+    # the matrix pipe beside vector work: two wavefronts per SIMD, n independent fp32 instructions behind every MFMA
+    # (the tiled MXINT kernel has 2.7 per MFMA, the INT kernel 12: 8 of them the per-group conversion and scaling)
+    beside = {}
+    for int8, name, per in ((0, "bf16", 32768.0), (1, "int8", 65536.0)):
+        for nv in (0, 4, 8, 12):
+            iters, wgs = 4096, cus * 2
+            f = lambda i: chk(P.lqer_probe_mfma_valu(wgs, iters, nv, int8, sink.data_ptr(), cur()))
+            f(0)
+            ms = min(_event_ms(f, 3) for _ in range(3))
+            beside[f"{name}_{nv}_valu"] = wgs * 4 * iters * 4 * per / (ms * 1e-3) / 1e12
+    out["mfma_beside_valu_tera_per_s"] = beside
     out["source"] = "csrc/bench_probes.hip, timed by events in this run"
     return out
 
@@ -526,6 +538,11 @@ def run_int_variant(rng, peaks):
                 ach = ops / (ms * 1e-3) / 1e12
                 rec["roofline"] = {"bound": "mfma", "kernel": "whole step (quant_token_kernel + 2 x int_gemm_kernel)", "achieved": ach,
                                    "peak": MFMA_INT8_PEAK_TOPS, "unit": "TOP/s", "frac": ach / MFMA_INT8_PEAK_TOPS, "traffic": None}
+                # what the int8 pipe delivers with this kernel's 12 vector instructions per MFMA beside it (probe)
+                lim = (peaks or {}).get("mfma_beside_valu_tera_per_s", {}).get("int8_12_valu")
+                if lim:
+                    rec["roofline"]["peak_with_12_valu_per_mfma"] = lim
+                    rec["roofline"]["frac_with_12_valu_per_mfma"] = ach / lim
             out.append(rec)
             del X, Y
         for l in layers:

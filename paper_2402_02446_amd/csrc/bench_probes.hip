@@ -6,6 +6,9 @@
 //   lqer_probe_copy         plain copy, 16 bytes per lane (read + write traffic)
 //   lqer_probe_mfma         register-resident loop of 32x32x16 bf16 MFMAs, `chains` independent accumulators
 //                           per wavefront, `waves` wavefronts per SIMD on every compute unit
+//   lqer_probe_mfma_valu    the same loop (bf16 32x32x16 or int8 32x32x32) with a fixed number of independent fp32
+//                           vector instructions behind every MFMA: what the matrix pipe still delivers when a kernel
+//                           has that much vector work per MFMA (both kinds of instruction issue through one port)
 // All launches are asynchronous on the given stream; the caller times them with events.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -65,6 +68,69 @@ __global__ __launch_bounds__(256) void mfma_kernel(int iters, float* sink) {
     if (s == -1.0f && sink != nullptr) sink[0] = s;          // sums of non-negative products: never true
 }
 
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+
+// Four independent accumulators; NV fused multiply-adds on registers of their own behind every MFMA.  The
+// instructions are written as asm statements so that they stay in this order.
+template <int NV, bool I8>
+__global__ __launch_bounds__(256) void mfma_valu_kernel(int iters, float* sink, float y, float z) {
+    constexpr int CH = 4;
+    f32x16 acc[CH];
+    i32x16 iacc[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            acc[c][r] = 0.f;
+            iacc[c][r] = 0;
+        }
+    bf16x8 a, b;
+    i32x4 ia, ib;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (__bf16)(float)((threadIdx.x + e) & 3);
+        b[e] = (__bf16)(float)((threadIdx.x * 3 + e) & 1);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        ia[e] = (int)threadIdx.x + e;
+        ib[e] = (int)threadIdx.x * 3 + e;
+    }
+    float v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = (float)(threadIdx.x + j);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            if constexpr (I8) asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+v"(iacc[c]) : "v"(ia), "v"(ib));
+            else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc[c]) : "v"(a), "v"(b));
+#pragma unroll
+            for (int j = 0; j < NV; ++j) asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(v[(c * NV + j) & 15]) : "v"(y), "v"(z));
+        }
+    }
+    asm volatile("s_nop 15\n s_nop 15");           // the last MFMAs' results are read below: past their latency
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) s += acc[c][0] + acc[c][15] + (float)iacc[c][3];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) s += v[j];
+    if (s == -1.2345f && sink != nullptr) sink[0] = s;    // keeps the arithmetic alive; not a value these sums take
+}
+
+template <bool I8>
+int launch_mfma_valu(int workgroups, int iters, int valu, float* sink, hipStream_t s) {
+    const dim3 grid((unsigned)workgroups), block(256);
+    switch (valu) {
+        case 0: hipLaunchKernelGGL((mfma_valu_kernel<0, I8>), grid, block, 0, s, iters, sink, 1.0f, 0.0f); break;
+        case 4: hipLaunchKernelGGL((mfma_valu_kernel<4, I8>), grid, block, 0, s, iters, sink, 1.0f, 0.0f); break;
+        case 8: hipLaunchKernelGGL((mfma_valu_kernel<8, I8>), grid, block, 0, s, iters, sink, 1.0f, 0.0f); break;
+        case 12: hipLaunchKernelGGL((mfma_valu_kernel<12, I8>), grid, block, 0, s, iters, sink, 1.0f, 0.0f); break;
+        default: return (int)hipErrorInvalidValue;
+    }
+    return (int)hipGetLastError();
+}
+
 }  // namespace
 
 extern "C" {
@@ -99,6 +165,14 @@ int lqer_probe_mfma(int workgroups, int iters, int chains, void* sink_dev, void*
     else if (chains == 8) hipLaunchKernelGGL(mfma_kernel<8>, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, (float*)sink_dev);
     else return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();
+}
+
+// Launches workgroups x 4 wavefronts, each doing iters x 4 MFMAs with `valu` (0, 4, 8 or 12) fp32 vector instructions
+// behind each one.  int8 = 0: bf16 32x32x16 (32768 flops per MFMA); 1: int8 32x32x32 (65536 operations).
+int lqer_probe_mfma_valu(int workgroups, int iters, int valu, int int8, void* sink_dev, void* hip_stream) {
+    if (workgroups <= 0 || iters <= 0) return (int)hipErrorInvalidValue;
+    return int8 ? launch_mfma_valu<true>(workgroups, iters, valu, (float*)sink_dev, (hipStream_t)hip_stream)
+                : launch_mfma_valu<false>(workgroups, iters, valu, (float*)sink_dev, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

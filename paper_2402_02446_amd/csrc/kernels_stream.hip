@@ -59,7 +59,7 @@ struct StreamArgs {
 //      arrives first, so the result is the same bits on every run.
 // WB: mantissa bits of W_q, 4 or 2 (half the code bytes per record: two 1 KiB loads per record instead of four).
 // BIGK: padded ranks above 64 (up to 256): the correction's operands are then not fetched ahead of the main
-//      product - there are up to four times as many - but where they are used.
+//      product - there are up to four times as many - but behind it, all of a wavefront's together.
 template <int G, int NWC, int NWK, int DT, int LR, bool ONE, int KSP, int WB, bool BIGK>
 __global__ __launch_bounds__(64 * NWC * NWK) void stream_kernel(StreamArgs a) {
     static_assert(WB == 4 || WB == 2, "weight mantissas of 4 or 2 bits");
