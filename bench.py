@@ -124,6 +124,7 @@ def probes():
         L.lqer_probe_stream_read.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         L.lqer_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
         L.lqer_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.lqer_probe_mfma_random.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.lqer_probe_mfma_valu.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         _probes = L
     return _probes
@@ -179,6 +180,12 @@ def measure_peaks():
         ms = min(_event_ms(f, 3) for _ in range(3))
         out[key] = wgs * 4 * iters * chains * 32768.0 / (ms * 1e-3) / 1e12
     out["mfma_bf16_tflops"] = max(out["mfma_bf16_tflops_1wave_per_simd"], out["mfma_bf16_tflops_2waves_per_simd"])
+    # the same loop on operands with random signs and significands: the data then toggles as in a real product, and the
+    # chip's power management answers with a lower clock
+    f = lambda i: chk(P.lqer_probe_mfma_random(cus * 2, 4096, 4, sink.data_ptr(), cur()))
+    f(0)
+    ms = min(_event_ms(f, 3) for _ in range(3))
+    out["mfma_bf16_tflops_random_operands"] = cus * 2 * 4 * 4096 * 4 * 32768.0 / (ms * 1e-3) / 1e12
     # the matrix pipe beside vector work: two wavefronts per SIMD, n independent fp32 instructions behind every MFMA
     # (the tiled MXINT kernel has 2.7 per MFMA, the INT kernel 12: 8 of them the per-group conversion and scaling)
     beside = {}
@@ -209,6 +216,11 @@ def roofline(bound, kernel, work, ms_kernel, ms_step, work_step, peaks, traffic=
     if meas:
         r["peak_measured"] = meas
         r["frac_measured"] = ach / meas
+    rnd = peaks.get("mfma_bf16_tflops_random_operands") if (peaks and bound != "hbm") else None
+    if rnd:
+        # the MFMA loop alone on operands whose bits toggle like real data (the chip then clocks lower)
+        r["peak_measured_random_operands"] = rnd
+        r["frac_measured_random_operands"] = ach / rnd
     if step is not None:
         r["achieved_step"] = step
         r["frac_step"] = step / peak

@@ -6,6 +6,7 @@
 //   lqer_probe_copy         plain copy, 16 bytes per lane (read + write traffic)
 //   lqer_probe_mfma         register-resident loop of 32x32x16 bf16 MFMAs, `chains` independent accumulators
 //                           per wavefront, `waves` wavefronts per SIMD on every compute unit
+//   lqer_probe_mfma_random  the same with operands of random signs and significands
 //   lqer_probe_mfma_valu    the same loop (bf16 32x32x16 or int8 32x32x32) with a fixed number of independent fp32
 //                           vector instructions behind every MFMA: what the matrix pipe still delivers when a kernel
 //                           has that much vector work per MFMA (both kinds of instruction issue through one port)
@@ -45,27 +46,40 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
-template <int CHAINS>
+// RANDOM: operands with random signs and significands (values in +-[1, 2)), four different pairs used in turn, instead
+// of one pair of small non-negative integers: the same instruction stream with the data toggling as it does in a real
+// product, which is what the chip's power management reacts to.
+template <int CHAINS, bool RANDOM>
 __global__ __launch_bounds__(256) void mfma_kernel(int iters, float* sink) {
     f32x16 acc[CHAINS];
 #pragma unroll
     for (int c = 0; c < CHAINS; ++c)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
-    bf16x8 a, b;
+    union Op { bf16x8 v; uint16_t h[8]; };
+    Op a[4], b[4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        a[e] = (__bf16)(float)((threadIdx.x + e) & 3);
-        b[e] = (__bf16)(float)((threadIdx.x * 3 + e) & 1);
-    }
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if (RANDOM) {
+                uint32_t x = (threadIdx.x * 8u + e) * 2654435761u + p * 40503u + blockIdx.x * 2246822519u;
+                x ^= x >> 15; x *= 2246822519u; x ^= x >> 13;
+                a[p].h[e] = (uint16_t)(0x3F80u | (x & 0x807Fu));
+                b[p].h[e] = (uint16_t)(0x3F80u | ((x >> 16) & 0x807Fu));
+            } else {
+                a[p].v[e] = (__bf16)(float)((threadIdx.x + e) & 3);
+                b[p].v[e] = (__bf16)(float)((threadIdx.x * 3 + e) & 1);
+            }
+        }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int c = 0; c < CHAINS; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
+        for (int c = 0; c < CHAINS; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c & 3].v, b[(c + (c >> 2)) & 3].v, acc[c], 0, 0, 0);
     }
     float s = 0.f;
 #pragma unroll
     for (int c = 0; c < CHAINS; ++c) s += acc[c][0] + acc[c][15];
-    if (s == -1.0f && sink != nullptr) sink[0] = s;          // sums of non-negative products: never true
+    if (s == -1.2345f && sink != nullptr) sink[0] = s;       // keeps the arithmetic alive; not a value these sums take
 }
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -161,8 +175,17 @@ int lqer_probe_copy(const void* src_dev, void* dst_dev, int64_t bytes, int workg
 // chains: 4 or 8.  flops of the launch = workgroups * 4 * iters * chains * 32768.
 int lqer_probe_mfma(int workgroups, int iters, int chains, void* sink_dev, void* hip_stream) {
     if (workgroups <= 0 || iters <= 0) return (int)hipErrorInvalidValue;
-    if (chains == 4) hipLaunchKernelGGL(mfma_kernel<4>, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, (float*)sink_dev);
-    else if (chains == 8) hipLaunchKernelGGL(mfma_kernel<8>, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, (float*)sink_dev);
+    if (chains == 4) hipLaunchKernelGGL((mfma_kernel<4, false>), dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, (float*)sink_dev);
+    else if (chains == 8) hipLaunchKernelGGL((mfma_kernel<8, false>), dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, (float*)sink_dev);
+    else return (int)hipErrorInvalidValue;
+    return (int)hipGetLastError();
+}
+
+// The same with operands whose bits differ from MFMA to MFMA and from lane to lane (see mfma_kernel).
+int lqer_probe_mfma_random(int workgroups, int iters, int chains, void* sink_dev, void* hip_stream) {
+    if (workgroups <= 0 || iters <= 0) return (int)hipErrorInvalidValue;
+    if (chains == 4) hipLaunchKernelGGL((mfma_kernel<4, true>), dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, (float*)sink_dev);
+    else if (chains == 8) hipLaunchKernelGGL((mfma_kernel<8, true>), dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, (float*)sink_dev);
     else return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();
 }
