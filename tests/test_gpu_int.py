@@ -1,7 +1,7 @@
 """GPU parity of the scaled-integer variant (Table 2 "L2QER-INT": INT4 g128 weights with FP16 scales, INT8 g128 factors,
 INT8 per-token activations) against the fp64 oracle: the per-token quantizer bit for bit, canonical arrays round-trip,
 the forward pass on ragged token and column counts and ranks from none to 128, the offline step, the static scratch,
-and the LLaMA-7B-shaped layer at full size."""
+the LLaMA-7B-shaped layers at full size, and the 4096 x 4096 layer at 65536 tokens."""
 import numpy as np
 import pytest
 
@@ -211,4 +211,42 @@ def test_7b_shaped_layers_every_tile(K, N, k, M):
     Ys = Y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
     err, ratio = _check(Ys, X[rows], layer, cols)
     print(f"{K}x{N} M={M}: rel. Frobenius error {err:.3g}, largest |error| / bound {ratio:.3g}")
+    h.free()
+
+
+def test_int_layer_at_65536_tokens_every_tile():
+    # the 4096 x 4096 layer at the decoder block's 65536 tokens, the configuration the benchmark times for this variant:
+    # one row of every band of 32 token rows against one column of every group of 32 columns (every output tile, every
+    # wavefront's part of it and every MFMA tile holds a compared element), norm and elementwise; the per-token
+    # quantizer's codes and scales on the same rows, bit for bit; everything else finite.
+    import torch
+    from paper_2402_02446_amd import binding
+    K = N = 4096
+    k, M = 32, 65536
+    layer, ch = _standin_layer(K, N, k, seed=5)
+    h = _upload(layer)
+    rng = np.random.default_rng(9)
+    X = torch.empty((M, K), dtype=torch.float32, device="cuda")
+    rows, cols = tile_cover_samples(rng, M, N)
+    rows = np.unique(np.r_[rows, 127, 128, 255, 256, 32767, 32768, M - 129, M - 128])
+    keep = {}
+    for r0 in range(0, M, 8192):                             # generated in slabs: the host never holds all of X
+        slab = synth.gen_activations(np.random.default_rng(r0 + 3), 8192, K, ch, 50.0)
+        X[r0:r0 + 8192] = torch.from_numpy(slab).cuda()
+        for r in rows[(rows >= r0) & (rows < r0 + 8192)]:
+            keep[int(r)] = slab[r - r0].copy()
+    Xs = np.stack([keep[int(r)] for r in rows])
+    Y = binding.lqer_linear_forward(h, X)
+    torch.cuda.synchronize()
+    idx = torch.from_numpy(rows).cuda()
+    Ys = Y[idx][:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    assert bool(torch.isfinite(Y).all())
+    err, ratio = _check(Ys, Xs, layer, cols)
+    print(f"INT {K}x{N} at {M} tokens: {len(rows)} x {len(cols)} samples, rel. Frobenius error {err:.3g}, largest |error| / bound {ratio:.3g}")
+    del Y
+    codes, scales = binding.lqer_quantize_int8_token(X)
+    torch.cuda.synchronize()
+    oc, os_ = intq.quantize_tokens(Xs)
+    assert np.array_equal(codes[idx].cpu().numpy(), oc)
+    assert np.array_equal(scales[idx].cpu().numpy().view(np.uint16), os_.view(np.uint16))
     h.free()
