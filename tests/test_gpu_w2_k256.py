@@ -166,19 +166,20 @@ def test_offline_step_with_two_bit_weights(K, N, k, exp_bits):
     h.free()
 
 
+@pytest.mark.parametrize("N", [4096, 11008])
 @pytest.mark.parametrize("M", [16, 2048])
-def test_w2a8_rank_256_on_the_7b_shaped_layer(M):
-    # Sec. 4.1's W2A8 configuration (k = 256) on the LLaMA-7B-shaped 4096 x 4096 layer, decode and prefill, in the
-    # launch configuration the benchmark times: every token row (M = 16) or one of every band of 32 against one
-    # column of every group of 32
-    layer, ch = oracle_layer_big(4096, 4096, 256, seed=40, w_bits=2)
+def test_w2a8_rank_256_on_the_7b_shaped_layers(M, N):
+    # Sec. 4.1's W2A8 configuration (k = 256) on the LLaMA-7B-shaped 4096 x 4096 and 4096 x 11008 layers, decode and
+    # prefill, in the launch configurations the benchmark times: every token row (M = 16) or one of every band of 32
+    # against one column of every group of 32
+    layer, ch = oracle_layer_big(4096, N, 256, seed=40, w_bits=2)
     h = upload(layer)
     X = synth.gen_activations(np.random.default_rng(M), M, 4096, ch, 50.0)
     Y = _fwd(h, X)
     assert np.all(np.isfinite(Y))
-    rows, cols = tile_cover_samples(np.random.default_rng(1), M, 4096)
+    rows, cols = tile_cover_samples(np.random.default_rng(1), M, N)
     if M <= 16:
         rows = np.arange(M)
     err, ratio = assert_forward_matches(Y[np.ix_(rows, cols)], X[rows], layer, cols)
-    print(f"M={M}: rel. Frobenius error {err:.3g}, largest |error| / bound {ratio:.3g}")
+    print(f"4096x{N} M={M}: rel. Frobenius error {err:.3g}, largest |error| / bound {ratio:.3g}")
     h.free()
