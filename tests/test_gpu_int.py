@@ -130,6 +130,9 @@ def test_round_trip_errors_and_other_entry_points():
     with pytest.raises(binding.LqerError) as e:
         binding.lqer_linear_forward(h, X, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
     assert e.value.status == 5
+    with pytest.raises(binding.LqerError) as e:           # beyond the static scratch (32 MiB): refused, nothing launched
+        binding.lqer_linear_forward_static(h, torch.zeros((140000, 256), dtype=torch.float32, device="cuda"))
+    assert e.value.status == 5
     assert binding.lqer_linear_forward(h, X[:0]).shape == (0, 100)
     h.free()
     # excluded values and shapes
