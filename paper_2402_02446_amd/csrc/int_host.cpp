@@ -81,7 +81,7 @@ static inline int perm_pos(int e) { return (e & ~31) + ((e & 1) << 4) + ((e & 31
 
 // K planes of the projection: it has few output columns, so with few token tiles its K groups are spread over
 // workgroups (each keeps at least two groups: a workgroup's groups are a chain of dependent memory round trips, which
-// is what a few-token call waits for); the main kernel adds the planes' partial T in plane order.
+// is what a few-token call waits for); a small kernel then adds the planes' partial T in plane order.
 static int projection_planes(const Layer& L, int64_t M) {
     const int64_t tiles = (M + 127) / 128, G = L.K / 128;
     int64_t s = 1;
